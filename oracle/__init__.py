@@ -1,0 +1,155 @@
+"""ctypes front end of the plain-C APMSqueeze oracle (test infrastructure only).
+
+The arithmetic lives in ``apms_oracle.c``; this module only compiles it with
+gcc, loads it and marshals numpy arrays.  Nothing here imports or is imported
+by the HIP library or its Python binding.  Only tests, the smoke check and the
+benchmark's CPU-baseline leg may use it.
+
+Compression stage: Algorithm 1 lines 3-12 / supplement "Proof to the Updating
+Form" steps 1-3; 1-bit operator: Section 5.1; warm-up: Section 3.2.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+ONEBIT = 0
+IDENTITY = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "apms_oracle.c")
+_LIB = os.path.join(_HERE, "libapms_oracle.so")
+_lib = None
+
+# No FMA contraction, no fast-math: every fp32 operation rounds once, in order.
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+          "-Wall", "-Wextra"]
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc; returns the path of the shared object."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", *CFLAGS, "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        i32, i64, f32, ptr = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_void_p
+        lib.apms_oracle_compress.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32]
+        lib.apms_oracle_server_reduce.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, ptr]
+        lib.apms_oracle_apply.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32, f32]
+        lib.apms_oracle_warmup_step.argtypes = [i64, i32, ptr, ptr, ptr, ptr, f32, f32, f32, f32, i64]
+        lib.apms_oracle_freeze.argtypes = [i64, i32, ptr, ptr, ptr, ptr]
+        for fn in (lib.apms_oracle_compress, lib.apms_oracle_server_reduce, lib.apms_oracle_apply,
+                   lib.apms_oracle_warmup_step, lib.apms_oracle_freeze):
+            fn.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _p(a, dtype, size):
+    """Pointer to a C-contiguous numpy array of the given dtype and element count (None -> NULL)."""
+    if a is None:
+        return None
+    if not (isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"]):
+        raise TypeError("expected a C-contiguous %s array" % np.dtype(dtype).name)
+    if a.size != size:
+        raise ValueError("expected %d elements, got %d" % (size, a.size))
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _check_shape(d, n, L):
+    if n < 1 or d < 0 or L < 32 or L % 32 or d % L:
+        raise ValueError("need n >= 1, L a positive multiple of 32, d a multiple of L")
+
+
+def compress(d, n, L, m, g, werr, packed, scales, beta, compressor=ONEBIT, dense=None):
+    """Worker step for all n workers and all chunks; werr, packed, scales (, dense) written in place."""
+    _check_shape(d, n, L)
+    C = d // L
+    f, u = np.float32, np.uint32
+    rc = _load().apms_oracle_compress(
+        compressor, d, n, L, _p(m, f, n * d), _p(g, f, n * d), _p(werr, f, n * d),
+        _p(packed, u, n * d // 32), _p(scales, f, n * C), _p(dense, f, n * d), np.float32(beta))
+    if rc:
+        raise MemoryError("oracle compress")
+
+
+def server_reduce(d, n, L, packed, scales, serr, spacked, sscales, compressor=ONEBIT,
+                  dense=None, sdense=None):
+    """Server step for all chunks; serr, spacked, sscales (, sdense) written in place."""
+    _check_shape(d, n, L)
+    C = d // L
+    f, u = np.float32, np.uint32
+    rc = _load().apms_oracle_server_reduce(
+        compressor, d, n, L, _p(packed, u, n * d // 32), _p(scales, f, n * C), _p(dense, f, n * d),
+        _p(serr, f, d), _p(spacked, u, d // 32), _p(sscales, f, C), _p(sdense, f, d))
+    if rc:
+        raise MemoryError("oracle server_reduce")
+
+
+def apply(d, n, L, spacked, sscales, v, x, m, lr, eps, compressor=ONEBIT, sdense=None):
+    """Gather + frozen-variance model update; x and all n slices of m written in place."""
+    _check_shape(d, n, L)
+    C = d // L
+    f, u = np.float32, np.uint32
+    _load().apms_oracle_apply(
+        compressor, d, n, L, _p(spacked, u, d // 32), _p(sscales, f, C), _p(sdense, f, d),
+        _p(v, f, d), _p(x, f, d), _p(m, f, n * d), np.float32(lr), np.float32(eps))
+
+
+def warmup_step(d, n, x, m, v, g, lr, beta1, beta2, eps, t):
+    """One Adam warm-up step on the average of the n gradients; x, m, v ([d]) in place; t is 1-based."""
+    if n < 1 or d < 0 or t < 1:
+        raise ValueError("need n >= 1, d >= 0, t >= 1")
+    f = np.float32
+    _load().apms_oracle_warmup_step(
+        d, n, _p(x, f, d), _p(m, f, d), _p(v, f, d), _p(g, f, n * d),
+        np.float32(lr), np.float32(beta1), np.float32(beta2), np.float32(eps), t)
+
+
+def freeze(d, n, m_warm, m, werr, serr):
+    """Warm-up -> compression stage hand-over: replicate m, zero both errors."""
+    f = np.float32
+    _load().apms_oracle_freeze(d, n, _p(m_warm, f, d), _p(m, f, n * d), _p(werr, f, n * d), _p(serr, f, d))
+
+
+class State:
+    """Host-side state of the compression stage for n simulated workers (numpy arrays)."""
+
+    def __init__(self, d, n, L, x, m, v, werr=None, serr=None):
+        _check_shape(d, n, L)
+        self.d, self.n, self.L, self.C = d, n, L, d // L
+        f = np.float32
+        self.x = np.ascontiguousarray(x, dtype=f).copy()
+        self.m = np.ascontiguousarray(m, dtype=f).reshape(n, d).copy()
+        self.v = np.ascontiguousarray(v, dtype=f).copy()
+        self.werr = np.zeros((n, d), f) if werr is None else np.ascontiguousarray(werr, dtype=f).reshape(n, d).copy()
+        self.serr = np.zeros(d, f) if serr is None else np.ascontiguousarray(serr, dtype=f).copy()
+        self.packed = np.zeros((n, d // 32), np.uint32)
+        self.scales = np.zeros((n, self.C), f)
+        self.spacked = np.zeros(d // 32, np.uint32)
+        self.sscales = np.zeros(self.C, f)
+        self.dense = None
+        self.sdense = None
+
+    def step(self, g, beta, lr, eps, compressor=ONEBIT):
+        """One full compressed step (compress -> server_reduce -> apply) on gradients g [n][d]."""
+        d, n, L = self.d, self.n, self.L
+        g = np.ascontiguousarray(g, dtype=np.float32).reshape(n, d)
+        if compressor == IDENTITY and self.dense is None:
+            self.dense = np.zeros((n, d), np.float32)
+            self.sdense = np.zeros(d, np.float32)
+        compress(d, n, L, self.m, g, self.werr, self.packed, self.scales, beta, compressor, self.dense)
+        server_reduce(d, n, L, self.packed, self.scales, self.serr, self.spacked, self.sscales,
+                      compressor, self.dense, self.sdense)
+        apply(d, n, L, self.spacked, self.sscales, self.v, self.x, self.m, lr, eps, compressor, self.sdense)

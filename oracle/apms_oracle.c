@@ -1,0 +1,318 @@
+/*
+ * APMSqueeze reference oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, single-threaded CPU statement of what one step of the
+ * compression stage of APMSqueeze computes (Algorithm 1, lines 3-12, in the
+ * parameter-server form of the supplement, "Proof to the Updating Form",
+ * steps 1-3, applied to every chunk independently), of the 1-bit
+ * compression operator (Section 5.1, "Compression Method"), and of one step
+ * of the Adam warm-up (Section 3.2, "Original Adam").
+ *
+ * Only tests, the smoke check and the benchmark's CPU-baseline leg may call
+ * this file.  It shares no code, header, table or helper with the HIP
+ * library and includes none of its headers.
+ *
+ * Arithmetic contract (the paper is silent on all of it; these are the
+ * readings this build fixes):
+ *   - every elementwise operation is one IEEE-754 binary32 operation, rounded
+ *     to nearest-even, in the order written below; no fused multiply-add
+ *     (compile with -ffp-contract=off, no -ffast-math); denormals are kept;
+ *   - the squared l2 norm behind a scale is the exact sum of the exact
+ *     squares: each square is formed in a wider type where it is exact and
+ *     the sum is carried in `long double` (64-bit significand on x86-64), so
+ *     its error is far below one binary64 ulp for any chunk length used here;
+ *     it is rounded to binary64 once, divided by the chunk length and square
+ *     rooted in binary64, then rounded once to binary32;
+ *   - sign(0) = +1: the sign bit sent is (u >= 0), so -0.0 maps to +1;
+ *   - sign words are packed LSB-first: element j of a worker's vector is bit
+ *     (j & 31) of word (j >> 5); bit 1 means +scale, bit 0 means -scale;
+ *   - the server sums the n decoded values in worker order 0..n-1 and then
+ *     multiplies by fl(1/n).
+ *
+ * Parity status: the trajectory VALUES have no printed worked example in the
+ * paper ("parity unpinned" for those); every function here is pinned by the
+ * invariants, closed forms, special cases and brute-force checks in
+ * tests/test_oracle_pins.py.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define APMS_ORACLE_ONEBIT 0   /* sign + l2 scale, Section 5.1            */
+#define APMS_ORACLE_IDENTITY 1 /* C[u] = u: the "uncompressed" variant of  */
+                               /* Section 5.3 (freeze v, no compression)   */
+
+/* ------------------------------------------------------------------------ */
+/* The compression operator C[.] on one chunk, and its decoder.             */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Section 5.1: keep the sign of every element and one scaling factor equal to
+ * (magnitude of the compensated vector) / (magnitude of the quantized one).
+ * With the l2 norm of the paper's notation the quantized vector (all +-1) has
+ * norm sqrt(L), so scale = ||u||_2 / sqrt(L) = sqrt(sum u^2 / L).
+ *
+ * u[0..L)        chunk to compress
+ * words[0..L/32) packed signs (written only for ONEBIT)
+ * *scale         scaling factor (ONEBIT), 1.0f for IDENTITY
+ * c[0..L)        decoded value C[u], what a receiver reconstructs
+ */
+static void compress_chunk(int compressor, const float *u, int64_t L,
+                           uint32_t *words, float *scale, float *c)
+{
+    if (compressor == APMS_ORACLE_IDENTITY) {
+        for (int64_t j = 0; j < L; ++j)
+            c[j] = u[j];
+        *scale = 1.0f;
+        return;
+    }
+    long double S = 0.0L;
+    for (int64_t j = 0; j < L; ++j)
+        S += (long double)u[j] * (long double)u[j];
+    double mean_sq = (double)S / (double)L;
+    float s = (float)sqrt(mean_sq);
+    *scale = s;
+    for (int64_t w = 0; w < L / 32; ++w)
+        words[w] = 0u;
+    for (int64_t j = 0; j < L; ++j) {
+        int positive = (u[j] >= 0.0f);
+        if (positive)
+            words[j >> 5] |= (uint32_t)1u << (j & 31);
+        c[j] = positive ? s : -s;
+    }
+}
+
+/* Decoded value of element j of a chunk, from its wire form. */
+static float decode_elem(int compressor, const uint32_t *words, float scale,
+                         const float *dense, int64_t j)
+{
+    if (compressor == APMS_ORACLE_IDENTITY)
+        return dense[j];
+    return ((words[j >> 5] >> (j & 31)) & 1u) ? scale : -scale;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Worker side: supplement step 1 (Algorithm 1, lines 6-7).                 */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * For every worker i and chunk k:
+ *     m_i   = beta * m + (1 - beta) * g_i          (local momentum)
+ *     u     = m_i + delta_i                        (error compensation)
+ *     send C[u];   delta_i <- u - C[u]
+ *
+ * d       vector length, a multiple of L;  L a multiple of 32
+ * m       [n][d] momentum slices (read only: the local m_i is never stored,
+ *         the gather of step 3 overwrites it)
+ * g       [n][d] local stochastic gradients
+ * werr    [n][d] worker errors delta_i, updated in place
+ * packed  [n][d/32] sign words out            (ONEBIT)
+ * scales  [n][d/L] one scale per worker chunk (ONEBIT; 1.0f for IDENTITY)
+ * dense   [n][d] decoded messages out (required for IDENTITY, where it IS the
+ *         wire form; optional, may be NULL, for ONEBIT)
+ * Returns 0, or -1 when the temporary chunk buffers cannot be allocated.
+ */
+int apms_oracle_compress(int compressor, int64_t d, int32_t n, int64_t L,
+                         const float *m, const float *g, float *werr,
+                         uint32_t *packed, float *scales, float *dense,
+                         float beta)
+{
+    if (d == 0)
+        return 0;
+    const int64_t C = d / L;
+    const float one_minus_beta = 1.0f - beta;
+    float *u = (float *)malloc((size_t)L * sizeof(float));
+    float *c = (float *)malloc((size_t)L * sizeof(float));
+    if (!u || !c) {
+        free(u);
+        free(c);
+        return -1;
+    }
+    for (int32_t i = 0; i < n; ++i) {
+        for (int64_t k = 0; k < C; ++k) {
+            const int64_t base = (int64_t)i * d + k * L;
+            for (int64_t j = 0; j < L; ++j) {
+                float bm = beta * m[base + j];
+                float bg = one_minus_beta * g[base + j];
+                float mi = bm + bg;
+                u[j] = mi + werr[base + j];
+            }
+            uint32_t *words = packed ? packed + base / 32 : NULL;
+            compress_chunk(compressor, u, L, words, &scales[(int64_t)i * C + k], c);
+            for (int64_t j = 0; j < L; ++j) {
+                werr[base + j] = u[j] - c[j];
+                if (dense)
+                    dense[base + j] = c[j];
+            }
+        }
+    }
+    free(u);
+    free(c);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Server side: supplement step 2 (Algorithm 1, line 9).                    */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * For every chunk k (served by worker k in the paper; here just chunk k):
+ *     a     = (1/n) * sum_{i=0}^{n-1} C[u_i]        (average of the n messages)
+ *     ubar  = a + deltabar
+ *     send C[ubar];   deltabar <- ubar - C[ubar]
+ *
+ * packed, scales, dense   the n workers' messages as written by
+ *                         apms_oracle_compress
+ * serr     [d] server error deltabar, updated in place
+ * spacked  [d/32] server sign words out (ONEBIT)
+ * sscales  [d/L]  server scales out     (ONEBIT; 1.0f for IDENTITY)
+ * sdense   [d]    decoded server message out (required for IDENTITY)
+ */
+int apms_oracle_server_reduce(int compressor, int64_t d, int32_t n, int64_t L,
+                              const uint32_t *packed, const float *scales,
+                              const float *dense, float *serr,
+                              uint32_t *spacked, float *sscales, float *sdense)
+{
+    if (d == 0)
+        return 0;
+    const int64_t C = d / L;
+    const float inv_n = 1.0f / (float)n;
+    float *ubar = (float *)malloc((size_t)L * sizeof(float));
+    float *c = (float *)malloc((size_t)L * sizeof(float));
+    if (!ubar || !c) {
+        free(ubar);
+        free(c);
+        return -1;
+    }
+    for (int64_t k = 0; k < C; ++k) {
+        const int64_t base = k * L;
+        for (int64_t j = 0; j < L; ++j) {
+            float acc = 0.0f;
+            for (int32_t i = 0; i < n; ++i) {
+                const int64_t wbase = (int64_t)i * d + base;
+                acc = acc + decode_elem(compressor,
+                                        packed ? packed + wbase / 32 : NULL,
+                                        scales[(int64_t)i * C + k],
+                                        dense ? dense + wbase : NULL, j);
+            }
+            float avg = acc * inv_n;
+            ubar[j] = avg + serr[base + j];
+        }
+        compress_chunk(compressor, ubar, L, spacked ? spacked + base / 32 : NULL,
+                       &sscales[k], c);
+        for (int64_t j = 0; j < L; ++j) {
+            serr[base + j] = ubar[j] - c[j];
+            if (sdense)
+                sdense[base + j] = c[j];
+        }
+    }
+    free(ubar);
+    free(c);
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Gather + model update: supplement step 3 (Algorithm 1, lines 10-11).     */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * Every worker replaces its momentum by the server's decoded message and
+ * takes the step preconditioned by the variance frozen at the end of the
+ * warm-up:
+ *     m_i <- C[ubar]   for all i
+ *     x   <- x - lr * m / (sqrt(v) + eps)
+ * The paper's update has no eps (it divides by sqrt(v)); eps = 0 reproduces
+ * it literally, eps > 0 is the guard Adam itself carries (Section 3.2).
+ * No bias correction in this stage.
+ *
+ * v [d] frozen variance (read only);  x [d] model, in place;
+ * m [n][d] momentum slices, all n overwritten with the same values.
+ */
+int apms_oracle_apply(int compressor, int64_t d, int32_t n, int64_t L,
+                      const uint32_t *spacked, const float *sscales,
+                      const float *sdense, const float *v, float *x, float *m,
+                      float lr, float eps)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        const int64_t k = j / L;
+        const int64_t base = k * L;
+        float mj = decode_elem(compressor, spacked ? spacked + base / 32 : NULL,
+                               sscales[k], sdense ? sdense + base : NULL,
+                               j - base);
+        for (int32_t i = 0; i < n; ++i)
+            m[(int64_t)i * d + j] = mj;
+        float root = sqrtf(v[j]);
+        float denom = root + eps;
+        float ratio = mj / denom;
+        float step = lr * ratio;
+        x[j] = x[j] - step;
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Warm-up: one step of the original Adam (Section 3.2) on the average of   */
+/* the n workers' gradients (Algorithm 1, line 2).                          */
+/* ------------------------------------------------------------------------ */
+
+/*
+ *     gbar = (1/n) sum_i g_i           (full-precision average, worker order)
+ *     m <- beta1 m + (1-beta1) gbar ;  v <- beta2 v + (1-beta2) gbar^2
+ *     mhat = m / (1-beta1^t) ;  vhat = v / (1-beta2^t)
+ *     x <- x - lr * mhat / (sqrt(vhat) + eps)
+ * t is the 1-based index of this step.  The two bias-correction denominators
+ * are formed in binary64 and rounded to binary32 once.
+ * x, m, v are [d]; g is [n][d].
+ */
+int apms_oracle_warmup_step(int64_t d, int32_t n, float *x, float *m, float *v,
+                            const float *g, float lr, float beta1, float beta2,
+                            float eps, int64_t t)
+{
+    const float inv_n = 1.0f / (float)n;
+    const float omb1 = 1.0f - beta1;
+    const float omb2 = 1.0f - beta2;
+    const float bc1 = (float)(1.0 - pow((double)beta1, (double)t));
+    const float bc2 = (float)(1.0 - pow((double)beta2, (double)t));
+    for (int64_t j = 0; j < d; ++j) {
+        float acc = 0.0f;
+        for (int32_t i = 0; i < n; ++i)
+            acc = acc + g[(int64_t)i * d + j];
+        float gbar = acc * inv_n;
+        float m_new = beta1 * m[j];
+        float m_inc = omb1 * gbar;
+        m_new = m_new + m_inc;
+        float gsq = gbar * gbar;
+        float v_new = beta2 * v[j];
+        float v_inc = omb2 * gsq;
+        v_new = v_new + v_inc;
+        m[j] = m_new;
+        v[j] = v_new;
+        float mhat = m_new / bc1;
+        float vhat = v_new / bc2;
+        float root = sqrtf(vhat);
+        float denom = root + eps;
+        float ratio = mhat / denom;
+        float step = lr * ratio;
+        x[j] = x[j] - step;
+    }
+    return 0;
+}
+
+/*
+ * Hand-over from the warm-up to the compression stage (Algorithm 1, line 1
+ * initialisation of the errors, and line 3): the warm-up momentum becomes
+ * every worker's momentum, both error vectors start at zero, v is frozen as
+ * it stands (raw, not bias-corrected).
+ * m_warm [d] in;  m [n][d], werr [n][d], serr [d] out.
+ */
+int apms_oracle_freeze(int64_t d, int32_t n, const float *m_warm, float *m,
+                       float *werr, float *serr)
+{
+    for (int32_t i = 0; i < n; ++i) {
+        memmove(m + (int64_t)i * d, m_warm, (size_t)d * sizeof(float));
+        memset(werr + (int64_t)i * d, 0, (size_t)d * sizeof(float));
+    }
+    memset(serr, 0, (size_t)d * sizeof(float));
+    return 0;
+}

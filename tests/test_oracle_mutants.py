@@ -1,0 +1,100 @@
+"""Do the pins bite?  Plant one plausible mistake at a time in a COPY of the oracle's C source
+(a dropped term, a wrong sign or index, a swapped operand, a different norm), compile it on the CPU,
+run the pin tests against the mutant and require that at least one fails.  CPU only.
+"""
+import ctypes
+import os
+import subprocess
+
+import pytest
+
+import oracle
+import test_oracle_pins as pins
+
+MUTANTS = [
+    # (id, old text, new text)
+    ("compensate_minus", "u[j] = mi + werr[base + j];", "u[j] = mi - werr[base + j];"),
+    ("error_negated", "werr[base + j] = u[j] - c[j];", "werr[base + j] = c[j] - u[j];"),
+    ("drop_gradient_term", "float mi = bm + bg;", "float mi = bm;"),
+    ("drop_momentum_term", "float mi = bm + bg;", "float mi = bg;"),
+    ("swap_m_g", "float bm = beta * m[base + j];", "float bm = beta * g[base + j];"),
+    ("beta_on_wrong_term", "float bg = one_minus_beta * g[base + j];", "float bg = beta * g[base + j];"),
+    ("msb_first", "(uint32_t)1u << (j & 31);", "(uint32_t)1u << (31 - (j & 31));"),
+    ("zero_is_negative", "int positive = (u[j] >= 0.0f);", "int positive = (u[j] > 0.0f);"),
+    ("scale_not_rooted", "float s = (float)sqrt(mean_sq);", "float s = (float)mean_sq;"),
+    ("scale_l1", "S += (long double)u[j] * (long double)u[j];", "S += fabsl((long double)u[j]) * 1e-2L;"),
+    ("scale_sum_not_mean", "double mean_sq = (double)S / (double)L;", "double mean_sq = (double)S;"),
+    ("scale_float_accum", "long double S = 0.0L;", "float S = 0.0f;"),
+    ("decode_flipped", "& 1u) ? scale : -scale;", "& 1u) ? -scale : scale;"),
+    ("no_average", "float avg = acc * inv_n;", "float avg = acc;"),
+    ("server_error_minus", "ubar[j] = avg + serr[base + j];", "ubar[j] = avg - serr[base + j];"),
+    ("server_error_not_fed_back", "serr[base + j] = ubar[j] - c[j];", "serr[base + j] = 0.0f;"),
+    ("server_reads_worker0", "const int64_t wbase = (int64_t)i * d + base;", "const int64_t wbase = base;"),
+    ("server_scale_transposed", "scales[(int64_t)i * C + k],\n", "scales[(int64_t)k * n + i],\n"),
+    ("worker_scale_transposed", "&scales[(int64_t)i * C + k], c);", "&scales[(int64_t)k * n + i], c);"),
+    ("gather_one_worker", "for (int32_t i = 0; i < n; ++i)\n            m[(int64_t)i * d + j] = mj;",
+     "for (int32_t i = 0; i < 1; ++i)\n            m[(int64_t)i * d + j] = mj;"),
+    ("no_sqrt_of_v", "float root = sqrtf(v[j]);", "float root = v[j];"),
+    ("ascent", "x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----", "x[j] = x[j] + step;\n    }\n    return 0;\n}\n\n/* ----"),
+    ("apply_no_lr", "float step = lr * ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----",
+     "float step = ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----"),
+    ("apply_scale_of_chunk0", "sscales[k], sdense ? sdense + base : NULL,", "sscales[0], sdense ? sdense + base : NULL,"),
+    ("adam_v_uses_g_not_gsq", "float v_inc = omb2 * gsq;", "float v_inc = omb2 * gbar;"),
+    ("adam_no_bias_correction_m", "float mhat = m_new / bc1;", "float mhat = m_new;"),
+    ("adam_no_bias_correction_v", "float vhat = v_new / bc2;", "float vhat = v_new;"),
+    ("adam_t_off_by_one", "pow((double)beta2, (double)t)", "pow((double)beta2, (double)(t - 1) + 1e-9)"),
+    ("adam_eps_inside_sqrt", "float root = sqrtf(vhat);", "float root = sqrtf(vhat + 1e-6f);"),
+    ("adam_sum_not_mean", "float gbar = acc * inv_n;", "float gbar = acc;"),
+    ("freeze_keeps_errors", "memset(serr, 0, (size_t)d * sizeof(float));", ""),
+]
+
+
+def _pin_calls():
+    calls = []
+    for name in sorted(dir(pins)):
+        fn = getattr(pins, name)
+        if not (name.startswith("test_") and callable(fn)):
+            continue
+        marks = [mk for mk in getattr(fn, "pytestmark", []) if mk.name == "parametrize"]
+        if not marks:
+            calls.append((name, fn, ()))
+        else:
+            for val in marks[0].args[1]:
+                calls.append((name, fn, (val,)))
+    return calls
+
+
+def _first_failure():
+    for name, fn, args in _pin_calls():
+        try:
+            fn(*args)
+        except AssertionError:
+            return name
+        except Exception:          # a mutant may also break a pin with a ValueError etc.
+            return name
+    return None
+
+
+def test_unmutated_oracle_passes_every_pin():
+    assert _first_failure() is None
+
+
+@pytest.mark.parametrize("mutant", MUTANTS, ids=lambda mt: mt[0])
+def test_pins_catch_planted_mistake(mutant, tmp_path, monkeypatch):
+    mid, old, new = mutant
+    src = open(os.path.join(os.path.dirname(oracle.__file__), "apms_oracle.c")).read()
+    assert src.count(old) == 1, "mutation site for %s must be unique (found %d)" % (mid, src.count(old))
+    c_path = tmp_path / "mutant.c"
+    so_path = tmp_path / "mutant.so"
+    c_path.write_text(src.replace(old, new))
+    flags = [f for f in oracle.CFLAGS if f not in ("-Wall", "-Wextra")]
+    subprocess.check_call(["gcc", *flags, "-w", "-o", str(so_path), str(c_path), "-lm"])
+    good = oracle._load()
+    bad = ctypes.CDLL(str(so_path))
+    for fname in ("apms_oracle_compress", "apms_oracle_server_reduce", "apms_oracle_apply",
+                  "apms_oracle_warmup_step", "apms_oracle_freeze"):
+        getattr(bad, fname).argtypes = getattr(good, fname).argtypes
+        getattr(bad, fname).restype = getattr(good, fname).restype
+    monkeypatch.setattr(oracle, "_lib", bad)
+    caught_by = _first_failure()
+    assert caught_by is not None, "no pin notices mutant '%s'" % mid
