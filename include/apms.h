@@ -1,0 +1,206 @@
+/*
+ * apms.h -- C ABI of libapms: the per-step data-parallel hot path of the
+ * compression stage of APMSqueeze (error-compensated 1-bit compressed
+ * momentum SGD with the Adam variance frozen after a warm-up) for one
+ * AMD MI355X (gfx950), n workers simulated as n state slices in HBM.
+ *
+ * Notation follows the paper (Algorithm 1; Section 3.3; supplement "Proof to
+ * the Updating Form"): x model, m momentum, v variance, g^(i) worker i's
+ * stochastic gradient, delta^(i) worker i's compression error, deltabar the
+ * server's compression error, C[.] the compression operator (here the 1-bit
+ * operator of Section 5.1: signs + one l2 scale per chunk).
+ *
+ * Conventions for every entry point
+ *   - Every array argument is a DEVICE pointer owned by the caller, 16-byte
+ *     aligned, on the device the context was created for.  The library never
+ *     allocates, frees or keeps them (it remembers the ADDRESS of an error
+ *     buffer left in deferred form, see apms_set_error_mode).  Distinct array
+ *     arguments of one call must not overlap.
+ *   - "[n][d]" is worker-major: worker i's slice starts at element i*d.
+ *     d is the (padded) vector length, a multiple of chunk_elems; chunk_elems
+ *     is a multiple of 32; C = d / chunk_elems chunks; chunk k is elements
+ *     [k*chunk_elems, (k+1)*chunk_elems).  A chunk is the unit that has its own
+ *     scale and its own server (Algorithm 1 line 7: the paper uses C = n).
+ *   - Sign words: element j of a vector is bit (j & 31) of 32-bit word (j >> 5);
+ *     bit 1 means +scale, bit 0 means -scale; sign(+-0) = +1.
+ *   - All floating point is IEEE binary32, one rounding per operation, no fused
+ *     multiply-add, in the operation order stated per call.  Squared norms are
+ *     accumulated in binary64 (exact squares, tree order fixed by the launch
+ *     plan) and each scale is rounded to binary32 once.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is queued asynchronously; no call synchronises the host.  A context
+ *     serves one stream at a time.  Results are deterministic for a given
+ *     context geometry (no floating-point atomics).
+ *   - Return value: APMS_OK or a negative apms_status.  Arguments are validated
+ *     on the host before anything is launched; on an error nothing was queued.
+ *     d == 0 is a valid empty problem: calls validate and return APMS_OK.
+ *   - There is no CPU fallback.  A context created with APMS_DEVICE_NONE only
+ *     validates: every compute call returns APMS_ENODEV once its arguments
+ *     have passed validation.
+ */
+#ifndef APMS_H
+#define APMS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct apms_ctx apms_ctx;
+
+typedef enum apms_status {
+    APMS_OK = 0,
+    APMS_EINVAL = -1,  /* null pointer, bad scalar (n < 1, beta outside [0,1), t < 1, ...) */
+    APMS_EALIGN = -2,  /* an array pointer is not 16-byte aligned */
+    APMS_ESHAPE = -3,  /* chunk_elems not a positive multiple of 32, or d not a multiple of it */
+    APMS_ENOMEM = -4,  /* host or device allocation of the context's scratch failed */
+    APMS_EHIP = -5,    /* a HIP call failed; see apms_last_hip_error */
+    APMS_ENODEV = -6,  /* validation-only context: arguments are fine, nothing can run */
+    APMS_EALIAS = -7,  /* two array arguments overlap */
+    APMS_ESTATE = -8   /* an error buffer is pending in deferred form and a different one was passed */
+} apms_status;
+
+#define APMS_DEVICE_NONE (-1)
+
+/* How the two error buffers are left by apms_compress / apms_server_reduce. */
+#define APMS_ERRORS_EAGER 0    /* on return (in stream order) they hold delta as the paper defines it */
+#define APMS_ERRORS_DEFERRED 1 /* they hold the compensated vector u; delta = u - C[u] is formed on next read */
+
+/* Launch geometry of a context (read-only report; see apms_get_plan). */
+typedef struct apms_plan {
+    int64_t d;
+    int32_t n;
+    int64_t chunk_elems;
+    int64_t chunks;                 /* C */
+    int32_t tile_elems;             /* elements one workgroup handles per iteration (4096) */
+    int32_t tiles_per_chunk;        /* ceil(chunk_elems / tile_elems); the last tile may be ragged */
+    int32_t compress_tiles_per_block;
+    int32_t compress_blocks_per_chunk;
+    int64_t compress_grid;          /* n * C * compress_blocks_per_chunk workgroups */
+    int32_t server_tiles_per_block;
+    int32_t server_blocks_per_chunk;
+    int64_t server_grid;            /* C * server_blocks_per_chunk */
+    int64_t apply_grid;             /* C * tiles_per_chunk */
+    int64_t scratch_bytes;          /* device memory owned by the context */
+} apms_plan;
+
+/*
+ * Create a context for vectors of d elements, n workers and chunks of
+ * chunk_elems elements on HIP device `device` (or APMS_DEVICE_NONE).  The
+ * context owns a few MB of device scratch (binary64 norm partials, pending
+ * scales).  Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
+ */
+int apms_create(apms_ctx **out, int64_t d, int32_t n, int64_t chunk_elems, int device);
+
+/* Free the context and its scratch.  NULL is accepted. */
+int apms_destroy(apms_ctx *ctx);
+
+/* Static English text for a status code. */
+const char *apms_strerror(int status);
+
+/* The raw hipError_t behind the last APMS_EHIP of this context (0 if none). */
+int apms_last_hip_error(const apms_ctx *ctx);
+
+/* Copy the launch geometry into *plan. */
+int apms_get_plan(const apms_ctx *ctx, apms_plan *plan);
+
+/*
+ * Tuning knob: how many 4096-element tiles one workgroup streams in
+ * apms_compress and in apms_server_reduce (each >= 1; 0 keeps the current
+ * value).  Changes the reduction tree of the norms, hence possibly the last
+ * bit of a scale; results stay deterministic for a fixed setting.
+ */
+int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t server_tiles);
+
+/*
+ * Error-buffer mode (default APMS_ERRORS_EAGER).
+ *
+ * The new error delta' = u - C[u] (Section 3.1; supplement steps 1-2) needs
+ * the scale of the WHOLE chunk, which is known only after the chunk has been
+ * streamed once.  In EAGER mode a second pass over the error buffer forms
+ * delta' before the call's work ends.  In DEFERRED mode the call stores the
+ * compensated vector u in the error buffer instead and the context keeps the
+ * chunk scales; the next apms_compress / apms_server_reduce on the SAME
+ * buffer forms delta' = u - (u >= 0 ? +s : -s) while reading it (bit-identical
+ * to the eager value: one binary32 subtraction of the same operands), which
+ * saves one read and one write of the buffer per step.  While a buffer is
+ * pending its contents are u, not delta: call apms_finalize_errors before
+ * reading it (checkpoint, test) or before handing a different buffer to the
+ * same context (else APMS_ESTATE).
+ */
+int apms_set_error_mode(apms_ctx *ctx, int mode);
+
+/*
+ * Bring pending error buffers to the paper's delta.  Either pointer may be
+ * NULL (skip).  A buffer that is not pending is left untouched.
+ *   worker_err [n][d], server_err [d].
+ */
+int apms_finalize_errors(apms_ctx *ctx, float *worker_err, float *server_err, void *stream);
+
+/*
+ * Warm-up: one step of the original Adam (Section 3.2; Algorithm 1 line 2)
+ * on the full-precision average of the n workers' gradients.
+ *   gbar = (sum_{i=0}^{n-1} g_i) * fl(1/n)                (worker order)
+ *   m <- fl(beta1*m) + fl(fl(1-beta1)*gbar)
+ *   v <- fl(beta2*v) + fl(fl(1-beta2)*fl(gbar*gbar))
+ *   x <- x - lr * (m / bc1) / (sqrt(v / bc2) + eps),  bc = 1 - beta^t formed in
+ *        binary64 on the host and rounded to binary32
+ *   x, m, v [d] in/out;  g [n][d] in;  t >= 1 is the 1-based step index.
+ * Errors: EINVAL (beta1, beta2 outside [0,1), t < 1, null), EALIGN, EALIAS.
+ */
+int apms_warmup_step(apms_ctx *ctx, float *x, float *m, float *v, const float *g,
+                     float lr, float beta1, float beta2, float eps, int64_t t, void *stream);
+
+/*
+ * Hand-over from warm-up to the compression stage (Algorithm 1, line 1
+ * initial errors = 0, and line 3): replicate worker 0's momentum slice to all
+ * n slices and zero both error buffers; v is frozen simply by no longer
+ * calling apms_warmup_step.  Clears any pending deferred state.
+ *   m [n][d]: slice 0 in, all slices out;  worker_err [n][d], server_err [d] out.
+ */
+int apms_freeze(apms_ctx *ctx, float *m, float *worker_err, float *server_err, void *stream);
+
+/*
+ * Worker side of one compressed step (Algorithm 1 lines 6-7; supplement
+ * step 1), for all n workers and all C chunks:
+ *   u      = (fl(beta*m_i) + fl(fl(1-beta)*g_i)) + delta_i
+ *   scale  = fl32( sqrt( sum_chunk u^2 / chunk_elems ) )        (Section 5.1)
+ *   bit    = (u >= 0)
+ *   delta_i <- u - (bit ? +scale : -scale)
+ *   m, g        [n][d] in (the local momentum is not stored: the gather of
+ *               apms_apply overwrites m)
+ *   worker_err  [n][d] in/out
+ *   packed      [n][d/32] out, sign words
+ *   scales      [n][C] out
+ * Errors: EINVAL (beta outside [0,1), null), EALIGN, EALIAS, ESTATE, EHIP.
+ */
+int apms_compress(apms_ctx *ctx, const float *m, const float *g, float *worker_err,
+                  uint32_t *packed, float *scales, float beta, void *stream);
+
+/*
+ * Server side (Algorithm 1 line 9; supplement step 2), for all C chunks:
+ *   a      = (sum_{i=0}^{n-1} (bit_i ? +scale_i : -scale_i)) * fl(1/n)
+ *   ubar   = a + deltabar
+ *   sscale = fl32( sqrt( sum_chunk ubar^2 / chunk_elems ) );  sbit = (ubar >= 0)
+ *   deltabar <- ubar - (sbit ? +sscale : -sscale)
+ *   packed [n][d/32], scales [n][C] in (as written by apms_compress)
+ *   server_err [d] in/out;  spacked [d/32] out;  sscales [C] out.
+ */
+int apms_server_reduce(apms_ctx *ctx, const uint32_t *packed, const float *scales,
+                       float *server_err, uint32_t *spacked, float *sscales, void *stream);
+
+/*
+ * Gather + model update (Algorithm 1 lines 10-11; supplement step 3):
+ *   m_i <- (sbit ? +sscale : -sscale)   for every worker i  (a copy: bit-exact)
+ *   x   <- x - lr * ( m / (sqrt(v) + eps) )        v frozen, no bias correction;
+ *          eps = 0 gives the paper's literal division by sqrt(v)
+ *   spacked [d/32], sscales [C], v [d] in;  x [d] in/out;  m [n][d] out.
+ */
+int apms_apply(apms_ctx *ctx, const uint32_t *spacked, const float *sscales, const float *v,
+               float *x, float *m, float lr, float eps, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APMS_H */

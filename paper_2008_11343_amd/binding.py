@@ -1,0 +1,179 @@
+"""Thin ctypes binding of libapms.so: same names as the C ABI (include/apms.h), argument marshalling only.
+
+Array arguments are torch tensors on the GPU (their data_ptr() is passed) or plain integer device
+addresses; `stream` is a torch.cuda.Stream, a raw hipStream_t integer or None (= torch's current
+stream).  Every step of the method runs in the library's HIP kernels; there is no fallback: if the
+shared library is missing it is built with hipcc, and if that is impossible the import fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch  # first: libapms must bind to the HIP runtime torch has already loaded
+
+from . import build as _build
+
+APMS_OK = 0
+APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS_EALIAS, APMS_ESTATE = (
+    -1, -2, -3, -4, -5, -6, -7, -8)
+APMS_DEVICE_NONE = -1
+APMS_ERRORS_EAGER = 0
+APMS_ERRORS_DEFERRED = 1
+
+EXPORTS = (
+    "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
+    "apms_set_tiles_per_block", "apms_set_error_mode", "apms_finalize_errors", "apms_warmup_step",
+    "apms_freeze", "apms_compress", "apms_server_reduce", "apms_apply",
+)
+
+
+class apms_plan(ctypes.Structure):
+    _fields_ = [
+        ("d", ctypes.c_int64), ("n", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
+        ("chunks", ctypes.c_int64), ("tile_elems", ctypes.c_int32), ("tiles_per_chunk", ctypes.c_int32),
+        ("compress_tiles_per_block", ctypes.c_int32), ("compress_blocks_per_chunk", ctypes.c_int32),
+        ("compress_grid", ctypes.c_int64), ("server_tiles_per_block", ctypes.c_int32),
+        ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
+        ("apply_grid", ctypes.c_int64), ("scratch_bytes", ctypes.c_int64),
+    ]
+
+    def as_dict(self):
+        return {name: getattr(self, name) for name, _ in self._fields_}
+
+
+class ApmsError(RuntimeError):
+    def __init__(self, status, where, hip=0):
+        self.status = status
+        self.hip = hip
+        msg = "%s: %s (status %d)" % (where, apms_strerror(status), status)
+        if hip:
+            msg += " [hipError_t %d]" % hip
+        super().__init__(msg)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load():
+    """Load libapms.so (building it first if it has never been built)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build()
+    lib = ctypes.CDLL(_build.LIB)
+    vp, i32, i64, f32, ci = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_int
+    sig = {
+        "apms_create": (ci, [ctypes.POINTER(vp), i64, i32, i64, ci]),
+        "apms_destroy": (ci, [vp]),
+        "apms_strerror": (ctypes.c_char_p, [ci]),
+        "apms_last_hip_error": (ci, [vp]),
+        "apms_get_plan": (ci, [vp, ctypes.POINTER(apms_plan)]),
+        "apms_set_tiles_per_block": (ci, [vp, i32, i32]),
+        "apms_set_error_mode": (ci, [vp, ci]),
+        "apms_finalize_errors": (ci, [vp, vp, vp, vp]),
+        "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
+        "apms_freeze": (ci, [vp, vp, vp, vp, vp]),
+        "apms_compress": (ci, [vp, vp, vp, vp, vp, vp, f32, vp]),
+        "apms_server_reduce": (ci, [vp, vp, vp, vp, vp, vp, vp]),
+        "apms_apply": (ci, [vp, vp, vp, vp, vp, vp, f32, f32, vp]),
+    }
+    for name in EXPORTS:
+        fn = getattr(lib, name)          # AttributeError if the library does not export it
+        fn.restype, fn.argtypes = sig[name]
+    _lib = lib
+    return lib
+
+
+def _ptr(a):
+    if a is None:
+        return None
+    if isinstance(a, int):
+        return a
+    if isinstance(a, torch.Tensor):
+        if not a.is_contiguous():
+            raise ValueError("tensor arguments must be contiguous")
+        return a.data_ptr() or None
+    raise TypeError("expected a torch tensor, an integer device address or None")
+
+
+def _stream(s):
+    if s is None:
+        return torch.cuda.current_stream().cuda_stream or None if torch.cuda.is_available() else None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+def _check(ctx, status, where):
+    if status != APMS_OK:
+        hip = load().apms_last_hip_error(ctx) if (ctx and status == APMS_EHIP) else 0
+        raise ApmsError(status, where, hip)
+
+
+def apms_strerror(status: int) -> str:
+    return load().apms_strerror(status).decode()
+
+
+def apms_create(d: int, n: int, chunk_elems: int, device: int = 0):
+    """Returns the opaque context handle."""
+    out = ctypes.c_void_p()
+    _check(None, load().apms_create(ctypes.byref(out), d, n, chunk_elems, device), "apms_create")
+    return out
+
+
+def apms_destroy(ctx):
+    _check(None, load().apms_destroy(ctx), "apms_destroy")
+
+
+def apms_last_hip_error(ctx) -> int:
+    return load().apms_last_hip_error(ctx)
+
+
+def apms_get_plan(ctx) -> dict:
+    plan = apms_plan()
+    _check(ctx, load().apms_get_plan(ctx, ctypes.byref(plan)), "apms_get_plan")
+    return plan.as_dict()
+
+
+def apms_set_tiles_per_block(ctx, compress_tiles: int = 0, server_tiles: int = 0):
+    _check(ctx, load().apms_set_tiles_per_block(ctx, compress_tiles, server_tiles), "apms_set_tiles_per_block")
+
+
+def apms_set_error_mode(ctx, mode: int):
+    _check(ctx, load().apms_set_error_mode(ctx, mode), "apms_set_error_mode")
+
+
+def apms_finalize_errors(ctx, worker_err=None, server_err=None, stream=None):
+    _check(ctx, load().apms_finalize_errors(ctx, _ptr(worker_err), _ptr(server_err), _stream(stream)),
+           "apms_finalize_errors")
+
+
+def apms_warmup_step(ctx, x, m, v, g, lr, beta1, beta2, eps, t, stream=None):
+    _check(ctx, load().apms_warmup_step(ctx, _ptr(x), _ptr(m), _ptr(v), _ptr(g), lr, beta1, beta2, eps, t,
+                                        _stream(stream)), "apms_warmup_step")
+
+
+def apms_freeze(ctx, m, worker_err, server_err, stream=None):
+    _check(ctx, load().apms_freeze(ctx, _ptr(m), _ptr(worker_err), _ptr(server_err), _stream(stream)),
+           "apms_freeze")
+
+
+def apms_compress(ctx, m, g, worker_err, packed, scales, beta, stream=None):
+    _check(ctx, load().apms_compress(ctx, _ptr(m), _ptr(g), _ptr(worker_err), _ptr(packed), _ptr(scales), beta,
+                                     _stream(stream)), "apms_compress")
+
+
+def apms_server_reduce(ctx, packed, scales, server_err, spacked, sscales, stream=None):
+    _check(ctx, load().apms_server_reduce(ctx, _ptr(packed), _ptr(scales), _ptr(server_err), _ptr(spacked),
+                                          _ptr(sscales), _stream(stream)), "apms_server_reduce")
+
+
+def apms_apply(ctx, spacked, sscales, v, x, m, lr, eps, stream=None):
+    _check(ctx, load().apms_apply(ctx, _ptr(spacked), _ptr(sscales), _ptr(v), _ptr(x), _ptr(m), lr, eps,
+                                  _stream(stream)), "apms_apply")

@@ -1,0 +1,377 @@
+// C ABI of libapms: argument validation, launch planning, deferred-error
+// bookkeeping.  Every entry point validates on the host before touching HIP.
+
+#include "../../include/apms.h"
+
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <new>
+
+#include "apms_launch.h"
+
+struct apms_ctx {
+    int64_t d = 0;
+    int32_t n = 0;
+    int64_t L = 0;
+    int64_t C = 0;
+    int device = APMS_DEVICE_NONE;
+    int32_t tiles_per_chunk = 0;
+    int32_t w_tiles_per_block = 0, w_blocks_per_chunk = 0;    // apms_compress
+    int32_t s_tiles_per_block = 0, s_blocks_per_chunk = 0;    // apms_server_reduce
+    // device scratch (owned)
+    double* w_partials = nullptr;     // [n*C][tiles_per_chunk] (sized for 1 tile per block)
+    double* s_partials = nullptr;     // [C][tiles_per_chunk]
+    float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
+    float* s_pending = nullptr;       // [C]
+    int64_t scratch_bytes = 0;
+    // deferred-error bookkeeping (host side, follows call order = stream order)
+    const void* pending_werr = nullptr;
+    const void* pending_serr = nullptr;
+    int error_mode = APMS_ERRORS_EAGER;
+    int last_hip = 0;
+};
+
+namespace {
+
+constexpr int32_t kTileElems = 4096;
+constexpr int32_t kDefaultCompressTiles = 8;
+constexpr int32_t kDefaultServerTiles = 4;
+constexpr int64_t kMaxGrid = 0x7fffffff;
+
+struct Range {
+    const void* p;
+    int64_t bytes;
+};
+
+bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+bool overlap(const Range& a, const Range& b) {
+    if (a.bytes <= 0 || b.bytes <= 0) return false;
+    const uintptr_t a0 = reinterpret_cast<uintptr_t>(a.p), b0 = reinterpret_cast<uintptr_t>(b.p);
+    return a0 < b0 + static_cast<uintptr_t>(b.bytes) && b0 < a0 + static_cast<uintptr_t>(a.bytes);
+}
+
+// null -> EINVAL, misaligned -> EALIGN, overlapping -> EALIAS; empty arrays (d == 0) are not looked at
+int check_arrays(const Range* r, int count) {
+    for (int i = 0; i < count; ++i)
+        if (r[i].bytes > 0 && !r[i].p) return APMS_EINVAL;
+    for (int i = 0; i < count; ++i)
+        if (r[i].bytes > 0 && misaligned(r[i].p)) return APMS_EALIGN;
+    for (int i = 0; i < count; ++i)
+        for (int j = i + 1; j < count; ++j)
+            if (overlap(r[i], r[j])) return APMS_EALIAS;
+    return APMS_OK;
+}
+
+bool unit_interval(float b) { return b >= 0.0f && b < 1.0f; }   // false for NaN
+
+int32_t ceil_div32(int64_t a, int64_t b) { return static_cast<int32_t>((a + b - 1) / b); }
+
+void plan_blocks(apms_ctx* c) {
+    c->w_blocks_per_chunk = c->tiles_per_chunk ? ceil_div32(c->tiles_per_chunk, c->w_tiles_per_block) : 0;
+    c->s_blocks_per_chunk = c->tiles_per_chunk ? ceil_div32(c->tiles_per_chunk, c->s_tiles_per_block) : 0;
+}
+
+apms::Geometry geometry(const apms_ctx* c) {
+    apms::Geometry g;
+    g.d = c->d;
+    g.L = c->L;
+    g.n = c->n;
+    g.C = static_cast<int32_t>(c->C);
+    g.tiles_per_chunk = c->tiles_per_chunk;
+    return g;
+}
+
+int hip_fail(apms_ctx* c, hipError_t e) {
+    c->last_hip = static_cast<int>(e);
+    return APMS_EHIP;
+}
+
+// Makes the context's device current for the duration of a call.
+struct DeviceScope {
+    int prev = -1;
+    bool switched = false;
+    hipError_t err = hipSuccess;
+    explicit DeviceScope(int device) {
+        err = hipGetDevice(&prev);
+        if (err == hipSuccess && prev != device) {
+            err = hipSetDevice(device);
+            switched = (err == hipSuccess);
+        }
+    }
+    ~DeviceScope() {
+        if (switched) (void)hipSetDevice(prev);
+    }
+};
+
+void free_scratch(apms_ctx* c) {
+    if (c->w_partials) (void)hipFree(c->w_partials);
+    if (c->s_partials) (void)hipFree(c->s_partials);
+    if (c->w_pending) (void)hipFree(c->w_pending);
+    if (c->s_pending) (void)hipFree(c->s_pending);
+    c->w_partials = c->s_partials = nullptr;
+    c->w_pending = c->s_pending = nullptr;
+}
+
+// Common tail of validation: empty problem -> OK (done), validation-only context -> ENODEV.
+// Returns 1 when the caller should go on and launch.
+int ready_to_launch(const apms_ctx* c, int* status) {
+    if (c->d == 0) {
+        *status = APMS_OK;
+        return 0;
+    }
+    if (c->device == APMS_DEVICE_NONE) {
+        *status = APMS_ENODEV;
+        return 0;
+    }
+    return 1;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* apms_strerror(int status) {
+    switch (status) {
+        case APMS_OK: return "ok";
+        case APMS_EINVAL: return "invalid argument (null pointer or scalar out of range)";
+        case APMS_EALIGN: return "array pointer is not 16-byte aligned";
+        case APMS_ESHAPE: return "chunk_elems must be a positive multiple of 32 and divide d";
+        case APMS_ENOMEM: return "allocation of the context's scratch failed";
+        case APMS_EHIP: return "a HIP call failed (see apms_last_hip_error)";
+        case APMS_ENODEV: return "validation-only context: no device to run on";
+        case APMS_EALIAS: return "array arguments overlap";
+        case APMS_ESTATE: return "another error buffer is pending in deferred form; finalize it first";
+        default: return "unknown apms status";
+    }
+}
+
+int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int device) {
+    if (!out) return APMS_EINVAL;
+    *out = nullptr;
+    if (n < 1 || d < 0 || (device < 0 && device != APMS_DEVICE_NONE)) return APMS_EINVAL;
+    if (chunk_elems < 32 || chunk_elems % 32 != 0 || d % chunk_elems != 0) return APMS_ESHAPE;
+    const int64_t C = d / chunk_elems;
+    const int64_t tiles = (chunk_elems + kTileElems - 1) / kTileElems;
+    // every grid must fit a 1-D launch, every (worker, chunk) index an int32
+    if (tiles > kMaxGrid || C > kMaxGrid || static_cast<int64_t>(n) * C > kMaxGrid ||
+        static_cast<int64_t>(n) * C * tiles > kMaxGrid)
+        return APMS_ESHAPE;
+    apms_ctx* c = new (std::nothrow) apms_ctx();
+    if (!c) return APMS_ENOMEM;
+    c->d = d;
+    c->n = n;
+    c->L = chunk_elems;
+    c->C = C;
+    c->device = device;
+    c->tiles_per_chunk = C ? static_cast<int32_t>(tiles) : 0;
+    c->w_tiles_per_block = kDefaultCompressTiles;
+    c->s_tiles_per_block = kDefaultServerTiles;
+    plan_blocks(c);
+    const int64_t pairs = static_cast<int64_t>(n) * C;
+    const int64_t wp = pairs * c->tiles_per_chunk * static_cast<int64_t>(sizeof(double));
+    const int64_t sp = C * c->tiles_per_chunk * static_cast<int64_t>(sizeof(double));
+    const int64_t wq = pairs * static_cast<int64_t>(sizeof(float));
+    const int64_t sq = C * static_cast<int64_t>(sizeof(float));
+    c->scratch_bytes = wp + sp + wq + sq;
+    if (device != APMS_DEVICE_NONE && d > 0) {
+        DeviceScope scope(device);
+        hipError_t e = scope.err;
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_partials), wp);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_partials), sp);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_pending), sq);
+        if (e != hipSuccess) {
+            free_scratch(c);
+            delete c;
+            return e == hipErrorOutOfMemory ? APMS_ENOMEM : APMS_EHIP;
+        }
+    }
+    *out = c;
+    return APMS_OK;
+}
+
+int apms_destroy(apms_ctx* ctx) {
+    if (!ctx) return APMS_OK;
+    if (ctx->device != APMS_DEVICE_NONE) {
+        DeviceScope scope(ctx->device);
+        free_scratch(ctx);
+    }
+    delete ctx;
+    return APMS_OK;
+}
+
+int apms_last_hip_error(const apms_ctx* ctx) { return ctx ? ctx->last_hip : 0; }
+
+int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
+    if (!c || !plan) return APMS_EINVAL;
+    plan->d = c->d;
+    plan->n = c->n;
+    plan->chunk_elems = c->L;
+    plan->chunks = c->C;
+    plan->tile_elems = kTileElems;
+    plan->tiles_per_chunk = c->tiles_per_chunk;
+    plan->compress_tiles_per_block = c->w_tiles_per_block;
+    plan->compress_blocks_per_chunk = c->w_blocks_per_chunk;
+    plan->compress_grid = static_cast<int64_t>(c->n) * c->C * c->w_blocks_per_chunk;
+    plan->server_tiles_per_block = c->s_tiles_per_block;
+    plan->server_blocks_per_chunk = c->s_blocks_per_chunk;
+    plan->server_grid = c->C * c->s_blocks_per_chunk;
+    plan->apply_grid = c->C * c->tiles_per_chunk;
+    plan->scratch_bytes = c->scratch_bytes;
+    return APMS_OK;
+}
+
+int apms_set_tiles_per_block(apms_ctx* c, int32_t compress_tiles, int32_t server_tiles) {
+    if (!c || compress_tiles < 0 || server_tiles < 0) return APMS_EINVAL;
+    if (compress_tiles) c->w_tiles_per_block = compress_tiles;
+    if (server_tiles) c->s_tiles_per_block = server_tiles;
+    plan_blocks(c);
+    return APMS_OK;
+}
+
+int apms_set_error_mode(apms_ctx* c, int mode) {
+    if (!c || (mode != APMS_ERRORS_EAGER && mode != APMS_ERRORS_DEFERRED)) return APMS_EINVAL;
+    c->error_mode = mode;
+    return APMS_OK;
+}
+
+int apms_finalize_errors(apms_ctx* c, float* worker_err, float* server_err, void* stream) {
+    if (!c) return APMS_EINVAL;
+    if ((worker_err && misaligned(worker_err)) || (server_err && misaligned(server_err))) return APMS_EALIGN;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const apms::Geometry geo = geometry(c);
+    if (worker_err && c->pending_werr == worker_err) {
+        hipError_t e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_werr = nullptr;
+    }
+    if (server_err && c->pending_serr == server_err) {
+        hipError_t e = apms::launch_finalize(geo, 1, server_err, c->s_pending, s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_serr = nullptr;
+    }
+    return APMS_OK;
+}
+
+int apms_warmup_step(apms_ctx* c, float* x, float* m, float* v, const float* g, float lr, float beta1,
+                     float beta2, float eps, int64_t t, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{x, vec}, {m, vec}, {v, vec}, {g, vec * c->n}};
+    if (int rc = check_arrays(r, 4)) return rc;
+    if (!unit_interval(beta1) || !unit_interval(beta2) || t < 1 || !(lr == lr) || !(eps == eps))
+        return APMS_EINVAL;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    const float bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(t)));
+    const float bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(t)));
+    const float inv_n = 1.0f / static_cast<float>(c->n);
+    hipError_t e = apms::launch_warmup(c->d, c->n, x, m, v, g, lr, beta1, 1.0f - beta1, beta2, 1.0f - beta2,
+                                       bc1, bc2, eps, inv_n, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
+int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{m, vec * c->n}, {worker_err, vec * c->n}, {server_err, vec}};
+    if (int rc = check_arrays(r, 3)) return rc;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_freeze(c->d, c->n, m, worker_err, server_err, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(c, e);
+    c->pending_werr = nullptr;
+    c->pending_serr = nullptr;
+    return APMS_OK;
+}
+
+int apms_compress(apms_ctx* c, const float* m, const float* g, float* worker_err, uint32_t* packed,
+                  float* scales, float beta, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t all = c->d * 4 * c->n;
+    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!unit_interval(beta)) return APMS_EINVAL;
+    if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const apms::Geometry geo = geometry(c);
+    const float* prev = c->pending_werr ? c->w_pending : nullptr;
+    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, worker_err,
+                                         packed, c->w_partials, prev, beta, 1.0f - beta, s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    // from here on the buffer holds u and the context holds its scales
+    c->pending_werr = worker_err;
+    e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
+                            c->w_pending, s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    if (c->error_mode == APMS_ERRORS_EAGER) {
+        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_werr = nullptr;
+    }
+    return APMS_OK;
+}
+
+int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales, float* server_err,
+                       uint32_t* spacked, float* sscales, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{packed, vec / 32 * c->n}, {scales, c->n * c->C * 4}, {server_err, vec},
+                       {spacked, vec / 32}, {sscales, c->C * 4}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (c->pending_serr && c->pending_serr != server_err) return APMS_ESTATE;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const apms::Geometry geo = geometry(c);
+    const float* prev = c->pending_serr ? c->s_pending : nullptr;
+    const float inv_n = 1.0f / static_cast<float>(c->n);
+    hipError_t e = apms::launch_server_reduce(geo, c->s_tiles_per_block, c->s_blocks_per_chunk, packed, scales,
+                                              server_err, spacked, c->s_partials, prev, inv_n, s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    c->pending_serr = server_err;
+    e = apms::launch_scales(c->C, c->s_blocks_per_chunk, c->L, c->s_partials, sscales, c->s_pending, s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    if (c->error_mode == APMS_ERRORS_EAGER) {
+        e = apms::launch_finalize(geo, 1, server_err, c->s_pending, s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_serr = nullptr;
+    }
+    return APMS_OK;
+}
+
+int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const float* v, float* x, float* m,
+               float lr, float eps, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{spacked, vec / 32}, {sscales, c->C * 4}, {v, vec}, {x, vec}, {m, vec * c->n}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!(lr == lr) || !(eps == eps)) return APMS_EINVAL;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_apply(geometry(c), spacked, sscales, v, x, m, lr, eps,
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
+}  // extern "C"

@@ -1,0 +1,55 @@
+// Host-callable launchers of the libapms kernels.  Each queues work on `stream`
+// and returns hipGetLastError() of its launches; none synchronises.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace apms {
+
+// Geometry shared by the chunked kernels.
+struct Geometry {
+    int64_t d;                 // vector length
+    int64_t L;                 // chunk length (multiple of 32)
+    int32_t n;                 // workers
+    int32_t C;                 // chunks = d / L
+    int32_t tiles_per_chunk;   // ceil(L / 4096)
+};
+
+// Worker step over all (worker, chunk) pairs: writes u into werr, sign words into
+// packed, one binary64 partial sum of u^2 per workgroup into partials
+// [n*C][blocks_per_chunk].  prev_scales (nullable, [n*C]) marks werr as holding
+// last step's u (deferred form).
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
+                           const float* m, const float* g, float* werr, uint32_t* packed,
+                           double* partials, const float* prev_scales, float beta, float one_minus_beta,
+                           hipStream_t stream);
+
+// Reduce partials [pairs][blocks_per_chunk] in fixed order, scale = fl32(sqrt(S / L));
+// writes scales_out[pair] and pending_out[pair] (either may be null).
+hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, const double* partials,
+                         float* scales_out, float* pending_out, hipStream_t stream);
+
+// err[p][j] <- err[p][j] - (err >= 0 ? +s_p : -s_p) for pairs p = slice*C + chunk,
+// slices = n (worker errors) or 1 (server error).
+hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
+                           hipStream_t stream);
+
+// Server step over all chunks.
+hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
+                                const uint32_t* packed, const float* scales, float* serr, uint32_t* spacked,
+                                double* partials, const float* prev_scales, float inv_n, hipStream_t stream);
+
+// Gather + model update.
+hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
+                        float* x, float* m, float lr, float eps, hipStream_t stream);
+
+// Adam warm-up step on the averaged gradient.
+hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,
+                         float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
+                         float bc2, float eps, float inv_n, hipStream_t stream);
+
+// m[i] <- m[0] for i >= 1; werr, serr <- 0.
+hipError_t launch_freeze(int64_t d, int32_t n, float* m, float* werr, float* serr, hipStream_t stream);
+
+}  // namespace apms

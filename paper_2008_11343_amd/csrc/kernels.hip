@@ -1,0 +1,476 @@
+// HIP kernels of libapms for gfx950: the compression stage of APMSqueeze
+// (Algorithm 1 lines 3-12; supplement "Proof to the Updating Form") and the
+// Adam warm-up step (Section 3.2).  All kernels are HBM-bandwidth bound:
+// 128-bit coalesced streaming accesses, sign packing by an OR across 8-lane
+// groups, binary64 norm partials reduced in a fixed order (no atomics).
+//
+// Built with -ffp-contract=off: every binary32 operation below rounds once, in
+// the order written.  The only fused operation is the explicit binary64
+// fma(u, u, acc), which equals mul-then-add because the product of two
+// binary32 values is exact in binary64.
+
+#include "apms_device.h"
+#include "apms_launch.h"
+
+namespace apms {
+
+namespace {
+
+// ------------------------------------------------------------------------
+// Worker step (Algorithm 1 lines 6-7): u = beta*m + (1-beta)*g + delta, sign
+// words, partial sums of u^2; u is parked in the error buffer.
+// ------------------------------------------------------------------------
+
+// If the error buffer holds last step's compensated vector u' (deferred form),
+// the error is delta = u' - C[u'] = u' - (u' >= 0 ? +s' : -s').  With s' = 0 this
+// is the identity, which is how a buffer that already holds delta is read.
+__device__ __forceinline__ float read_error(float stored, float prev_scale) {
+    return stored - signed_scale(stored >= 0.0f, prev_scale);
+}
+
+__device__ __forceinline__ f32x4 compensated(f32x4 vm, f32x4 vg, f32x4 ve, float beta, float omb,
+                                             float prev_scale) {
+    f32x4 u;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float bm = beta * vm[c];
+        const float bg = omb * vg[c];
+        const float mi = bm + bg;                       // local momentum m_t^(i)
+        u[c] = mi + read_error(ve[c], prev_scale);      // + delta^(i)
+    }
+    return u;
+}
+
+__device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const double w = static_cast<double>(u[c]);
+        acc[c] = fma(w, w, acc[c]);
+    }
+}
+
+template <bool kFull>
+__device__ __forceinline__ void compress_tile(const float* __restrict__ m, const float* __restrict__ g,
+                                              float* __restrict__ e, uint32_t* __restrict__ packed,
+                                              int64_t chunk_base, int64_t tile_off, int64_t L, int lane_off,
+                                              int lane, int wave, float beta, float omb, float prev_scale,
+                                              double (&acc)[4]) {
+    const int64_t off0 = tile_off + lane_off;             // inside the chunk
+    bool ok[kRows];
+    f32x4 vm[kRows], vg[kRows], ve[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        ok[r] = kFull || (off0 + 32 * r < L);
+        if (ok[r]) {
+            const int64_t p = chunk_base + off0 + 32 * r;
+            vm[r] = load_stream(m + p);
+            vg[r] = load_stream(g + p);
+            ve[r] = load_stream(e + p);
+        }
+    }
+    uint32_t words[kRows];
+    const int shift = 4 * (lane & 7);
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        uint32_t nib = 0u;
+        if (ok[r]) {
+            const f32x4 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
+            store_stream(e + chunk_base + off0 + 32 * r, u);
+            accumulate_squares(acc, u);
+            nib = sign_nibble(u) << shift;
+        }
+        words[r] = or_across_group8(nib);                 // all 64 lanes take part
+    }
+    if ((lane & 7) == 0) {
+        // first of the four consecutive words this 8-lane group owns
+        const int64_t w0 = (chunk_base + tile_off + wave * kWaveTile + (lane >> 3) * 128) >> 5;
+        if (kFull && (w0 & 3) == 0) {
+            u32x4 pk = {words[0], words[1], words[2], words[3]};
+            *reinterpret_cast<u32x4*>(packed + w0) = pk;
+        } else {
+#pragma unroll
+            for (int r = 0; r < kRows; ++r)
+                if (ok[r]) packed[w0 + r] = words[r];
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void compress_kernel(
+    const float* __restrict__ m, const float* __restrict__ g, float* __restrict__ e,
+    uint32_t* __restrict__ packed, double* __restrict__ partials, const float* __restrict__ prev_scales,
+    int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk, int32_t tiles_per_block,
+    int32_t blocks_per_chunk, float beta, float omb) {
+    __shared__ double lds[kWaves];
+    const int64_t blk = blockIdx.x;
+    const int64_t pair = blk / blocks_per_chunk;          // worker * C + chunk
+    const int32_t b = static_cast<int32_t>(blk - pair * blocks_per_chunk);
+    const int64_t worker = pair / C;
+    const int64_t chunk = pair - worker * C;
+    const int64_t chunk_base = worker * d + chunk * L;
+    const float prev_scale = prev_scales ? prev_scales[pair] : 0.0f;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int lane_off = lane_base_offset(wave, lane);
+    const int32_t t0 = b * tiles_per_block;
+    const int32_t t1 = min(t0 + tiles_per_block, tiles_per_chunk);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int32_t t = t0; t < t1; ++t) {
+        const int64_t tile_off = static_cast<int64_t>(t) * kTile;
+        if (tile_off + kTile <= L)
+            compress_tile<true>(m, g, e, packed, chunk_base, tile_off, L, lane_off, lane, wave, beta, omb,
+                                prev_scale, acc);
+        else
+            compress_tile<false>(m, g, e, packed, chunk_base, tile_off, L, lane_off, lane, wave, beta, omb,
+                                 prev_scale, acc);
+    }
+    const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    const double total = block_sum_f64(mine, lds);
+    if (threadIdx.x == 0) partials[blk] = total;
+}
+
+// ------------------------------------------------------------------------
+// Scale of every chunk (Section 5.1): ||u||_2 / sqrt(L).
+// ------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kThreads) void scales_kernel(const double* __restrict__ partials,
+                                                          int32_t blocks_per_chunk, int64_t L,
+                                                          float* __restrict__ scales_out,
+                                                          float* __restrict__ pending_out) {
+    __shared__ double lds[kWaves];
+    const int64_t pair = blockIdx.x;
+    const double* p = partials + pair * blocks_per_chunk;
+    double mine = 0.0;
+    for (int32_t j = threadIdx.x; j < blocks_per_chunk; j += kThreads) mine += p[j];
+    const double S = block_sum_f64(mine, lds);
+    if (threadIdx.x == 0) {
+        const double mean_sq = S / static_cast<double>(L);
+        const float s = static_cast<float>(sqrt(mean_sq));
+        if (scales_out) scales_out[pair] = s;
+        if (pending_out) pending_out[pair] = s;
+    }
+}
+
+// ------------------------------------------------------------------------
+// Eager error: delta' = u - C[u] in place (Section 3.1).
+// ------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ err,
+                                                            const float* __restrict__ scales, int64_t d,
+                                                            int64_t L, int32_t C, int32_t tiles_per_chunk) {
+    const int64_t blk = blockIdx.x;
+    const int64_t pair = blk / tiles_per_chunk;           // slice * C + chunk
+    const int64_t tile = blk - pair * tiles_per_chunk;
+    const int64_t slice = pair / C;
+    const int64_t chunk = pair - slice * C;
+    const int64_t chunk_base = slice * d + chunk * L;
+    const float s = scales[pair];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int64_t off0 = tile * kTile + lane_base_offset(wave, lane);
+    f32x4 ve[kRows];
+    bool ok[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        ok[r] = off0 + 32 * r < L;
+        if (ok[r]) ve[r] = load_stream(err + chunk_base + off0 + 32 * r);
+    }
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        if (!ok[r]) continue;
+        f32x4 out;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) out[c] = read_error(ve[r][c], s);
+        store_stream(err + chunk_base + off0 + 32 * r, out);
+    }
+}
+
+// ------------------------------------------------------------------------
+// Server step (Algorithm 1 line 9): average the n decoded messages in worker
+// order, add the server error, re-compress.
+// ------------------------------------------------------------------------
+
+template <bool kFull>
+__device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
+                                            const float* __restrict__ scales, float* __restrict__ serr,
+                                            uint32_t* __restrict__ spacked, int64_t d, int64_t L, int32_t C,
+                                            int32_t n, int64_t chunk, int64_t tile_off, int lane_off, int lane,
+                                            int wave, float inv_n, float prev_scale, double (&acc)[4]) {
+    const int64_t chunk_base = chunk * L;                 // inside one [d] vector
+    const int64_t off0 = tile_off + lane_off;
+    const int shift = 4 * (lane & 7);
+    // first of this group's four consecutive words, inside one worker's [d/32] words
+    const int64_t w0 = (chunk_base + tile_off + wave * kWaveTile + (lane >> 3) * 128) >> 5;
+    const int64_t words_per_worker = d >> 5;
+    bool ok[kRows];
+    f32x4 ve[kRows];
+    f32x4 sum[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        ok[r] = kFull || (off0 + 32 * r < L);
+        if (ok[r]) ve[r] = load_stream(serr + chunk_base + off0 + 32 * r);
+        sum[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+    }
+#pragma unroll 4
+    for (int32_t i = 0; i < n; ++i) {
+        const float s = scales[static_cast<int64_t>(i) * C + chunk];
+        const uint32_t* wp = packed + i * words_per_worker + w0;
+        uint32_t w[kRows];
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) w[r] = ok[r] ? wp[r] : 0u;
+#pragma unroll
+        for (int r = 0; r < kRows; ++r) {
+            const uint32_t nib = w[r] >> shift;
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                sum[r][c] = sum[r][c] + signed_scale((nib >> c) & 1u, s);
+        }
+    }
+    uint32_t words[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        uint32_t nib = 0u;
+        if (ok[r]) {
+            f32x4 ubar;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float avg = sum[r][c] * inv_n;
+                ubar[c] = avg + read_error(ve[r][c], prev_scale);
+            }
+            store_stream(serr + chunk_base + off0 + 32 * r, ubar);
+            accumulate_squares(acc, ubar);
+            nib = sign_nibble(ubar) << shift;
+        }
+        words[r] = or_across_group8(nib);
+    }
+    if ((lane & 7) == 0) {
+        if (kFull && (w0 & 3) == 0) {
+            u32x4 pk = {words[0], words[1], words[2], words[3]};
+            *reinterpret_cast<u32x4*>(spacked + w0) = pk;
+        } else {
+#pragma unroll
+            for (int r = 0; r < kRows; ++r)
+                if (ok[r]) spacked[w0 + r] = words[r];
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void server_kernel(
+    const uint32_t* __restrict__ packed, const float* __restrict__ scales, float* __restrict__ serr,
+    uint32_t* __restrict__ spacked, double* __restrict__ partials, const float* __restrict__ prev_scales,
+    int64_t d, int64_t L, int32_t C, int32_t n, int32_t tiles_per_chunk, int32_t tiles_per_block,
+    int32_t blocks_per_chunk, float inv_n) {
+    __shared__ double lds[kWaves];
+    const int64_t blk = blockIdx.x;
+    const int64_t chunk = blk / blocks_per_chunk;
+    const int32_t b = static_cast<int32_t>(blk - chunk * blocks_per_chunk);
+    const float prev_scale = prev_scales ? prev_scales[chunk] : 0.0f;
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int lane_off = lane_base_offset(wave, lane);
+    const int32_t t0 = b * tiles_per_block;
+    const int32_t t1 = min(t0 + tiles_per_block, tiles_per_chunk);
+    double acc[4] = {0.0, 0.0, 0.0, 0.0};
+    for (int32_t t = t0; t < t1; ++t) {
+        const int64_t tile_off = static_cast<int64_t>(t) * kTile;
+        if (tile_off + kTile <= L)
+            server_tile<true>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
+                              inv_n, prev_scale, acc);
+        else
+            server_tile<false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
+                               inv_n, prev_scale, acc);
+    }
+    const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+    const double total = block_sum_f64(mine, lds);
+    if (threadIdx.x == 0) partials[blk] = total;
+}
+
+// ------------------------------------------------------------------------
+// Gather + model update (Algorithm 1 lines 10-11).
+// ------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restrict__ spacked,
+                                                         const float* __restrict__ sscales,
+                                                         const float* __restrict__ v, float* __restrict__ x,
+                                                         float* __restrict__ m, int64_t d, int64_t L,
+                                                         int32_t n, int32_t tiles_per_chunk, float lr,
+                                                         float eps) {
+    const int64_t blk = blockIdx.x;
+    const int64_t chunk = blk / tiles_per_chunk;
+    const int64_t tile = blk - chunk * tiles_per_chunk;
+    const int64_t chunk_base = chunk * L;
+    const float s = sscales[chunk];
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int64_t off0 = tile * kTile + lane_base_offset(wave, lane);
+    const int shift = 4 * (lane & 7);
+    bool ok[kRows];
+    f32x4 vv[kRows], vx[kRows];
+    uint32_t w[kRows];
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        ok[r] = off0 + 32 * r < L;
+        if (ok[r]) {
+            const int64_t p = chunk_base + off0 + 32 * r;
+            w[r] = spacked[p >> 5];
+            vv[r] = load_stream(v + p);
+            vx[r] = load_stream(x + p);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kRows; ++r) {
+        if (!ok[r]) continue;
+        const int64_t p = chunk_base + off0 + 32 * r;
+        const uint32_t nib = w[r] >> shift;
+        f32x4 mom, xn;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            mom[c] = signed_scale((nib >> c) & 1u, s);       // decoded server message
+            const float root = sqrtf(vv[r][c]);
+            const float denom = root + eps;
+            const float ratio = mom[c] / denom;
+            const float step = lr * ratio;
+            xn[c] = vx[r][c] - step;
+        }
+        store_stream(x + p, xn);
+        for (int32_t i = 0; i < n; ++i) store_stream(m + static_cast<int64_t>(i) * d + p, mom);
+    }
+}
+
+// ------------------------------------------------------------------------
+// Warm-up: original Adam on the averaged gradient (Section 3.2).
+// ------------------------------------------------------------------------
+
+__global__ __launch_bounds__(kThreads) void warmup_kernel(float* __restrict__ x, float* __restrict__ m,
+                                                          float* __restrict__ v, const float* __restrict__ g,
+                                                          int64_t d, int32_t n, float lr, float beta1,
+                                                          float omb1, float beta2, float omb2, float bc1,
+                                                          float bc2, float eps, float inv_n) {
+    const int64_t quads = d >> 2;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride) {
+        const int64_t p = q << 2;
+        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 4
+        for (int32_t i = 0; i < n; ++i) {
+            const f32x4 gi = load_stream(g + static_cast<int64_t>(i) * d + p);
+#pragma unroll
+            for (int c = 0; c < 4; ++c) acc[c] = acc[c] + gi[c];
+        }
+        const f32x4 mo = load_stream(m + p), vo = load_stream(v + p), xo = load_stream(x + p);
+        f32x4 mn, vn, xn;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float gbar = acc[c] * inv_n;
+            const float m_keep = beta1 * mo[c];
+            const float m_inc = omb1 * gbar;
+            mn[c] = m_keep + m_inc;
+            const float gsq = gbar * gbar;
+            const float v_keep = beta2 * vo[c];
+            const float v_inc = omb2 * gsq;
+            vn[c] = v_keep + v_inc;
+            const float mhat = mn[c] / bc1;
+            const float vhat = vn[c] / bc2;
+            const float root = sqrtf(vhat);
+            const float denom = root + eps;
+            const float ratio = mhat / denom;
+            const float step = lr * ratio;
+            xn[c] = xo[c] - step;
+        }
+        store_stream(m + p, mn);
+        store_stream(v + p, vn);
+        store_stream(x + p, xn);
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void freeze_kernel(float* __restrict__ m, float* __restrict__ werr,
+                                                          float* __restrict__ serr, int64_t d, int32_t n) {
+    const int64_t quads = d >> 2;
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    const f32x4 zero = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride) {
+        const int64_t p = q << 2;
+        const f32x4 m0 = load_stream(m + p);
+        store_stream(serr + p, zero);
+        store_stream(werr + p, zero);
+        for (int32_t i = 1; i < n; ++i) {
+            store_stream(m + static_cast<int64_t>(i) * d + p, m0);
+            store_stream(werr + static_cast<int64_t>(i) * d + p, zero);
+        }
+    }
+}
+
+inline uint32_t stride_grid(int64_t d) {
+    const int64_t quads = d >> 2;
+    int64_t blocks = (quads + kThreads - 1) / kThreads;
+    const int64_t cap = 256 * 16;                         // 16 workgroups per CU, grid-stride beyond that
+    if (blocks > cap) blocks = cap;
+    if (blocks < 1) blocks = 1;
+    return static_cast<uint32_t>(blocks);
+}
+
+}  // namespace
+
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
+                           const float* m, const float* g, float* werr, uint32_t* packed, double* partials,
+                           const float* prev_scales, float beta, float one_minus_beta, hipStream_t stream) {
+    const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, m, g,
+                       werr, packed, partials, prev_scales, geo.d, geo.L, geo.C, geo.tiles_per_chunk,
+                       tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, const double* partials,
+                         float* scales_out, float* pending_out, hipStream_t stream) {
+    if (pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(scales_kernel, dim3(static_cast<uint32_t>(pairs)), dim3(kThreads), 0, stream, partials,
+                       blocks_per_chunk, L, scales_out, pending_out);
+    return hipGetLastError();
+}
+
+hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
+                           hipStream_t stream) {
+    const int64_t grid = static_cast<int64_t>(slices) * geo.C * geo.tiles_per_chunk;
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(finalize_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, err,
+                       scales, geo.d, geo.L, geo.C, geo.tiles_per_chunk);
+    return hipGetLastError();
+}
+
+hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
+                                const uint32_t* packed, const float* scales, float* serr, uint32_t* spacked,
+                                double* partials, const float* prev_scales, float inv_n, hipStream_t stream) {
+    const int64_t grid = static_cast<int64_t>(geo.C) * blocks_per_chunk;
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(server_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, packed,
+                       scales, serr, spacked, partials, prev_scales, geo.d, geo.L, geo.C, geo.n,
+                       geo.tiles_per_chunk, tiles_per_block, blocks_per_chunk, inv_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
+                        float* x, float* m, float lr, float eps, hipStream_t stream) {
+    const int64_t grid = static_cast<int64_t>(geo.C) * geo.tiles_per_chunk;
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, spacked,
+                       sscales, v, x, m, geo.d, geo.L, geo.n, geo.tiles_per_chunk, lr, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,
+                         float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
+                         float bc2, float eps, float inv_n, hipStream_t stream) {
+    if (d <= 0) return hipSuccess;
+    hipLaunchKernelGGL(warmup_kernel, dim3(stride_grid(d)), dim3(kThreads), 0, stream, x, m, v, g, d, n, lr,
+                       beta1, one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
+    return hipGetLastError();
+}
+
+hipError_t launch_freeze(int64_t d, int32_t n, float* m, float* werr, float* serr, hipStream_t stream) {
+    if (d <= 0) return hipSuccess;
+    hipLaunchKernelGGL(freeze_kernel, dim3(stride_grid(d)), dim3(kThreads), 0, stream, m, werr, serr, d, n);
+    return hipGetLastError();
+}
+
+}  // namespace apms

@@ -1,0 +1,195 @@
+"""Host-side tests of the C-ABI boundary: no GPU, no compute.
+
+The library must load, export every function include/apms.h declares, and turn every invalid call into
+a status code before anything is launched.  A context created with APMS_DEVICE_NONE validates only.
+"""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2008_11343_amd import binding as B
+from paper_2008_11343_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+A = 0x10000          # fake, well-aligned "device addresses": validation never dereferences them
+STEP = 0x10000000
+
+
+def fake(i):
+    return A + i * STEP
+
+
+@pytest.fixture
+def ctx():
+    c = B.apms_create(d=8192, n=2, chunk_elems=4096, device=B.APMS_DEVICE_NONE)
+    yield c
+    B.apms_destroy(c)
+
+
+def status_of(fn, *args, **kw):
+    try:
+        fn(*args, **kw)
+    except B.ApmsError as e:
+        return e.status
+    return B.APMS_OK
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "apms.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(apms_[a-z_]+)\s*\(", header))
+    assert declared == set(B.EXPORTS)
+    lib = ctypes.CDLL(B.library_path())
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_strerror_covers_all_codes():
+    texts = {B.apms_strerror(code) for code in range(0, -9, -1)}
+    assert len(texts) == 9 and "unknown apms status" not in texts
+    assert B.apms_strerror(-99) == "unknown apms status"
+
+
+@pytest.mark.parametrize("d,n,chunk,expect", [
+    (8192, 0, 4096, B.APMS_EINVAL),
+    (-32, 1, 32, B.APMS_EINVAL),
+    (8192, 1, 0, B.APMS_ESHAPE),
+    (8192, 1, 48, B.APMS_ESHAPE),          # not a multiple of 32
+    (8192, 1, 4096 * 3, B.APMS_ESHAPE),    # does not divide d
+    (8192, 1, 16, B.APMS_ESHAPE),
+    (0, 3, 32, B.APMS_OK),                 # empty problem
+    (96, 5, 32, B.APMS_OK),
+])
+def test_create_validation(d, n, chunk, expect):
+    try:
+        c = B.apms_create(d, n, chunk, B.APMS_DEVICE_NONE)
+    except B.ApmsError as e:
+        assert e.status == expect
+    else:
+        assert expect == B.APMS_OK
+        B.apms_destroy(c)
+
+
+def test_create_rejects_bad_device_and_null_out():
+    assert status_of(B.apms_create, 8192, 1, 4096, -7) == B.APMS_EINVAL
+    assert B.load().apms_create(None, 8192, 1, 4096, B.APMS_DEVICE_NONE) == B.APMS_EINVAL
+    assert B.load().apms_destroy(None) == B.APMS_OK
+
+
+def test_valid_calls_on_validation_only_context_report_no_device(ctx):
+    """No CPU fallback: with nothing to run on, a valid call fails loudly."""
+    assert status_of(B.apms_compress, ctx, fake(0), fake(1), fake(2), fake(3), fake(4), 0.9) == B.APMS_ENODEV
+    assert status_of(B.apms_server_reduce, ctx, fake(0), fake(1), fake(2), fake(3), fake(4)) == B.APMS_ENODEV
+    assert status_of(B.apms_apply, ctx, fake(0), fake(1), fake(2), fake(3), fake(4), 1e-4, 1e-8) == B.APMS_ENODEV
+    assert status_of(B.apms_warmup_step, ctx, fake(0), fake(1), fake(2), fake(3), 1e-3, 0.9, 0.999, 1e-8, 1) == \
+        B.APMS_ENODEV
+    assert status_of(B.apms_freeze, ctx, fake(0), fake(1), fake(2)) == B.APMS_ENODEV
+    assert status_of(B.apms_finalize_errors, ctx, fake(0), fake(1)) == B.APMS_ENODEV
+
+
+def test_null_misaligned_and_overlapping_arrays(ctx):
+    good = [fake(i) for i in range(5)]
+    for pos in range(5):
+        args = list(good)
+        args[pos] = None
+        assert status_of(B.apms_compress, ctx, *args, 0.9) == B.APMS_EINVAL
+        assert status_of(B.apms_server_reduce, ctx, *args) == B.APMS_EINVAL
+        assert status_of(B.apms_apply, ctx, *args, 1e-4, 1e-8) == B.APMS_EINVAL
+        args[pos] = good[pos] + 4
+        assert status_of(B.apms_compress, ctx, *args, 0.9) == B.APMS_EALIGN
+        assert status_of(B.apms_server_reduce, ctx, *args) == B.APMS_EALIGN
+        assert status_of(B.apms_apply, ctx, *args, 1e-4, 1e-8) == B.APMS_EALIGN
+    # worker_err overlapping the tail of m ([n][d] floats = 65536 bytes)
+    args = list(good)
+    args[2] = good[0] + 65536 - 16
+    assert status_of(B.apms_compress, ctx, *args, 0.9) == B.APMS_EALIAS
+    args[2] = good[0] + 65536                      # touching, not overlapping
+    assert status_of(B.apms_compress, ctx, *args, 0.9) == B.APMS_ENODEV
+    # apply: x aliasing v
+    assert status_of(B.apms_apply, ctx, good[0], good[1], good[2], good[2], good[4], 1e-4, 1e-8) == B.APMS_EALIAS
+    assert status_of(B.apms_warmup_step, ctx, good[0], good[0], good[2], good[3], 1e-3, 0.9, 0.999, 1e-8, 1) == \
+        B.APMS_EALIAS
+
+
+def test_scalar_ranges(ctx):
+    good = [fake(i) for i in range(5)]
+    for beta in (-0.1, 1.0, 1.5, float("nan")):
+        assert status_of(B.apms_compress, ctx, *good, beta) == B.APMS_EINVAL
+    assert status_of(B.apms_compress, ctx, *good, 0.0) == B.APMS_ENODEV
+    w = good[:4]
+    assert status_of(B.apms_warmup_step, ctx, *w, 1e-3, 0.9, 0.999, 1e-8, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_warmup_step, ctx, *w, 1e-3, 1.0, 0.999, 1e-8, 1) == B.APMS_EINVAL
+    assert status_of(B.apms_warmup_step, ctx, *w, 1e-3, 0.9, -0.5, 1e-8, 1) == B.APMS_EINVAL
+    assert status_of(B.apms_warmup_step, ctx, *w, float("nan"), 0.9, 0.999, 1e-8, 1) == B.APMS_EINVAL
+    assert status_of(B.apms_apply, ctx, *good, float("nan"), 1e-8) == B.APMS_EINVAL
+    assert status_of(B.apms_set_error_mode, ctx, 7) == B.APMS_EINVAL
+    assert status_of(B.apms_set_tiles_per_block, ctx, -1, 0) == B.APMS_EINVAL
+
+
+def test_empty_problem_is_ok_without_a_device():
+    c = B.apms_create(0, 4, 64, B.APMS_DEVICE_NONE)
+    try:
+        B.apms_compress(c, None, None, None, None, None, 0.9)
+        B.apms_server_reduce(c, None, None, None, None, None)
+        B.apms_apply(c, None, None, None, None, None, 1e-4, 1e-8)
+        B.apms_warmup_step(c, None, None, None, None, 1e-3, 0.9, 0.999, 1e-8, 1)
+        B.apms_freeze(c, None, None, None)
+        plan = B.apms_get_plan(c)
+        assert plan["chunks"] == 0 and plan["compress_grid"] == 0 and plan["apply_grid"] == 0
+    finally:
+        B.apms_destroy(c)
+
+
+@pytest.mark.parametrize("wl", W.CONFIGS, ids=lambda w: w.name)
+def test_launch_plan_of_every_config(wl):
+    """Host launch planning: grids cover every tile exactly once and fit a 1-D launch."""
+    c = B.apms_create(wl.d_pad, wl.n, wl.L, B.APMS_DEVICE_NONE)
+    try:
+        p = B.apms_get_plan(c)
+        assert p["d"] == wl.d_pad and p["n"] == wl.n and p["chunk_elems"] == wl.L and p["chunks"] == wl.C
+        assert p["tile_elems"] == 4096
+        assert p["tiles_per_chunk"] == -(-wl.L // 4096)
+        for kind in ("compress", "server"):
+            tpb, bpc = p[kind + "_tiles_per_block"], p[kind + "_blocks_per_chunk"]
+            assert (bpc - 1) * tpb < p["tiles_per_chunk"] <= bpc * tpb
+        assert p["compress_grid"] == wl.n * wl.C * p["compress_blocks_per_chunk"] < 2 ** 31
+        assert p["server_grid"] == wl.C * p["server_blocks_per_chunk"]
+        assert p["apply_grid"] == wl.C * p["tiles_per_chunk"]
+        assert p["scratch_bytes"] < 64 << 20
+        B.apms_set_tiles_per_block(c, 3, 5)
+        q = B.apms_get_plan(c)
+        assert q["compress_tiles_per_block"] == 3 and q["server_tiles_per_block"] == 5
+        assert q["compress_blocks_per_chunk"] == -(-p["tiles_per_chunk"] // 3)
+    finally:
+        B.apms_destroy(c)
+
+
+def test_ragged_chunk_plan():
+    c = B.apms_create(3 * (4096 * 2 + 160), 2, 4096 * 2 + 160, B.APMS_DEVICE_NONE)
+    try:
+        p = B.apms_get_plan(c)
+        assert p["tiles_per_chunk"] == 3 and p["chunks"] == 3
+    finally:
+        B.apms_destroy(c)
+
+
+def test_workload_recipes():
+    """The synthetic configurations: padded sizes, chunk lengths and the tensor-list bucket."""
+    sizes = {w.name: (w.d_pad, w.n, w.L, w.C) for w in W.CONFIGS}
+    assert sizes["tiny"] == (1 << 20, 4, 1 << 16, 16)
+    assert sizes["bert-base-flat"] == (110_002_176, 8, 13_750_272, 8)
+    assert sizes["bert-large-flat"] == (340_000_768, 16, 21_250_048, 16)
+    assert sizes["worker-scaling"] == (110_100_480, 64, 1_720_320, 64)
+    assert sizes["bert-large-tensor-list"] == (335_151_104, 16, 20_946_944, 16)
+    t = W.bert_large_tensors()
+    assert len(t) == 391 and sum(s for _, s, _ in t) == 335_141_888
+    assert sum(1 for _, _, ln in t if ln) == 2 * (1 + 2 * 24)
+    small = W.scaled(W.FULL_PIPELINE, 4096 * 16, n=2)
+    g0, g1 = W.host_grad(small, 0), W.host_grad(small, 1)
+    assert g0.shape == (2, small.d_pad) and not (g0 == g1).all()
+    assert (W.host_grad(small, 0) == g0).all()                 # seeded: same key, same bits
+    st = W.host_state(W.scaled(W.TINY, 5000, chunk=4096))
+    assert st["x"].shape == (8192,) and (st["x"][5000:] == 0).all() and (st["v"][5000:] == 1).all()
+    assert (st["m"][:, 5000:] == 0).all() and not st["werr"].any() and not st["serr"].any()

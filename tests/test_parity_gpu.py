@@ -1,0 +1,298 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs.
+
+Bar (from the build's target): sign words bit-exact; scales, errors, momenta and parameters within
+rtol 1e-5 / atol 1e-7.  Scales are additionally expected to be bit-equal except where the binary64
+sum lands next to a binary32 rounding boundary (the two sides add in different orders).
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2008_11343_amd import binding as B
+from paper_2008_11343_amd import workloads as W
+from paper_2008_11343_amd.runner import DeviceRun, from_host_state
+
+pytestmark = pytest.mark.gpu
+
+F = np.float32
+RTOL, ATOL = 1e-5, 1e-7
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[parity] " + msg, flush=True)
+
+
+def host(t):
+    a = t.detach().cpu().numpy()
+    return a.view(np.uint32) if a.dtype == np.int32 else a
+
+
+def close(a, b, what):
+    np.testing.assert_allclose(a, b, rtol=RTOL, atol=ATOL, err_msg=what)
+
+
+def same_words(a, b, what):
+    a, b = np.asarray(a).reshape(-1), np.asarray(b).reshape(-1)
+    bad = np.flatnonzero(a != b)
+    assert bad.size == 0, "%s: %d sign words differ, first at word %d: %08x vs %08x" % (
+        what, bad.size, bad[0], a[bad[0]], b[bad[0]])
+
+
+def oracle_state(d, n, L, st):
+    return oracle.State(d, n, L, st["x"], st["m"], st["v"], st["werr"], st["serr"])
+
+
+def compare_all(run, ost, tag, errors=True):
+    same_words(host(run.packed), ost.packed, tag + " packed")
+    same_words(host(run.spacked), ost.spacked, tag + " spacked")
+    close(host(run.scales), ost.scales, tag + " scales")
+    close(host(run.sscales), ost.sscales, tag + " sscales")
+    close(host(run.x), ost.x, tag + " x")
+    # the gathered momentum is a copy of +-sscale: exact given equal server scales
+    gm, om = host(run.m), ost.m
+    close(gm, om, tag + " m")
+    if np.array_equal(host(run.sscales), ost.sscales):
+        assert np.array_equal(gm, om), tag + " m must be a bit-exact copy"
+    if errors:
+        close(host(run.werr), ost.werr, tag + " worker_err")
+        close(host(run.serr), ost.serr, tag + " server_err")
+
+
+def random_case(seed, d, n, L, err_scale=3e-3):
+    rng = np.random.default_rng(seed)
+    st = dict(
+        x=rng.normal(0, 0.02, d).astype(F),
+        m=rng.normal(0, 1e-3, (n, d)).astype(F),
+        v=np.exp(rng.normal(-12, 1, d)).astype(F),
+        werr=rng.normal(0, err_scale, (n, d)).astype(F),
+        serr=rng.normal(0, err_scale / 3, d).astype(F),
+    )
+    g = rng.normal(0, 1e-2, (n, d)).astype(F)
+    return st, g
+
+
+SHAPES = [
+    # (n, L, C): one ragged word-tail tile, chunks not a multiple of the tile, several tiles per block
+    (1, 32, 1),
+    (3, 160, 2),
+    (2, 4096, 2),
+    (3, 4096 * 9 + 32 * 5, 3),
+    (5, 4096 * 17, 2),
+    (4, 65536, 4),
+    (16, 4096 * 3 + 1024, 2),
+]
+
+
+@pytest.mark.parametrize("n,L,C", SHAPES)
+@pytest.mark.parametrize("deferred", [False, True], ids=["eager", "deferred"])
+def test_stagewise_parity(n, L, C, deferred):
+    """Each call fed the oracle's inputs for that stage: signs must match exactly."""
+    d = L * C
+    say("stagewise n=%d L=%d C=%d deferred=%s" % (n, L, C, deferred))
+    st, g = random_case(100 + n + L, d, n, L)
+    st["werr"][0, :8] = [0.0, -0.0, 1e-40, -1e-40, 0.0, 0.0, 0.0, 0.0]
+    g[0, :8] = 0.0
+    st["m"][0, :8] = 0.0
+    ost = oracle_state(d, n, L, st)
+    run = DeviceRun(d, n, L, DEV, deferred=deferred, state={k: torch.from_numpy(v) for k, v in st.items()})
+    gd = torch.from_numpy(g).to(DEV)
+    beta, lr, eps = 0.9, 1e-4, 1e-8
+
+    run.compress(gd, beta)
+    oracle.compress(d, n, L, ost.m, g, ost.werr, ost.packed, ost.scales, beta)
+    same_words(host(run.packed), ost.packed, "packed")
+    close(host(run.scales), ost.scales, "scales")
+    # stage 2 consumes the ORACLE's messages
+    run.packed.copy_(torch.from_numpy(ost.packed.view(np.int32)))
+    run.scales.copy_(torch.from_numpy(ost.scales))
+    run.server_reduce()
+    oracle.server_reduce(d, n, L, ost.packed, ost.scales, ost.serr, ost.spacked, ost.sscales)
+    same_words(host(run.spacked), ost.spacked, "spacked")
+    close(host(run.sscales), ost.sscales, "sscales")
+    run.spacked.copy_(torch.from_numpy(ost.spacked.view(np.int32)))
+    run.sscales.copy_(torch.from_numpy(ost.sscales))
+    run.apply(lr, eps)
+    oracle.apply(d, n, L, ost.spacked, ost.sscales, ost.v, ost.x, ost.m, lr, eps)
+    assert np.array_equal(host(run.m), ost.m), "gathered momentum must be a bit-exact copy"
+    close(host(run.x), ost.x, "x")
+    if deferred:
+        run.finalize_errors()
+    close(host(run.werr), ost.werr, "worker_err")
+    close(host(run.serr), ost.serr, "server_err")
+    torch.cuda.synchronize()
+    run.close()
+
+
+@pytest.mark.parametrize("deferred", [False, True], ids=["eager", "deferred"])
+def test_tiny_trajectory(deferred):
+    """Config 'tiny' (d = 2^20, n = 4, chunk 2^16): 10 compressed steps, every buffer, every step."""
+    wl = W.TINY
+    st = W.host_state(wl)
+    ost = oracle_state(wl.d_pad, wl.n, wl.L, st)
+    run = from_host_state(wl, st, DEV, deferred=deferred)
+    gd = torch.empty(wl.n, wl.d_pad, dtype=torch.float32, device=DEV)
+    equal_scales = 0
+    for step in range(wl.steps):
+        say("tiny trajectory step %d deferred=%s" % (step, deferred))
+        g = W.host_grad(wl, step)
+        gd.copy_(torch.from_numpy(g))
+        run.step(gd, wl.beta, wl.lr, wl.eps)
+        ost.step(g, wl.beta, wl.lr, wl.eps)
+        if deferred and step in (4, wl.steps - 1):
+            run.finalize_errors()            # mid-run and final: pending -> delta, then carry on
+        compare_all(run, ost, "step %d" % step, errors=(not deferred) or step in (4, wl.steps - 1))
+        equal_scales += int(np.array_equal(host(run.scales), ost.scales))
+    assert equal_scales >= wl.steps - 1
+    run.close()
+
+
+@pytest.mark.parametrize("n", [1, 3, 5, 64])
+def test_worker_counts(n):
+    """n = 1, non-power-of-two n and the 64-worker case of the worker-scaling config, three steps each."""
+    L, C = 4096 * 2 + 96, 2
+    d = L * C
+    st, _ = random_case(7 + n, d, n, L, err_scale=0.0)
+    ost = oracle_state(d, n, L, st)
+    run = DeviceRun(d, n, L, DEV, deferred=True, state={k: torch.from_numpy(v) for k, v in st.items()})
+    wl = W.scaled(W.WORKER_SCALING, d, n=n, chunk=L)
+    for step in range(3):
+        say("worker count n=%d step %d" % (n, step))
+        g = W.host_grad(wl, step)
+        run.step(torch.from_numpy(g).to(DEV), 0.9, 1e-4, 1e-8)
+        ost.step(g, 0.9, 1e-4, 1e-8)
+    run.finalize_errors()
+    compare_all(run, ost, "n=%d" % n)
+    run.close()
+
+
+def test_degenerate_values():
+    """All-zero input (scale 0, all signs +), denormals, huge and tiny magnitudes side by side."""
+    n, L, C = 2, 4096 + 64, 2
+    d = L * C
+    z = np.zeros
+    st = dict(x=z(d, F), m=z((n, d), F), v=np.ones(d, F), werr=z((n, d), F), serr=z(d, F))
+    g = z((n, d), F)
+    g[1, L:L + 6] = [1e-38, -1e-38, 1e-42, -1e-42, 3e3, -3e3]     # chunk 1 of worker 1 only
+    ost = oracle_state(d, n, L, st)
+    run = DeviceRun(d, n, L, DEV, state={k: torch.from_numpy(v) for k, v in st.items()})
+    for step in range(2):
+        say("degenerate values step %d" % step)
+        run.step(torch.from_numpy(g).to(DEV), 0.9, 1e-4, 1e-8)
+        ost.step(g, 0.9, 1e-4, 1e-8)
+        compare_all(run, ost, "degenerate step %d" % step)
+    assert host(run.scales)[0, 0] == 0.0 and host(run.scales)[1, 1] > 0.0
+    run.close()
+
+
+def test_empty_problem_on_device():
+    run = DeviceRun(0, 3, 64, DEV)
+    g = torch.empty(3, 0, dtype=torch.float32, device=DEV)
+    run.step(g, 0.9, 1e-4, 1e-8)
+    run.finalize_errors()
+    torch.cuda.synchronize()
+    run.close()
+
+
+def test_determinism_and_tile_plan_independence():
+    """Same inputs -> same bits; a different tiles-per-block plan changes only the summation tree
+    (scales within 1 ulp), never a sign word of the same step."""
+    n, L, C = 4, 4096 * 13, 2
+    d = L * C
+    st, g = random_case(55, d, n, L)
+    outs = []
+    for tiles in (8, 8, 1, 5):
+        run = DeviceRun(d, n, L, DEV, state={k: torch.from_numpy(v) for k, v in st.items()})
+        B.apms_set_tiles_per_block(run.ctx, tiles, tiles)
+        say("determinism tiles_per_block=%d" % tiles)
+        run.step(torch.from_numpy(g).to(DEV), 0.9, 1e-4, 1e-8)
+        outs.append({k: host(getattr(run, k)).copy() for k in
+                     ("packed", "scales", "spacked", "sscales", "x", "m", "werr", "serr")})
+        run.close()
+    for k, v in outs[0].items():
+        assert np.array_equal(v, outs[1][k]), k
+    for other in outs[2:]:
+        same_words(other["packed"], outs[0]["packed"], "packed across plans")
+        np.testing.assert_allclose(other["scales"], outs[0]["scales"], rtol=2e-7)
+
+
+def test_pending_buffer_state_machine():
+    """Deferred mode remembers which buffer holds u; a different buffer is refused until finalize."""
+    n, L, C = 2, 4096, 1
+    d = L * C
+    st, g = random_case(77, d, n, L)
+    run = DeviceRun(d, n, L, DEV, deferred=True, state={k: torch.from_numpy(v) for k, v in st.items()})
+    gd = torch.from_numpy(g).to(DEV)
+    run.compress(gd, 0.9)
+    other = torch.zeros_like(run.werr)
+    with pytest.raises(B.ApmsError) as ei:
+        B.apms_compress(run.ctx, run.m, gd, other, run.packed, run.scales, 0.9)
+    assert ei.value.status == B.APMS_ESTATE
+    run.finalize_errors()
+    B.apms_compress(run.ctx, run.m, gd, other, run.packed, run.scales, 0.9)    # now fine
+    B.apms_finalize_errors(run.ctx, other, None)
+    torch.cuda.synchronize()
+    run.close()
+
+
+def test_side_stream():
+    """Work is queued on the caller's stream."""
+    n, L, C = 2, 4096 * 2, 2
+    d = L * C
+    st, g = random_case(88, d, n, L)
+    ost = oracle_state(d, n, L, st)
+    run = DeviceRun(d, n, L, DEV, state={k: torch.from_numpy(v) for k, v in st.items()})
+    gd = torch.from_numpy(g).to(DEV)
+    torch.cuda.synchronize()
+    s = torch.cuda.Stream()
+    run.step(gd, 0.9, 1e-4, 1e-8, stream=s)
+    s.synchronize()
+    ost.step(g, 0.9, 1e-4, 1e-8)
+    compare_all(run, ost, "side stream")
+    run.close()
+
+
+def test_warmup_freeze_then_compressed():
+    """The full pipeline at reduced size: a BERT-style tensor list (LayerNorm gradients 10x smaller),
+    5 Adam warm-up steps on the averaged gradient, freeze, then 6 compressed steps."""
+    tensors = tuple(W.bert_large_tensors(layers=2, hidden=64, ffn=256, vocab=500, positions=32))
+    total = sum(s for _, s, _ in tensors)
+    wl = W.Workload("pipeline-small", W.FULL_PIPELINE.index, d=total, n=4, steps=6, warmup_steps=5,
+                    tensors=tensors)
+    d, n, L = wl.d_pad, wl.n, wl.L
+    st = W.host_state(wl, warm_start=True)
+    run = DeviceRun(d, n, L, DEV, deferred=True)
+    run.x.copy_(torch.from_numpy(st["x"]))
+    run.v.zero_()
+    # rubbish in what freeze must overwrite
+    run.m[1:].fill_(3.0)
+    run.werr.fill_(1.0)
+    run.serr.fill_(-1.0)
+    ox, om, ov = st["x"].copy(), st["m"].copy(), st["v"].copy()
+    lr_w = 1e-3
+    for t in range(1, wl.warmup_steps + 1):
+        say("pipeline warm-up step %d" % t)
+        g = W.host_grad(wl, t - 1)
+        run.warmup_step(torch.from_numpy(g).to(DEV), lr_w, wl.beta, wl.beta2, wl.eps, t)
+        oracle.warmup_step(d, n, ox, om, ov, g, lr_w, wl.beta, wl.beta2, wl.eps, t)
+        close(host(run.x), ox, "warm-up x")
+        close(host(run.m[0]), om, "warm-up m")
+        np.testing.assert_allclose(host(run.v), ov, rtol=RTOL, atol=1e-12, err_msg="warm-up v")
+    run.freeze()
+    omn, owerr, oserr = np.empty((n, d), F), np.ones((n, d), F), np.ones(d, F)
+    oracle.freeze(d, n, om, omn, owerr, oserr)
+    assert np.array_equal(host(run.werr), owerr) and np.array_equal(host(run.serr), oserr)
+    for i in range(n):
+        assert np.array_equal(host(run.m[i]), host(run.m[0]))
+    # continue both sides from the GPU's frozen state (one copy of the bits)
+    ost = oracle.State(d, n, L, host(run.x), host(run.m), host(run.v))
+    for step in range(wl.steps):
+        say("pipeline compressed step %d" % step)
+        g = W.host_grad(wl, wl.warmup_steps + step)
+        run.step(torch.from_numpy(g).to(DEV), wl.beta, wl.lr, wl.eps)
+        ost.step(g, wl.beta, wl.lr, wl.eps)
+        compare_all(run, ost, "pipeline step %d" % step, errors=False)
+    run.finalize_errors()
+    compare_all(run, ost, "pipeline end")
+    run.close()
