@@ -1,0 +1,189 @@
+#!/usr/bin/env python3
+"""Benchmark of the APMSqueeze compressed-momentum step on one MI355X.
+
+A "step" is one pass of the whole hot path (apms_compress -> apms_server_reduce -> apms_apply,
+Algorithm 1 lines 6-11) over one batch of fresh synthetic gradients for all n simulated workers.
+Inputs are generated in HBM before the timed region of each step; the timed region is bracketed by
+HIP events on the stream the kernels are launched on.  In deferred-error mode the final
+apms_finalize_errors (which completes the last step's error update) is inside the timed total.
+
+Prints ONE JSON line on stdout (progress goes to stderr):
+  value      parameters per second of the whole job (d_pad * steps / timed seconds)
+  roofline   HBM roofline of the dominant kernel (the worker-side compress kernel)
+  cpu_baseline  the CPU oracle, as it stands, timed on a bounded sample of the same workload
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
+
+METRIC = "compressed-momentum step params/sec & HBM GB/s (% of peak), BERT-Large d, 1 GPU"
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(n):
+    """Bytes per parameter per step that the method itself has to move, per call (fp32 state resident in
+    HBM: m_i, g_i, delta_i per worker; sign words 1 bit per element; scales negligible)."""
+    return {
+        "compress": 16.125 * n,                # read m, g, delta; write delta; write 1/8 B of signs; per worker
+        "server_reduce": 8.0 + (n + 1) / 8.0,  # read n sign streams; read+write server error; write signs
+        "apply": 12.125 + 4.0 * n,             # read signs, v, x; write x; write m to n slices
+    }
+
+
+def cpu_baseline(wl, run, g, sample_elems, steps):
+    """Time the CPU oracle (single thread, as it stands) on the first `sample_elems` parameters of the
+    workload: same state bits, copied from HBM, treated as one chunk."""
+    import numpy as np
+    import oracle
+    S, n = sample_elems, wl.n
+    st = oracle.State(S, n, S, run.x[:S].cpu().numpy(), run.m[:, :S].cpu().numpy(), run.v[:S].cpu().numpy())
+    gs = np.ascontiguousarray(g[:, :S].cpu().numpy())
+    st.step(gs, wl.beta, wl.lr, wl.eps)               # page in, untimed
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        st.step(gs, wl.beta, wl.lr, wl.eps)
+    dt = time.perf_counter() - t0
+    return {
+        "value": S * steps / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
+        "sample": "first %d parameters x %d workers of %s as one chunk, %d steps, %.1f s" % (S, n, wl.name, steps, dt),
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="bert-large-flat")
+    ap.add_argument("--mode", choices=["deferred", "eager"], default="deferred")
+    ap.add_argument("--compress-tiles", type=int, default=0)
+    ap.add_argument("--server-tiles", type=int, default=0)
+    ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 22)
+    ap.add_argument("--cpu-steps", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        sys.exit("bench.py: this build runs on ONE GPU (n workers are simulated as n state slices in HBM); "
+                 "--gpus N with N > 1 is not supported")
+
+    import torch
+    from paper_2008_11343_amd import binding as B
+    from paper_2008_11343_amd import workloads as W
+    from paper_2008_11343_amd.runner import DeviceRun
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    wl = {w.name: w for w in W.CONFIGS}[args.workload]
+    dev = "cuda:0"
+    d, n, L = wl.d_pad, wl.n, wl.L
+    log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
+        (wl.name, d, n, L, wl.C, wl.grad, args.mode))
+    st = W.device_state(wl, dev)
+    run = DeviceRun(d, n, L, dev, deferred=(args.mode == "deferred"), state=st)
+    del st
+    if args.compress_tiles or args.server_tiles:
+        B.apms_set_tiles_per_block(run.ctx, args.compress_tiles, args.server_tiles)
+    plan = B.apms_get_plan(run.ctx)
+    g = torch.empty(n, d, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def one_step(step, events=None):
+        if step == 0 or not args.reuse_grad:
+            W.device_grad_(wl, step, g)
+        if events is not None:
+            events[0].record(stream)
+        run.compress(g, wl.beta)
+        if events is not None:
+            events[1].record(stream)
+        run.server_reduce()
+        if events is not None:
+            events[2].record(stream)
+        run.apply(wl.lr, wl.eps)
+        if events is not None:
+            events[3].record(stream)
+
+    for s in range(args.warmup):
+        one_step(s)
+    run.finalize_errors()          # the timed region starts from a state with nothing pending
+    torch.cuda.synchronize()
+    log("warm-up done (%d steps)" % args.warmup)
+
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    fin = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    wall0 = time.perf_counter()
+    for s in range(args.steps):
+        one_step(args.warmup + s, ev[s])
+    fin[0].record(stream)
+    run.finalize_errors()
+    fin[1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - wall0
+
+    t_c = [e[0].elapsed_time(e[1]) for e in ev]
+    t_s = [e[1].elapsed_time(e[2]) for e in ev]
+    t_a = [e[2].elapsed_time(e[3]) for e in ev]
+    t_fin = fin[0].elapsed_time(fin[1])
+    total_ms = sum(t_c) + sum(t_s) + sum(t_a) + t_fin
+    ms_per_step = total_ms / args.steps
+    value = d * args.steps / (total_ms * 1e-3)
+    ab = algorithmic_bytes(n)
+    mean = lambda xs: sum(xs) / len(xs)
+    step_bytes = d * sum(ab.values())
+    compress_ms = mean(t_c)
+    achieved = d * ab["compress"] / (compress_ms * 1e-3) / 1e9
+    log("ms/step %.3f (compress %.3f, server_reduce %.3f, apply %.3f, final finalize %.3f total); wall %.2f s" %
+        (ms_per_step, compress_ms, mean(t_s), mean(t_a), t_fin, wall))
+
+    out = {
+        "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {
+            "workload": "%s: d_pad=%d n=%d chunk=%d" % (wl.name, d, n, L),
+            "error_mode": args.mode, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
+            "worker_params_per_s": value * n,
+            "algorithmic_bytes_per_param_step": sum(ab.values()),
+            "step_GBps_algorithmic": step_bytes / (ms_per_step * 1e-3) / 1e9,
+            "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "ms": {"compress": compress_ms, "server_reduce": mean(t_s), "apply": mean(t_a),
+                   "final_finalize_total": t_fin},
+            "GBps": {"compress": achieved,
+                     "server_reduce": d * ab["server_reduce"] / (mean(t_s) * 1e-3) / 1e9,
+                     "apply": d * ab["apply"] / (mean(t_a) * 1e-3) / 1e9},
+            "plan": {k: plan[k] for k in ("compress_tiles_per_block", "compress_grid", "server_tiles_per_block",
+                                          "server_grid", "apply_grid")},
+            "wall_s_including_input_generation": wall,
+            "device": torch.cuda.get_device_name(0),
+        },
+        "roofline": {
+            "kernel": "compress_kernel (apms_compress)", "bound": "hbm", "achieved": achieved,
+            "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None,
+            "bytes_per_launch_algorithmic": d * ab["compress"],
+            "avg_launch_ms": compress_ms,
+        },
+    }
+    if not args.no_cpu_baseline:
+        log("timing the CPU oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(wl, run, g, min(args.cpu_sample, L), args.cpu_steps)
+    run.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()
