@@ -72,17 +72,20 @@ typedef struct apms_plan {
     int64_t d;
     int32_t n;
     int64_t chunk_elems;
-    int64_t chunks;                 /* C */
-    int32_t tile_elems;             /* elements one workgroup handles per iteration (4096) */
-    int32_t tiles_per_chunk;        /* ceil(chunk_elems / tile_elems); the last tile may be ragged */
+    int64_t chunks;                     /* C */
+    /* A tile is the run of consecutive elements of one chunk a workgroup handles per iteration;
+       a chunk has ceil(chunk_elems / tile) tiles, the last one possibly ragged. */
+    int32_t compress_tile_elems;
     int32_t compress_tiles_per_block;
     int32_t compress_blocks_per_chunk;
-    int64_t compress_grid;          /* n * C * compress_blocks_per_chunk workgroups */
+    int64_t compress_grid;              /* n * C * compress_blocks_per_chunk workgroups */
+    int32_t server_tile_elems;
     int32_t server_tiles_per_block;
     int32_t server_blocks_per_chunk;
-    int64_t server_grid;            /* C * server_blocks_per_chunk */
-    int64_t apply_grid;             /* C * tiles_per_chunk */
-    int64_t scratch_bytes;          /* device memory owned by the context */
+    int64_t server_grid;                /* C * server_blocks_per_chunk */
+    int32_t apply_tile_elems;
+    int64_t apply_grid;                 /* n * C * ceil(chunk_elems / apply_tile_elems) */
+    int64_t scratch_bytes;              /* device memory owned by the context */
 } apms_plan;
 
 /*
@@ -106,8 +109,8 @@ int apms_last_hip_error(const apms_ctx *ctx);
 int apms_get_plan(const apms_ctx *ctx, apms_plan *plan);
 
 /*
- * Tuning knob: how many 4096-element tiles one workgroup streams in
- * apms_compress and in apms_server_reduce (each >= 1; 0 keeps the current
+ * Tuning knob: how many tiles one workgroup streams in apms_compress and in
+ * apms_server_reduce (each >= 1; 0 keeps the current
  * value).  Changes the reduction tree of the norms, hence possibly the last
  * bit of a scale; results stay deterministic for a fixed setting.
  */

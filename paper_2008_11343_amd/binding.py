@@ -31,11 +31,13 @@ EXPORTS = (
 class apms_plan(ctypes.Structure):
     _fields_ = [
         ("d", ctypes.c_int64), ("n", ctypes.c_int32), ("chunk_elems", ctypes.c_int64),
-        ("chunks", ctypes.c_int64), ("tile_elems", ctypes.c_int32), ("tiles_per_chunk", ctypes.c_int32),
-        ("compress_tiles_per_block", ctypes.c_int32), ("compress_blocks_per_chunk", ctypes.c_int32),
-        ("compress_grid", ctypes.c_int64), ("server_tiles_per_block", ctypes.c_int32),
+        ("chunks", ctypes.c_int64),
+        ("compress_tile_elems", ctypes.c_int32), ("compress_tiles_per_block", ctypes.c_int32),
+        ("compress_blocks_per_chunk", ctypes.c_int32), ("compress_grid", ctypes.c_int64),
+        ("server_tile_elems", ctypes.c_int32), ("server_tiles_per_block", ctypes.c_int32),
         ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
-        ("apply_grid", ctypes.c_int64), ("scratch_bytes", ctypes.c_int64),
+        ("apply_tile_elems", ctypes.c_int32), ("apply_grid", ctypes.c_int64),
+        ("scratch_bytes", ctypes.c_int64),
     ]
 
     def as_dict(self):

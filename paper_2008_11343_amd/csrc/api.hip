@@ -18,12 +18,12 @@ struct apms_ctx {
     int64_t L = 0;
     int64_t C = 0;
     int device = APMS_DEVICE_NONE;
-    int32_t tiles_per_chunk = 0;
-    int32_t w_tiles_per_block = 0, w_blocks_per_chunk = 0;    // apms_compress
-    int32_t s_tiles_per_block = 0, s_blocks_per_chunk = 0;    // apms_server_reduce
+    int32_t w_tiles_per_chunk = 0, w_tiles_per_block = 0, w_blocks_per_chunk = 0;    // apms_compress
+    int32_t s_tiles_per_chunk = 0, s_tiles_per_block = 0, s_blocks_per_chunk = 0;    // apms_server_reduce
+    int32_t a_tiles_per_chunk = 0;                                                   // apms_apply
     // device scratch (owned)
-    double* w_partials = nullptr;     // [n*C][tiles_per_chunk] (sized for 1 tile per block)
-    double* s_partials = nullptr;     // [C][tiles_per_chunk]
+    double* w_partials = nullptr;     // [n*C][w_tiles_per_chunk] (sized for 1 tile per block)
+    double* s_partials = nullptr;     // [C][s_tiles_per_chunk]
     float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
     float* s_pending = nullptr;       // [C]
     int64_t scratch_bytes = 0;
@@ -36,8 +36,9 @@ struct apms_ctx {
 
 namespace {
 
-constexpr int32_t kTileElems = 4096;
-constexpr int32_t kDefaultCompressTiles = 8;
+// Measured on MI355X: the worker kernel streams best with one tile per (short-lived) workgroup, the
+// server kernel with a few.
+constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
 
@@ -71,8 +72,8 @@ bool unit_interval(float b) { return b >= 0.0f && b < 1.0f; }   // false for NaN
 int32_t ceil_div32(int64_t a, int64_t b) { return static_cast<int32_t>((a + b - 1) / b); }
 
 void plan_blocks(apms_ctx* c) {
-    c->w_blocks_per_chunk = c->tiles_per_chunk ? ceil_div32(c->tiles_per_chunk, c->w_tiles_per_block) : 0;
-    c->s_blocks_per_chunk = c->tiles_per_chunk ? ceil_div32(c->tiles_per_chunk, c->s_tiles_per_block) : 0;
+    c->w_blocks_per_chunk = c->w_tiles_per_chunk ? ceil_div32(c->w_tiles_per_chunk, c->w_tiles_per_block) : 0;
+    c->s_blocks_per_chunk = c->s_tiles_per_chunk ? ceil_div32(c->s_tiles_per_chunk, c->s_tiles_per_block) : 0;
 }
 
 apms::Geometry geometry(const apms_ctx* c) {
@@ -81,7 +82,6 @@ apms::Geometry geometry(const apms_ctx* c) {
     g.L = c->L;
     g.n = c->n;
     g.C = static_cast<int32_t>(c->C);
-    g.tiles_per_chunk = c->tiles_per_chunk;
     return g;
 }
 
@@ -155,8 +155,10 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     if (n < 1 || d < 0 || (device < 0 && device != APMS_DEVICE_NONE)) return APMS_EINVAL;
     if (chunk_elems < 32 || chunk_elems % 32 != 0 || d % chunk_elems != 0) return APMS_ESHAPE;
     const int64_t C = d / chunk_elems;
-    const int64_t tiles = (chunk_elems + kTileElems - 1) / kTileElems;
-    // every grid must fit a 1-D launch, every (worker, chunk) index an int32
+    // every grid must fit a 1-D launch, every (worker, chunk) index an int32: bound them all by the
+    // finest tiling any kernel uses
+    constexpr int64_t kMinTile = apms::tile_elems(1);
+    const int64_t tiles = (chunk_elems + kMinTile - 1) / kMinTile;
     if (tiles > kMaxGrid || C > kMaxGrid || static_cast<int64_t>(n) * C > kMaxGrid ||
         static_cast<int64_t>(n) * C * tiles > kMaxGrid)
         return APMS_ESHAPE;
@@ -167,13 +169,16 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     c->L = chunk_elems;
     c->C = C;
     c->device = device;
-    c->tiles_per_chunk = C ? static_cast<int32_t>(tiles) : 0;
+    const apms::Geometry geo = geometry(c);
+    c->w_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kCompressTile));
+    c->s_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kServerTile));
+    c->a_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kApplyTile));
     c->w_tiles_per_block = kDefaultCompressTiles;
     c->s_tiles_per_block = kDefaultServerTiles;
     plan_blocks(c);
     const int64_t pairs = static_cast<int64_t>(n) * C;
-    const int64_t wp = pairs * c->tiles_per_chunk * static_cast<int64_t>(sizeof(double));
-    const int64_t sp = C * c->tiles_per_chunk * static_cast<int64_t>(sizeof(double));
+    const int64_t wp = pairs * c->w_tiles_per_chunk * static_cast<int64_t>(sizeof(double));
+    const int64_t sp = C * c->s_tiles_per_chunk * static_cast<int64_t>(sizeof(double));
     const int64_t wq = pairs * static_cast<int64_t>(sizeof(float));
     const int64_t sq = C * static_cast<int64_t>(sizeof(float));
     c->scratch_bytes = wp + sp + wq + sq;
@@ -212,15 +217,16 @@ int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
     plan->n = c->n;
     plan->chunk_elems = c->L;
     plan->chunks = c->C;
-    plan->tile_elems = kTileElems;
-    plan->tiles_per_chunk = c->tiles_per_chunk;
+    plan->compress_tile_elems = apms::kCompressTile;
     plan->compress_tiles_per_block = c->w_tiles_per_block;
     plan->compress_blocks_per_chunk = c->w_blocks_per_chunk;
     plan->compress_grid = static_cast<int64_t>(c->n) * c->C * c->w_blocks_per_chunk;
+    plan->server_tile_elems = apms::kServerTile;
     plan->server_tiles_per_block = c->s_tiles_per_block;
     plan->server_blocks_per_chunk = c->s_blocks_per_chunk;
     plan->server_grid = c->C * c->s_blocks_per_chunk;
-    plan->apply_grid = c->C * c->tiles_per_chunk;
+    plan->apply_tile_elems = apms::kApplyTile;
+    plan->apply_grid = c->C * c->a_tiles_per_chunk * c->n;
     plan->scratch_bytes = c->scratch_bytes;
     return APMS_OK;
 }

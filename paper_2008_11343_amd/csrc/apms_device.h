@@ -1,35 +1,38 @@
 // Device-side building blocks shared by the libapms kernels (gfx950, wave64).
 //
-// Tile layout.  A workgroup of 256 threads (4 waves) handles a tile of 4096
-// consecutive elements of one chunk per iteration; each wave owns 1024 of them
-// (32 sign words).  Inside a wave, lane l and row r (r = 0..3) own the four
-// consecutive elements starting at
-//       128*(l>>3) + 32*r + 4*(l&7)
-// so the eight lanes of a group (l>>3) cover exactly one 32-element sign word
-// per row, and the four rows of a group are four CONSECUTIVE words.  Every
-// 128-bit load instruction of a wave therefore touches eight fully used 128-byte
-// segments, and after an OR across the 8-lane group the group leader stores the
-// four words of its rows as one 128-bit store (128 contiguous bytes per wave).
+// Two ways of laying a tile of kThreads*4*ROWS consecutive elements over a workgroup:
+//
+//  * packing layout (kernels that PRODUCE sign words).  Each wave owns 256*ROWS consecutive
+//    elements; lane l and row r (r < ROWS) own the four consecutive elements starting at
+//        32*ROWS*(l>>3) + 32*r + 4*(l&7)
+//    so the eight lanes of a group (l>>3) cover exactly one 32-element sign word per row, and the
+//    ROWS rows of a group are ROWS CONSECUTIVE words.  Every 128-bit load of a wave touches eight
+//    fully used 128-byte segments; after an OR across the 8-lane group the group leader stores its
+//    ROWS words with one wide store.
+//
+//  * plain layout (kernels that only READ sign words).  Row r of thread t starts at element
+//    r*kThreads*4 + 4*t: every wave access is 1 KB contiguous; the thread's four elements sit at bit
+//    4*(t&7) of word (offset >> 5).
 #pragma once
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include "apms_launch.h"
+
 namespace apms {
 
-constexpr int kThreads = 256;
 constexpr int kWaveSize = 64;
 constexpr int kWaves = kThreads / kWaveSize;
-constexpr int kRows = 4;                              // 128-bit rows per lane per tile
-constexpr int kWaveTile = kWaveSize * 4 * kRows;      // 1024 elements = 32 words
-constexpr int kTile = kWaves * kWaveTile;             // 4096 elements
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
-// Offset of (wave, lane, row 0) inside a tile; row r adds 32*r.
-__device__ __forceinline__ int lane_base_offset(int wave, int lane) {
-    return wave * kWaveTile + (lane >> 3) * 128 + (lane & 7) * 4;
+// Packing layout: offset of (wave, lane, row 0) inside a tile; row r adds 32*r.
+template <int ROWS>
+__device__ __forceinline__ int packing_lane_offset(int wave, int lane) {
+    return wave * (kWaveSize * 4 * ROWS) + (lane >> 3) * (32 * ROWS) + (lane & 7) * 4;
 }
 
 // Streaming (read-once / write-once) 128-bit accesses.
@@ -59,9 +62,34 @@ __device__ __forceinline__ uint32_t or_across_group8(uint32_t v) {
     return v;
 }
 
-// Sum of one binary64 value per thread over the workgroup, in a fixed order:
-// butterfly-free shuffle tree inside each wave (offsets 32,16,...,1), then the
-// four wave sums added in wave order by thread 0.  Valid result in thread 0.
+// The leader of an 8-lane group stores the ROWS consecutive sign words of its rows, starting at
+// word index w0: wide stores when the tile is full and w0 is suitably aligned, else word by word.
+template <int ROWS, bool kFull>
+__device__ __forceinline__ void store_group_words(uint32_t* __restrict__ dst, int64_t w0,
+                                                  const uint32_t (&words)[ROWS], const bool (&ok)[ROWS]) {
+    if constexpr (ROWS % 4 == 0) {
+        if (kFull && (w0 & 3) == 0) {
+#pragma unroll
+            for (int r = 0; r < ROWS; r += 4) {
+                u32x4 pk = {words[r], words[r + 1], words[r + 2], words[r + 3]};
+                *reinterpret_cast<u32x4*>(dst + w0 + r) = pk;
+            }
+            return;
+        }
+    } else if constexpr (ROWS == 2) {
+        if (kFull && (w0 & 1) == 0) {
+            u32x2 pk = {words[0], words[1]};
+            *reinterpret_cast<u32x2*>(dst + w0) = pk;
+            return;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r)
+        if (ok[r]) dst[w0 + r] = words[r];
+}
+
+// Sum of one binary64 value per thread over the workgroup, in a fixed order: shuffle tree inside each
+// wave (offsets 32,16,...,1), then the wave sums added in wave order by thread 0.  Valid in thread 0.
 __device__ __forceinline__ double block_sum_f64(double v, double* lds /* kWaves doubles */) {
 #pragma unroll
     for (int off = kWaveSize / 2; off > 0; off >>= 1)

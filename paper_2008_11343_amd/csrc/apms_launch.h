@@ -7,19 +7,35 @@
 
 namespace apms {
 
-// Geometry shared by the chunked kernels.
+// Workgroup shape: kThreads threads, each owning ROWS 128-bit rows (4 floats) of a tile, so a tile is
+// kThreads * 4 * ROWS consecutive elements of one chunk.  Rows per kernel were chosen by measurement
+// on MI355X (short-lived workgroups with few bytes in flight each stream best).
+constexpr int kThreads = 256;
+constexpr int kCompressRows = 4;
+constexpr int kServerRows = 4;
+constexpr int kApplyRows = 1;
+constexpr int kFinalizeRows = 4;
+
+constexpr int tile_elems(int rows) { return kThreads * 4 * rows; }
+constexpr int kCompressTile = tile_elems(kCompressRows);
+constexpr int kServerTile = tile_elems(kServerRows);
+constexpr int kApplyTile = tile_elems(kApplyRows);
+constexpr int kFinalizeTile = tile_elems(kFinalizeRows);
+
+// Problem geometry shared by the chunked kernels.
 struct Geometry {
-    int64_t d;                 // vector length
-    int64_t L;                 // chunk length (multiple of 32)
-    int32_t n;                 // workers
-    int32_t C;                 // chunks = d / L
-    int32_t tiles_per_chunk;   // ceil(L / 4096)
+    int64_t d;   // vector length
+    int64_t L;   // chunk length (multiple of 32)
+    int32_t n;   // workers
+    int32_t C;   // chunks = d / L
 };
 
-// Worker step over all (worker, chunk) pairs: writes u into werr, sign words into
-// packed, one binary64 partial sum of u^2 per workgroup into partials
-// [n*C][blocks_per_chunk].  prev_scales (nullable, [n*C]) marks werr as holding
-// last step's u (deferred form).
+inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L + tile - 1) / tile : 0; }
+
+// Worker step over all (worker, chunk) pairs: writes u into werr, sign words into packed, one binary64
+// partial sum of u^2 per workgroup into partials [n*C][blocks_per_chunk]; a workgroup streams
+// tiles_per_block consecutive tiles of kCompressTile elements.  prev_scales (nullable, [n*C]) marks werr
+// as holding last step's u (deferred form).
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                            const float* m, const float* g, float* werr, uint32_t* packed,
                            double* partials, const float* prev_scales, float beta, float one_minus_beta,
@@ -35,7 +51,7 @@ hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, con
 hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
                            hipStream_t stream);
 
-// Server step over all chunks.
+// Server step over all chunks (tiles of kServerTile elements).
 hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                                 const uint32_t* packed, const float* scales, float* serr, uint32_t* spacked,
                                 double* partials, const float* prev_scales, float inv_n, hipStream_t stream);

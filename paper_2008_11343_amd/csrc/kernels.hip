@@ -55,11 +55,12 @@ __device__ __forceinline__ void compress_tile(const float* __restrict__ m, const
                                               int64_t chunk_base, int64_t tile_off, int64_t L, int lane_off,
                                               int lane, int wave, float beta, float omb, float prev_scale,
                                               double (&acc)[4]) {
+    constexpr int ROWS = kCompressRows;
     const int64_t off0 = tile_off + lane_off;             // inside the chunk
-    bool ok[kRows];
-    f32x4 vm[kRows], vg[kRows], ve[kRows];
+    bool ok[ROWS];
+    f32x4 vm[ROWS], vg[ROWS], ve[ROWS];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         ok[r] = kFull || (off0 + 32 * r < L);
         if (ok[r]) {
             const int64_t p = chunk_base + off0 + 32 * r;
@@ -68,10 +69,10 @@ __device__ __forceinline__ void compress_tile(const float* __restrict__ m, const
             ve[r] = load_stream(e + p);
         }
     }
-    uint32_t words[kRows];
+    uint32_t words[ROWS];
     const int shift = 4 * (lane & 7);
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         uint32_t nib = 0u;
         if (ok[r]) {
             const f32x4 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
@@ -82,16 +83,9 @@ __device__ __forceinline__ void compress_tile(const float* __restrict__ m, const
         words[r] = or_across_group8(nib);                 // all 64 lanes take part
     }
     if ((lane & 7) == 0) {
-        // first of the four consecutive words this 8-lane group owns
-        const int64_t w0 = (chunk_base + tile_off + wave * kWaveTile + (lane >> 3) * 128) >> 5;
-        if (kFull && (w0 & 3) == 0) {
-            u32x4 pk = {words[0], words[1], words[2], words[3]};
-            *reinterpret_cast<u32x4*>(packed + w0) = pk;
-        } else {
-#pragma unroll
-            for (int r = 0; r < kRows; ++r)
-                if (ok[r]) packed[w0 + r] = words[r];
-        }
+        // first of the ROWS consecutive words this 8-lane group owns
+        const int64_t w0 = (chunk_base + off0) >> 5;
+        store_group_words<ROWS, kFull>(packed, w0, words, ok);
     }
 }
 
@@ -110,13 +104,13 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     const float prev_scale = prev_scales ? prev_scales[pair] : 0.0f;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    const int lane_off = lane_base_offset(wave, lane);
+    const int lane_off = packing_lane_offset<kCompressRows>(wave, lane);
     const int32_t t0 = b * tiles_per_block;
     const int32_t t1 = min(t0 + tiles_per_block, tiles_per_chunk);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int32_t t = t0; t < t1; ++t) {
-        const int64_t tile_off = static_cast<int64_t>(t) * kTile;
-        if (tile_off + kTile <= L)
+        const int64_t tile_off = static_cast<int64_t>(t) * kCompressTile;
+        if (tile_off + kCompressTile <= L)
             compress_tile<true>(m, g, e, packed, chunk_base, tile_off, L, lane_off, lane, wave, beta, omb,
                                 prev_scale, acc);
         else
@@ -157,6 +151,7 @@ __global__ __launch_bounds__(kThreads) void scales_kernel(const double* __restri
 __global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ err,
                                                             const float* __restrict__ scales, int64_t d,
                                                             int64_t L, int32_t C, int32_t tiles_per_chunk) {
+    constexpr int ROWS = kFinalizeRows;
     const int64_t blk = blockIdx.x;
     const int64_t pair = blk / tiles_per_chunk;           // slice * C + chunk
     const int64_t tile = blk - pair * tiles_per_chunk;
@@ -164,23 +159,21 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ 
     const int64_t chunk = pair - slice * C;
     const int64_t chunk_base = slice * d + chunk * L;
     const float s = scales[pair];
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int64_t off0 = tile * kTile + lane_base_offset(wave, lane);
-    f32x4 ve[kRows];
-    bool ok[kRows];
+    const int64_t off0 = tile * kFinalizeTile + threadIdx.x * 4;      // plain layout
+    f32x4 ve[ROWS];
+    bool ok[ROWS];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        ok[r] = off0 + 32 * r < L;
-        if (ok[r]) ve[r] = load_stream(err + chunk_base + off0 + 32 * r);
+    for (int r = 0; r < ROWS; ++r) {
+        ok[r] = off0 + r * (kThreads * 4) < L;
+        if (ok[r]) ve[r] = load_stream(err + chunk_base + off0 + r * (kThreads * 4));
     }
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         if (!ok[r]) continue;
         f32x4 out;
 #pragma unroll
         for (int c = 0; c < 4; ++c) out[c] = read_error(ve[r][c], s);
-        store_stream(err + chunk_base + off0 + 32 * r, out);
+        store_stream(err + chunk_base + off0 + r * (kThreads * 4), out);
     }
 }
 
@@ -195,17 +188,18 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
                                             uint32_t* __restrict__ spacked, int64_t d, int64_t L, int32_t C,
                                             int32_t n, int64_t chunk, int64_t tile_off, int lane_off, int lane,
                                             int wave, float inv_n, float prev_scale, double (&acc)[4]) {
+    constexpr int ROWS = kServerRows;
     const int64_t chunk_base = chunk * L;                 // inside one [d] vector
     const int64_t off0 = tile_off + lane_off;
     const int shift = 4 * (lane & 7);
-    // first of this group's four consecutive words, inside one worker's [d/32] words
-    const int64_t w0 = (chunk_base + tile_off + wave * kWaveTile + (lane >> 3) * 128) >> 5;
+    // first of this group's ROWS consecutive words, inside one worker's [d/32] words
+    const int64_t w0 = (chunk_base + off0) >> 5;
     const int64_t words_per_worker = d >> 5;
-    bool ok[kRows];
-    f32x4 ve[kRows];
-    f32x4 sum[kRows];
+    bool ok[ROWS];
+    f32x4 ve[ROWS];
+    f32x4 sum[ROWS];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         ok[r] = kFull || (off0 + 32 * r < L);
         if (ok[r]) ve[r] = load_stream(serr + chunk_base + off0 + 32 * r);
         sum[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
@@ -214,20 +208,20 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
     for (int32_t i = 0; i < n; ++i) {
         const float s = scales[static_cast<int64_t>(i) * C + chunk];
         const uint32_t* wp = packed + i * words_per_worker + w0;
-        uint32_t w[kRows];
+        uint32_t w[ROWS];
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) w[r] = ok[r] ? wp[r] : 0u;
+        for (int r = 0; r < ROWS; ++r) w[r] = ok[r] ? wp[r] : 0u;
 #pragma unroll
-        for (int r = 0; r < kRows; ++r) {
+        for (int r = 0; r < ROWS; ++r) {
             const uint32_t nib = w[r] >> shift;
 #pragma unroll
             for (int c = 0; c < 4; ++c)
                 sum[r][c] = sum[r][c] + signed_scale((nib >> c) & 1u, s);
         }
     }
-    uint32_t words[kRows];
+    uint32_t words[ROWS];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         uint32_t nib = 0u;
         if (ok[r]) {
             f32x4 ubar;
@@ -242,16 +236,7 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
         }
         words[r] = or_across_group8(nib);
     }
-    if ((lane & 7) == 0) {
-        if (kFull && (w0 & 3) == 0) {
-            u32x4 pk = {words[0], words[1], words[2], words[3]};
-            *reinterpret_cast<u32x4*>(spacked + w0) = pk;
-        } else {
-#pragma unroll
-            for (int r = 0; r < kRows; ++r)
-                if (ok[r]) spacked[w0 + r] = words[r];
-        }
-    }
+    if ((lane & 7) == 0) store_group_words<ROWS, kFull>(spacked, w0, words, ok);
 }
 
 __global__ __launch_bounds__(kThreads) void server_kernel(
@@ -266,13 +251,13 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
     const float prev_scale = prev_scales ? prev_scales[chunk] : 0.0f;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    const int lane_off = lane_base_offset(wave, lane);
+    const int lane_off = packing_lane_offset<kServerRows>(wave, lane);
     const int32_t t0 = b * tiles_per_block;
     const int32_t t1 = min(t0 + tiles_per_block, tiles_per_chunk);
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int32_t t = t0; t < t1; ++t) {
-        const int64_t tile_off = static_cast<int64_t>(t) * kTile;
-        if (tile_off + kTile <= L)
+        const int64_t tile_off = static_cast<int64_t>(t) * kServerTile;
+        if (tile_off + kServerTile <= L)
             server_tile<true>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
                               inv_n, prev_scale, acc);
         else
@@ -288,51 +273,63 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
 // Gather + model update (Algorithm 1 lines 10-11).
 // ------------------------------------------------------------------------
 
+// One workgroup = one tile of ONE worker's momentum slice, slice-major, so the n slices are written as
+// one long contiguous fill of m[n][d]; the workgroups of slice 0 also take the model step for their tile.
 __global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restrict__ spacked,
                                                          const float* __restrict__ sscales,
                                                          const float* __restrict__ v, float* __restrict__ x,
                                                          float* __restrict__ m, int64_t d, int64_t L,
-                                                         int32_t n, int32_t tiles_per_chunk, float lr,
-                                                         float eps) {
+                                                         int64_t tiles_per_slice, int32_t tiles_per_chunk,
+                                                         float lr, float eps) {
     const int64_t blk = blockIdx.x;
-    const int64_t chunk = blk / tiles_per_chunk;
-    const int64_t tile = blk - chunk * tiles_per_chunk;
+    const int64_t slice = blk / tiles_per_slice;
+    const int64_t ct = blk - slice * tiles_per_slice;     // chunk * tiles_per_chunk + tile
+    const int64_t chunk = ct / tiles_per_chunk;
+    const int64_t tile = ct - chunk * tiles_per_chunk;
+    constexpr int ROWS = kApplyRows;
+    constexpr int kRowStride = kThreads * 4;              // plain layout
     const int64_t chunk_base = chunk * L;
     const float s = sscales[chunk];
-    const int lane = threadIdx.x & (kWaveSize - 1);
-    const int wave = threadIdx.x >> 6;
-    const int64_t off0 = tile * kTile + lane_base_offset(wave, lane);
-    const int shift = 4 * (lane & 7);
-    bool ok[kRows];
-    f32x4 vv[kRows], vx[kRows];
-    uint32_t w[kRows];
+    const int64_t off0 = tile * kApplyTile + threadIdx.x * 4;
+    const int shift = 4 * (threadIdx.x & 7);
+    const bool model_step = (slice == 0);
+    float* __restrict__ mslice = m + slice * d;
+    bool ok[ROWS];
+    f32x4 vv[ROWS], vx[ROWS];
+    uint32_t w[ROWS];
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
-        ok[r] = off0 + 32 * r < L;
+    for (int r = 0; r < ROWS; ++r) {
+        ok[r] = off0 + r * kRowStride < L;
         if (ok[r]) {
-            const int64_t p = chunk_base + off0 + 32 * r;
+            const int64_t p = chunk_base + off0 + r * kRowStride;
             w[r] = spacked[p >> 5];
-            vv[r] = load_stream(v + p);
-            vx[r] = load_stream(x + p);
+            if (model_step) {
+                vv[r] = load_stream(v + p);
+                vx[r] = load_stream(x + p);
+            }
         }
     }
 #pragma unroll
-    for (int r = 0; r < kRows; ++r) {
+    for (int r = 0; r < ROWS; ++r) {
         if (!ok[r]) continue;
-        const int64_t p = chunk_base + off0 + 32 * r;
+        const int64_t p = chunk_base + off0 + r * kRowStride;
         const uint32_t nib = w[r] >> shift;
-        f32x4 mom, xn;
+        f32x4 mom;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            mom[c] = signed_scale((nib >> c) & 1u, s);       // decoded server message
-            const float root = sqrtf(vv[r][c]);
-            const float denom = root + eps;
-            const float ratio = mom[c] / denom;
-            const float step = lr * ratio;
-            xn[c] = vx[r][c] - step;
+        for (int c = 0; c < 4; ++c) mom[c] = signed_scale((nib >> c) & 1u, s);   // decoded server message
+        store_stream(mslice + p, mom);
+        if (model_step) {
+            f32x4 xn;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float root = sqrtf(vv[r][c]);
+                const float denom = root + eps;
+                const float ratio = mom[c] / denom;
+                const float step = lr * ratio;
+                xn[c] = vx[r][c] - step;
+            }
+            store_stream(x + p, xn);
         }
-        store_stream(x + p, xn);
-        for (int32_t i = 0; i < n; ++i) store_stream(m + static_cast<int64_t>(i) * d + p, mom);
     }
 }
 
@@ -416,8 +413,9 @@ hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t
     const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, m, g,
-                       werr, packed, partials, prev_scales, geo.d, geo.L, geo.C, geo.tiles_per_chunk,
-                       tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
+                       werr, packed, partials, prev_scales, geo.d, geo.L, geo.C,
+                       static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile)), tiles_per_block,
+                       blocks_per_chunk, beta, one_minus_beta);
     return hipGetLastError();
 }
 
@@ -431,10 +429,11 @@ hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, con
 
 hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
                            hipStream_t stream) {
-    const int64_t grid = static_cast<int64_t>(slices) * geo.C * geo.tiles_per_chunk;
+    const int64_t tpc = tiles_per_chunk(geo, kFinalizeTile);
+    const int64_t grid = static_cast<int64_t>(slices) * geo.C * tpc;
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(finalize_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, err,
-                       scales, geo.d, geo.L, geo.C, geo.tiles_per_chunk);
+                       scales, geo.d, geo.L, geo.C, static_cast<int32_t>(tpc));
     return hipGetLastError();
 }
 
@@ -445,16 +444,19 @@ hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, in
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(server_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, packed,
                        scales, serr, spacked, partials, prev_scales, geo.d, geo.L, geo.C, geo.n,
-                       geo.tiles_per_chunk, tiles_per_block, blocks_per_chunk, inv_n);
+                       static_cast<int32_t>(tiles_per_chunk(geo, kServerTile)), tiles_per_block,
+                       blocks_per_chunk, inv_n);
     return hipGetLastError();
 }
 
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
                         float* x, float* m, float lr, float eps, hipStream_t stream) {
-    const int64_t grid = static_cast<int64_t>(geo.C) * geo.tiles_per_chunk;
+    const int64_t tpc = tiles_per_chunk(geo, kApplyTile);
+    const int64_t tiles_per_slice = static_cast<int64_t>(geo.C) * tpc;
+    const int64_t grid = tiles_per_slice * geo.n;
     if (grid <= 0) return hipSuccess;
     hipLaunchKernelGGL(apply_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, spacked,
-                       sscales, v, x, m, geo.d, geo.L, geo.n, geo.tiles_per_chunk, lr, eps);
+                       sscales, v, x, m, geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
     return hipGetLastError();
 }
 
