@@ -26,6 +26,12 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 
+# HBM bytes per launch of the compress kernel measured with rocprofv3 PMC counters (FETCH_SIZE and
+# WRITE_SIZE runs, each scaled by what the counter reads for a plain copy of known size); the summary
+# with the commands is profiles/bench_bert-large-flat_hbm_traffic.txt.  Reported only for the workload
+# and error mode it was measured on.
+MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 87.763e9}
+
 METRIC = "compressed-momentum step params/sec & HBM GB/s (% of peak), BERT-Large d, 1 GPU"
 
 
@@ -73,6 +79,9 @@ def main():
     ap.add_argument("--server-tiles", type=int, default=0)
     ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of n*d floats (a kernel of known HBM traffic, for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 22)
     ap.add_argument("--cpu-steps", type=int, default=4)
     args = ap.parse_args()
@@ -116,6 +125,12 @@ def main():
         if events is not None:
             events[3].record(stream)
 
+    if args.calibration_copy:
+        W.device_grad_(wl, 0, g)
+        run.werr.copy_(g)
+        run.werr.zero_()
+        torch.cuda.synchronize()
+        log("calibration copy done: %d bytes read, %d bytes written" % (4 * n * d, 4 * n * d))
     for s in range(args.warmup):
         one_step(s)
     run.finalize_errors()          # the timed region starts from a state with nothing pending
@@ -173,7 +188,8 @@ def main():
         "roofline": {
             "kernel": "compress_kernel (apms_compress)", "bound": "hbm", "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": None,
+            "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)),
+            "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/bench_bert-large-flat_hbm_traffic.txt",
             "bytes_per_launch_algorithmic": d * ab["compress"],
             "avg_launch_ms": compress_ms,
         },
