@@ -1,0 +1,97 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
+(deferred-error mode, default tiling): chunks are independent parameter-server problems
+(supplement, first paragraph of 'Proof to the Updating Form'), so the oracle follows a sample of
+whole chunks (first, last, one seeded pick) through the steps on the very bits the GPU consumes,
+and whole-buffer properties are checked on the device.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2008_11343_amd import workloads as W
+from paper_2008_11343_amd.runner import DeviceRun
+
+pytestmark = pytest.mark.gpu
+
+RTOL, ATOL = 1e-5, 1e-7
+DEV = "cuda:0"
+
+
+def say(msg):
+    print("[fullsize] " + msg, flush=True)
+
+
+def words(t):
+    return t.cpu().numpy().view(np.uint32)
+
+
+def check_chunk(run, ost, k, L, tag, errors):
+    n = run.n
+    sl = slice(k * L, (k + 1) * L)
+    wsl = slice(k * L // 32, (k + 1) * L // 32)
+    gp, op = words(run.packed[:, wsl]), ost.packed
+    bad = int((gp != op).sum())
+    assert bad == 0, "%s: %d worker sign words differ" % (tag, bad)
+    bad = int((words(run.spacked[wsl]) != ost.spacked).sum())
+    assert bad == 0, "%s: %d server sign words differ" % (tag, bad)
+    np.testing.assert_allclose(run.scales[:, k].cpu().numpy(), ost.scales[:, 0], rtol=RTOL, atol=ATOL, err_msg=tag)
+    np.testing.assert_allclose(run.sscales[k].item(), ost.sscales[0], rtol=RTOL, atol=ATOL, err_msg=tag)
+    np.testing.assert_allclose(run.x[sl].cpu().numpy(), ost.x, rtol=RTOL, atol=ATOL, err_msg=tag + " x")
+    for i in (0, n - 1):
+        np.testing.assert_allclose(run.m[i, sl].cpu().numpy(), ost.m[i], rtol=RTOL, atol=ATOL, err_msg=tag + " m")
+    if errors:
+        for i in range(n):
+            np.testing.assert_allclose(run.werr[i, sl].cpu().numpy(), ost.werr[i], rtol=RTOL, atol=ATOL,
+                                       err_msg=tag + " worker_err[%d]" % i)
+        np.testing.assert_allclose(run.serr[sl].cpu().numpy(), ost.serr, rtol=RTOL, atol=ATOL,
+                                   err_msg=tag + " server_err")
+
+
+def whole_buffer_properties(run, tag):
+    """Holds at any size: every worker's momentum is the same copy of +-sscale[chunk], with the sign the
+    server's sign word carries (Algorithm 1 line 10)."""
+    d, n, L, C = run.d, run.n, run.L, run.C
+    shifts = torch.arange(32, device=DEV, dtype=torch.int32)
+    step = 1 << 24
+    for lo in range(0, d, step):
+        hi = min(d, lo + step)
+        w = run.spacked[lo // 32:hi // 32]
+        bits = ((w.unsqueeze(1) >> shifts) & 1).reshape(-1).bool()
+        chunk_of = torch.arange(lo, hi, device=DEV) // L
+        s = run.sscales[chunk_of]
+        expect = torch.where(bits, s, -s)
+        for i in range(n):
+            assert torch.equal(run.m[i, lo:hi], expect), "%s: momentum slice %d is not the decoded server message" % (tag, i)
+
+
+@pytest.mark.parametrize("wl,steps", [(W.BERT_BASE, 3), (W.BERT_LARGE, 2), (W.WORKER_SCALING, 2)],
+                         ids=lambda v: v.name if hasattr(v, "name") else str(v))
+def test_sampled_chunks_at_full_size(wl, steps):
+    d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    say("%s: d_pad=%d n=%d chunk=%d, %d steps" % (wl.name, d, n, L, steps))
+    st = W.device_state(wl, DEV)
+    run = DeviceRun(d, n, L, DEV, deferred=True, state=st)
+    del st
+    rng = np.random.default_rng(W.BASE_SEED + wl.index)
+    picks = sorted({0, C - 1, int(rng.integers(1, C - 1))})
+    osts = {}
+    for k in picks:
+        sl = slice(k * L, (k + 1) * L)
+        osts[k] = oracle.State(L, n, L, run.x[sl].cpu().numpy(), run.m[:, sl].cpu().numpy(), run.v[sl].cpu().numpy())
+    g = torch.empty(n, d, dtype=torch.float32, device=DEV)
+    for step in range(steps):
+        W.device_grad_(wl, step, g)
+        run.step(g, wl.beta, wl.lr, wl.eps)
+        last = step == steps - 1
+        if last:
+            run.finalize_errors()
+        torch.cuda.synchronize()
+        for k in picks:
+            say("%s step %d: oracle on chunk %d" % (wl.name, step, k))
+            gk = np.ascontiguousarray(g[:, k * L:(k + 1) * L].cpu().numpy())
+            osts[k].step(gk, wl.beta, wl.lr, wl.eps)
+            check_chunk(run, osts[k], k, L, "%s step %d chunk %d" % (wl.name, step, k), errors=last)
+    say("%s: whole-buffer properties" % wl.name)
+    whole_buffer_properties(run, wl.name)
+    run.close()
