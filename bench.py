@@ -82,8 +82,8 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of n*d floats (a kernel of known HBM traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
-    ap.add_argument("--cpu-sample", type=int, default=1 << 22)
-    ap.add_argument("--cpu-steps", type=int, default=4)
+    ap.add_argument("--cpu-sample", type=int, default=1 << 23)
+    ap.add_argument("--cpu-steps", type=int, default=8)
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on ONE GPU (n workers are simulated as n state slices in HBM); "
