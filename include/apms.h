@@ -86,6 +86,7 @@ typedef struct apms_plan {
     int32_t apply_tile_elems;
     int64_t apply_grid;                 /* n * C * ceil(chunk_elems / apply_tile_elems) */
     int64_t scratch_bytes;              /* device memory owned by the context */
+    int32_t occupancy_pad[4];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_* */
 } apms_plan;
 
 /*
@@ -115,6 +116,18 @@ int apms_get_plan(const apms_ctx *ctx, apms_plan *plan);
  * bit of a scale; results stay deterministic for a fixed setting.
  */
 int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t server_tiles);
+
+/*
+ * Tuning knob: ask for lds_bytes of dynamic LDS per workgroup of one kernel without using it.  LDS is
+ * what caps the number of workgroups a compute unit holds at once at no other cost, and these
+ * streaming kernels reach their best HBM efficiency with few workgroups in flight per CU.
+ * 0 <= lds_bytes <= 160 KB - 256.  Does not change any result.
+ */
+#define APMS_KERNEL_COMPRESS 0
+#define APMS_KERNEL_SERVER 1
+#define APMS_KERNEL_APPLY 2
+#define APMS_KERNEL_FINALIZE 3
+int apms_set_occupancy_pad(apms_ctx *ctx, int kernel, int32_t lds_bytes);
 
 /*
  * Error-buffer mode (default APMS_ERRORS_EAGER).

@@ -20,10 +20,11 @@ APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS
 APMS_DEVICE_NONE = -1
 APMS_ERRORS_EAGER = 0
 APMS_ERRORS_DEFERRED = 1
+APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE = 0, 1, 2, 3
 
 EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
-    "apms_set_tiles_per_block", "apms_set_error_mode", "apms_finalize_errors", "apms_warmup_step",
+    "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_error_mode", "apms_finalize_errors", "apms_warmup_step",
     "apms_freeze", "apms_compress", "apms_server_reduce", "apms_apply",
 )
 
@@ -37,11 +38,13 @@ class apms_plan(ctypes.Structure):
         ("server_tile_elems", ctypes.c_int32), ("server_tiles_per_block", ctypes.c_int32),
         ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
         ("apply_tile_elems", ctypes.c_int32), ("apply_grid", ctypes.c_int64),
-        ("scratch_bytes", ctypes.c_int64),
+        ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 4),
     ]
 
     def as_dict(self):
-        return {name: getattr(self, name) for name, _ in self._fields_}
+        out = {name: getattr(self, name) for name, _ in self._fields_}
+        out["occupancy_pad"] = list(self.occupancy_pad)
+        return out
 
 
 class ApmsError(RuntimeError):
@@ -77,6 +80,7 @@ def load():
         "apms_last_hip_error": (ci, [vp]),
         "apms_get_plan": (ci, [vp, ctypes.POINTER(apms_plan)]),
         "apms_set_tiles_per_block": (ci, [vp, i32, i32]),
+        "apms_set_occupancy_pad": (ci, [vp, ci, i32]),
         "apms_set_error_mode": (ci, [vp, ci]),
         "apms_finalize_errors": (ci, [vp, vp, vp, vp]),
         "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
@@ -145,6 +149,10 @@ def apms_get_plan(ctx) -> dict:
 
 def apms_set_tiles_per_block(ctx, compress_tiles: int = 0, server_tiles: int = 0):
     _check(ctx, load().apms_set_tiles_per_block(ctx, compress_tiles, server_tiles), "apms_set_tiles_per_block")
+
+
+def apms_set_occupancy_pad(ctx, kernel: int, lds_bytes: int):
+    _check(ctx, load().apms_set_occupancy_pad(ctx, kernel, lds_bytes), "apms_set_occupancy_pad")
 
 
 def apms_set_error_mode(ctx, mode: int):

@@ -21,6 +21,7 @@ struct apms_ctx {
     int32_t w_tiles_per_chunk = 0, w_tiles_per_block = 0, w_blocks_per_chunk = 0;    // apms_compress
     int32_t s_tiles_per_chunk = 0, s_tiles_per_block = 0, s_blocks_per_chunk = 0;    // apms_server_reduce
     int32_t a_tiles_per_chunk = 0;                                                   // apms_apply
+    int32_t lds_pad[4] = {0, 0, 0, 0};          // per APMS_KERNEL_*: unused dynamic LDS that caps occupancy
     // device scratch (owned)
     double* w_partials = nullptr;     // [n*C][w_tiles_per_chunk] (sized for 1 tile per block)
     double* s_partials = nullptr;     // [C][s_tiles_per_chunk]
@@ -41,6 +42,9 @@ namespace {
 constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
+// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize): measured on MI355X,
+// these streams are fastest with 2 workgroups (8 waves) per CU.
+constexpr int32_t kDefaultLdsPad[4] = {64 * 1024, 0, 0, 0};
 
 struct Range {
     const void* p;
@@ -173,6 +177,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     c->w_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kCompressTile));
     c->s_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kServerTile));
     c->a_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kApplyTile));
+    for (int k = 0; k < 4; ++k) c->lds_pad[k] = kDefaultLdsPad[k];
     c->w_tiles_per_block = kDefaultCompressTiles;
     c->s_tiles_per_block = kDefaultServerTiles;
     plan_blocks(c);
@@ -185,6 +190,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     if (device != APMS_DEVICE_NONE && d > 0) {
         DeviceScope scope(device);
         hipError_t e = scope.err;
+        if (e == hipSuccess) e = apms::enable_large_lds_pads();
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_partials), wp);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_partials), sp);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
@@ -228,6 +234,7 @@ int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
     plan->apply_tile_elems = apms::kApplyTile;
     plan->apply_grid = c->C * c->a_tiles_per_chunk * c->n;
     plan->scratch_bytes = c->scratch_bytes;
+    for (int k = 0; k < 4; ++k) plan->occupancy_pad[k] = c->lds_pad[k];
     return APMS_OK;
 }
 
@@ -236,6 +243,12 @@ int apms_set_tiles_per_block(apms_ctx* c, int32_t compress_tiles, int32_t server
     if (compress_tiles) c->w_tiles_per_block = compress_tiles;
     if (server_tiles) c->s_tiles_per_block = server_tiles;
     plan_blocks(c);
+    return APMS_OK;
+}
+
+int apms_set_occupancy_pad(apms_ctx* c, int kernel, int32_t lds_bytes) {
+    if (!c || kernel < 0 || kernel > 3 || lds_bytes < 0 || lds_bytes > apms::kMaxLdsPad) return APMS_EINVAL;
+    c->lds_pad[kernel] = lds_bytes;
     return APMS_OK;
 }
 
@@ -255,12 +268,12 @@ int apms_finalize_errors(apms_ctx* c, float* worker_err, float* server_err, void
     hipStream_t s = static_cast<hipStream_t>(stream);
     const apms::Geometry geo = geometry(c);
     if (worker_err && c->pending_werr == worker_err) {
-        hipError_t e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, s);
+        hipError_t e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_werr = nullptr;
     }
     if (server_err && c->pending_serr == server_err) {
-        hipError_t e = apms::launch_finalize(geo, 1, server_err, c->s_pending, s);
+        hipError_t e = apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_serr = nullptr;
     }
@@ -319,7 +332,8 @@ int apms_compress(apms_ctx* c, const float* m, const float* g, float* worker_err
     const apms::Geometry geo = geometry(c);
     const float* prev = c->pending_werr ? c->w_pending : nullptr;
     hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, worker_err,
-                                         packed, c->w_partials, prev, beta, 1.0f - beta, s);
+                                         packed, c->w_partials, prev, beta, 1.0f - beta,
+                                         c->lds_pad[APMS_KERNEL_COMPRESS], s);
     if (e != hipSuccess) return hip_fail(c, e);
     // from here on the buffer holds u and the context holds its scales
     c->pending_werr = worker_err;
@@ -327,7 +341,7 @@ int apms_compress(apms_ctx* c, const float* m, const float* g, float* worker_err
                             c->w_pending, s);
     if (e != hipSuccess) return hip_fail(c, e);
     if (c->error_mode == APMS_ERRORS_EAGER) {
-        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, s);
+        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_werr = nullptr;
     }
@@ -351,13 +365,14 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     const float* prev = c->pending_serr ? c->s_pending : nullptr;
     const float inv_n = 1.0f / static_cast<float>(c->n);
     hipError_t e = apms::launch_server_reduce(geo, c->s_tiles_per_block, c->s_blocks_per_chunk, packed, scales,
-                                              server_err, spacked, c->s_partials, prev, inv_n, s);
+                                              server_err, spacked, c->s_partials, prev, inv_n,
+                                              c->lds_pad[APMS_KERNEL_SERVER], s);
     if (e != hipSuccess) return hip_fail(c, e);
     c->pending_serr = server_err;
     e = apms::launch_scales(c->C, c->s_blocks_per_chunk, c->L, c->s_partials, sscales, c->s_pending, s);
     if (e != hipSuccess) return hip_fail(c, e);
     if (c->error_mode == APMS_ERRORS_EAGER) {
-        e = apms::launch_finalize(geo, 1, server_err, c->s_pending, s);
+        e = apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_serr = nullptr;
     }
@@ -376,7 +391,7 @@ int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
     hipError_t e = apms::launch_apply(geometry(c), spacked, sscales, v, x, m, lr, eps,
-                                      static_cast<hipStream_t>(stream));
+                                      c->lds_pad[APMS_KERNEL_APPLY], static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 

@@ -14,7 +14,7 @@ constexpr int kThreads = 256;
 constexpr int kCompressRows = 4;
 constexpr int kServerRows = 4;
 constexpr int kApplyRows = 1;
-constexpr int kFinalizeRows = 4;
+constexpr int kFinalizeRows = 1;
 
 constexpr int tile_elems(int rows) { return kThreads * 4 * rows; }
 constexpr int kCompressTile = tile_elems(kCompressRows);
@@ -30,6 +30,14 @@ struct Geometry {
     int32_t C;   // chunks = d / L
 };
 
+// Dynamic LDS a launch asks for WITHOUT using it: LDS is the one resource that caps how many workgroups
+// a CU holds at once without costing anything else, and on MI355X these streaming kernels reach their
+// best HBM efficiency with few workgroups in flight per CU.
+constexpr int32_t kMaxLdsPad = 160 * 1024 - 256;
+
+// Raise each kernel's dynamic-LDS limit so that pads above 64 KB can be launched (once per process).
+hipError_t enable_large_lds_pads();
+
 inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L + tile - 1) / tile : 0; }
 
 // Worker step over all (worker, chunk) pairs: writes u into werr, sign words into packed, one binary64
@@ -39,7 +47,7 @@ inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L 
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                            const float* m, const float* g, float* werr, uint32_t* packed,
                            double* partials, const float* prev_scales, float beta, float one_minus_beta,
-                           hipStream_t stream);
+                           int32_t lds_pad, hipStream_t stream);
 
 // Reduce partials [pairs][blocks_per_chunk] in fixed order, scale = fl32(sqrt(S / L));
 // writes scales_out[pair] and pending_out[pair] (either may be null).
@@ -49,16 +57,17 @@ hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, con
 // err[p][j] <- err[p][j] - (err >= 0 ? +s_p : -s_p) for pairs p = slice*C + chunk,
 // slices = n (worker errors) or 1 (server error).
 hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
-                           hipStream_t stream);
+                           int32_t lds_pad, hipStream_t stream);
 
 // Server step over all chunks (tiles of kServerTile elements).
 hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                                 const uint32_t* packed, const float* scales, float* serr, uint32_t* spacked,
-                                double* partials, const float* prev_scales, float inv_n, hipStream_t stream);
+                                double* partials, const float* prev_scales, float inv_n, int32_t lds_pad,
+                                hipStream_t stream);
 
 // Gather + model update.
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
-                        float* x, float* m, float lr, float eps, hipStream_t stream);
+                        float* x, float* m, float lr, float eps, int32_t lds_pad, hipStream_t stream);
 
 // Adam warm-up step on the averaged gradient.
 hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,

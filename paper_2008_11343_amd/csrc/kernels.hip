@@ -407,12 +407,23 @@ inline uint32_t stride_grid(int64_t d) {
 
 }  // namespace
 
+hipError_t enable_large_lds_pads() {
+    const void* kernels[] = {reinterpret_cast<const void*>(compress_kernel), reinterpret_cast<const void*>(server_kernel),
+                             reinterpret_cast<const void*>(apply_kernel), reinterpret_cast<const void*>(finalize_kernel)};
+    for (const void* k : kernels) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                            const float* m, const float* g, float* werr, uint32_t* packed, double* partials,
-                           const float* prev_scales, float beta, float one_minus_beta, hipStream_t stream) {
+                           const float* prev_scales, float beta, float one_minus_beta, int32_t lds_pad,
+                           hipStream_t stream) {
     const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, m, g,
+    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, m, g,
                        werr, packed, partials, prev_scales, geo.d, geo.L, geo.C,
                        static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile)), tiles_per_block,
                        blocks_per_chunk, beta, one_minus_beta);
@@ -428,21 +439,22 @@ hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, con
 }
 
 hipError_t launch_finalize(const Geometry& geo, int32_t slices, float* err, const float* scales,
-                           hipStream_t stream) {
+                           int32_t lds_pad, hipStream_t stream) {
     const int64_t tpc = tiles_per_chunk(geo, kFinalizeTile);
     const int64_t grid = static_cast<int64_t>(slices) * geo.C * tpc;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(finalize_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, err,
+    hipLaunchKernelGGL(finalize_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, err,
                        scales, geo.d, geo.L, geo.C, static_cast<int32_t>(tpc));
     return hipGetLastError();
 }
 
 hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
                                 const uint32_t* packed, const float* scales, float* serr, uint32_t* spacked,
-                                double* partials, const float* prev_scales, float inv_n, hipStream_t stream) {
+                                double* partials, const float* prev_scales, float inv_n, int32_t lds_pad,
+                                hipStream_t stream) {
     const int64_t grid = static_cast<int64_t>(geo.C) * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(server_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, packed,
+    hipLaunchKernelGGL(server_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, packed,
                        scales, serr, spacked, partials, prev_scales, geo.d, geo.L, geo.C, geo.n,
                        static_cast<int32_t>(tiles_per_chunk(geo, kServerTile)), tiles_per_block,
                        blocks_per_chunk, inv_n);
@@ -450,12 +462,12 @@ hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, in
 }
 
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
-                        float* x, float* m, float lr, float eps, hipStream_t stream) {
+                        float* x, float* m, float lr, float eps, int32_t lds_pad, hipStream_t stream) {
     const int64_t tpc = tiles_per_chunk(geo, kApplyTile);
     const int64_t tiles_per_slice = static_cast<int64_t>(geo.C) * tpc;
     const int64_t grid = tiles_per_slice * geo.n;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), 0, stream, spacked,
+    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, spacked,
                        sscales, v, x, m, geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
     return hipGetLastError();
 }

@@ -126,6 +126,10 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_apply, ctx, *good, float("nan"), 1e-8) == B.APMS_EINVAL
     assert status_of(B.apms_set_error_mode, ctx, 7) == B.APMS_EINVAL
     assert status_of(B.apms_set_tiles_per_block, ctx, -1, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, 4, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 200 * 1024) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 4096) == B.APMS_OK
+    assert B.apms_get_plan(ctx)["occupancy_pad"][B.APMS_KERNEL_APPLY] == 4096
 
 
 def test_empty_problem_is_ok_without_a_device():
