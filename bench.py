@@ -4,8 +4,9 @@
 A "step" is one pass of the whole hot path (apms_compress -> apms_server_reduce -> apms_apply,
 Algorithm 1 lines 6-11) over one batch of fresh synthetic gradients for all n simulated workers.
 Inputs are generated in HBM before the timed region of each step; the timed region is bracketed by
-HIP events on the stream the kernels are launched on.  In deferred-error mode the final
-apms_finalize_errors (which completes the last step's error update) is inside the timed total.
+HIP events on the stream the kernels are launched on.  In the deferred modes the timed region starts
+with nothing pending and the closing apms_finalize (which completes the last step's error update and
+momentum gather) is inside the timed total.
 
 Prints ONE JSON line on stdout (progress goes to stderr):
   value      parameters per second of the whole job (d_pad * steps / timed seconds)
@@ -30,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, each scaled by what the counter reads for a plain copy of known size); the summary
 # with the commands is profiles/bench_bert-large-flat_hbm_traffic.txt.  Reported only for the workload
 # and error mode it was measured on.
-MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 87.763e9}
+MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred-errors"): 87.763e9}
 
 METRIC = "compressed-momentum step params/sec & HBM GB/s (% of peak), BERT-Large d, 1 GPU"
 
@@ -39,14 +40,23 @@ def log(msg):
     print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
-def algorithmic_bytes(n):
-    """Bytes per parameter per step that the method itself has to move, per call (fp32 state resident in
-    HBM: m_i, g_i, delta_i per worker; sign words 1 bit per element; scales negligible)."""
-    return {
-        "compress": 16.125 * n,                # read m, g, delta; write delta; write 1/8 B of signs; per worker
-        "server_reduce": 8.0 + (n + 1) / 8.0,  # read n sign streams; read+write server error; write signs
-        "apply": 12.125 + 4.0 * n,             # read signs, v, x; write x; write m to n slices
-    }
+def call_bytes(n, gather_deferred=False):
+    """Bytes per parameter per step each CALL has to move (fp32 state resident in HBM: m_i, g_i, delta_i
+    per worker; sign words 1 bit per element; scales negligible).
+
+    Eager gather (the accounting the workload was specified with, 344.25 B at n = 16):
+      apms_compress       16.125 n        read m, g, delta; write delta; write n/8 B of signs
+      apms_server_reduce  8 + (n+1)/8     read n sign streams; read + write server error; write signs
+      apms_apply          12.125 + 4 n    read signs, v, x; write x; write m to n slices
+    Deferred gather (apms_compress carries out the previous step's gather and uses the decoded momentum
+    instead of reading m back, 282.25 B at n = 16):
+      apms_compress       16.25 n         read g, delta, n/8 B of server signs; write delta, m, n/8 B of signs
+      apms_apply          12.125          read signs, v, x; write x
+    """
+    server = 8.0 + (n + 1) / 8.0
+    if gather_deferred:
+        return {"compress": 16.25 * n, "server_reduce": server, "apply": 12.125}
+    return {"compress": 16.125 * n, "server_reduce": server, "apply": 12.125 + 4.0 * n}
 
 
 def cpu_baseline(wl, run, g, sample_elems, steps):
@@ -74,9 +84,12 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert-large-flat")
-    ap.add_argument("--mode", choices=["deferred", "eager"], default="deferred")
+    ap.add_argument("--mode", choices=["deferred", "deferred-errors", "eager"], default="deferred",
+                    help="deferred: error buffers and the momentum gather are written one call later "
+                         "(apms_set_deferral); eager: every buffer is final when its call's work ends")
     ap.add_argument("--compress-tiles", type=int, default=0)
     ap.add_argument("--server-tiles", type=int, default=0)
+    ap.add_argument("--occupancy-pad", default="", help="e.g. compress=65536,apply=0 (apms_set_occupancy_pad)")
     ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -102,10 +115,17 @@ def main():
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))
     st = W.device_state(wl, dev)
-    run = DeviceRun(d, n, L, dev, deferred=(args.mode == "deferred"), state=st)
+    deferral = {"deferred": B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, "deferred-errors": B.APMS_DEFER_ERRORS,
+                "eager": 0}[args.mode]
+    run = DeviceRun(d, n, L, dev, deferred=deferral, state=st)
     del st
     if args.compress_tiles or args.server_tiles:
         B.apms_set_tiles_per_block(run.ctx, args.compress_tiles, args.server_tiles)
+    kernel_ids = {"compress": B.APMS_KERNEL_COMPRESS, "server": B.APMS_KERNEL_SERVER,
+                  "apply": B.APMS_KERNEL_APPLY, "finalize": B.APMS_KERNEL_FINALIZE}
+    for item in filter(None, args.occupancy_pad.split(",")):
+        name, val = item.split("=")
+        B.apms_set_occupancy_pad(run.ctx, kernel_ids[name], int(val))
     plan = B.apms_get_plan(run.ctx)
     g = torch.empty(n, d, dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
@@ -133,7 +153,7 @@ def main():
         log("calibration copy done: %d bytes read, %d bytes written" % (4 * n * d, 4 * n * d))
     for s in range(args.warmup):
         one_step(s)
-    run.finalize_errors()          # the timed region starts from a state with nothing pending
+    run.finalize()          # the timed region starts from a state with nothing pending
     torch.cuda.synchronize()
     log("warm-up done (%d steps)" % args.warmup)
 
@@ -144,7 +164,7 @@ def main():
     for s in range(args.steps):
         one_step(args.warmup + s, ev[s])
     fin[0].record(stream)
-    run.finalize_errors()
+    run.finalize()
     fin[1].record(stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - wall0
@@ -156,7 +176,8 @@ def main():
     total_ms = sum(t_c) + sum(t_s) + sum(t_a) + t_fin
     ms_per_step = total_ms / args.steps
     value = d * args.steps / (total_ms * 1e-3)
-    ab = algorithmic_bytes(n)
+    ab = call_bytes(n, gather_deferred=bool(deferral & B.APMS_DEFER_GATHER))
+    spec_bytes = sum(call_bytes(n).values())       # the workload's own accounting (eager gather)
     mean = lambda xs: sum(xs) / len(xs)
     step_bytes = d * sum(ab.values())
     compress_ms = mean(t_c)
@@ -170,18 +191,20 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": "%s: d_pad=%d n=%d chunk=%d" % (wl.name, d, n, L),
-            "error_mode": args.mode, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
+            "mode": args.mode, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
             "worker_params_per_s": value * n,
-            "algorithmic_bytes_per_param_step": sum(ab.values()),
-            "step_GBps_algorithmic": step_bytes / (ms_per_step * 1e-3) / 1e9,
+            "bytes_per_param_step": sum(ab.values()),
+            "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
             "step_frac_of_hbm_peak": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+            "bytes_per_param_step_eager_accounting": spec_bytes,
+            "step_GBps_eager_accounting": d * spec_bytes / (ms_per_step * 1e-3) / 1e9,
             "ms": {"compress": compress_ms, "server_reduce": mean(t_s), "apply": mean(t_a),
                    "final_finalize_total": t_fin},
             "GBps": {"compress": achieved,
                      "server_reduce": d * ab["server_reduce"] / (mean(t_s) * 1e-3) / 1e9,
                      "apply": d * ab["apply"] / (mean(t_a) * 1e-3) / 1e9},
             "plan": {k: plan[k] for k in ("compress_tiles_per_block", "compress_grid", "server_tiles_per_block",
-                                          "server_grid", "apply_grid")},
+                                          "server_grid", "apply_grid", "occupancy_pad")},
             "wall_s_including_input_generation": wall,
             "device": torch.cuda.get_device_name(0),
         },

@@ -13,8 +13,8 @@
  * Conventions for every entry point
  *   - Every array argument is a DEVICE pointer owned by the caller, 16-byte
  *     aligned, on the device the context was created for.  The library never
- *     allocates, frees or keeps them (it remembers the ADDRESS of an error
- *     buffer left in deferred form, see apms_set_error_mode).  Distinct array
+ *     allocates, frees or keeps them (it remembers the ADDRESS of a buffer
+ *     left in deferred form, see apms_set_deferral).  Distinct array
  *     arguments of one call must not overlap.
  *   - "[n][d]" is worker-major: worker i's slice starts at element i*d.
  *     d is the (padded) vector length, a multiple of chunk_elems; chunk_elems
@@ -58,14 +58,14 @@ typedef enum apms_status {
     APMS_EHIP = -5,    /* a HIP call failed; see apms_last_hip_error */
     APMS_ENODEV = -6,  /* validation-only context: arguments are fine, nothing can run */
     APMS_EALIAS = -7,  /* two array arguments overlap */
-    APMS_ESTATE = -8   /* an error buffer is pending in deferred form and a different one was passed */
+    APMS_ESTATE = -8   /* the call would lose or read state that is pending in deferred form */
 } apms_status;
 
 #define APMS_DEVICE_NONE (-1)
 
-/* How the two error buffers are left by apms_compress / apms_server_reduce. */
-#define APMS_ERRORS_EAGER 0    /* on return (in stream order) they hold delta as the paper defines it */
-#define APMS_ERRORS_DEFERRED 1 /* they hold the compensated vector u; delta = u - C[u] is formed on next read */
+/* Deferral flags for apms_set_deferral (0 = everything eager, the default). */
+#define APMS_DEFER_ERRORS 1 /* error buffers hold the compensated vector u; delta = u - C[u] is formed on next read */
+#define APMS_DEFER_GATHER 2 /* apms_apply leaves m untouched; the next apms_compress writes the gathered momentum */
 
 /* Launch geometry of a context (read-only report; see apms_get_plan). */
 typedef struct apms_plan {
@@ -130,29 +130,37 @@ int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t serv
 int apms_set_occupancy_pad(apms_ctx *ctx, int kernel, int32_t lds_bytes);
 
 /*
- * Error-buffer mode (default APMS_ERRORS_EAGER).
+ * Deferral: software pipelining of two writes across the step boundary.  Results are bit-identical to
+ * the eager ones; what changes is WHEN a caller-owned buffer holds its final value.
  *
- * The new error delta' = u - C[u] (Section 3.1; supplement steps 1-2) needs
- * the scale of the WHOLE chunk, which is known only after the chunk has been
- * streamed once.  In EAGER mode a second pass over the error buffer forms
- * delta' before the call's work ends.  In DEFERRED mode the call stores the
- * compensated vector u in the error buffer instead and the context keeps the
- * chunk scales; the next apms_compress / apms_server_reduce on the SAME
- * buffer forms delta' = u - (u >= 0 ? +s : -s) while reading it (bit-identical
- * to the eager value: one binary32 subtraction of the same operands), which
- * saves one read and one write of the buffer per step.  While a buffer is
- * pending its contents are u, not delta: call apms_finalize_errors before
- * reading it (checkpoint, test) or before handing a different buffer to the
- * same context (else APMS_ESTATE).
+ * APMS_DEFER_ERRORS.  The new error delta' = u - C[u] (Section 3.1; supplement steps 1-2) needs the
+ * scale of the WHOLE chunk, known only after the chunk has been streamed once.  Eagerly, a second pass
+ * over the error buffer forms delta' before the call's work ends.  Deferred, the call stores the
+ * compensated vector u in the error buffer and the context keeps the chunk scales; the next
+ * apms_compress / apms_server_reduce on the SAME buffer forms delta' = u - (u >= 0 ? +s : -s) while
+ * reading it (one binary32 subtraction of the same operands), saving one read and one write of the
+ * buffer per step.
+ *
+ * APMS_DEFER_GATHER.  Eagerly, apms_apply writes the decoded server message to all n momentum slices
+ * (Algorithm 1 line 10) and the next apms_compress reads them back.  Deferred, apms_apply only takes
+ * the model step and remembers `spacked` (by address) and the server scales (by value); the next
+ * apms_compress on the SAME m decodes the sign words itself, WRITES the n momentum slices and uses the
+ * decoded values in place of reading m: the momentum state is still materialised in m[n][d] every step,
+ * it is just not read back.  Until then `spacked` must stay untouched (apms_server_reduce with that
+ * address is refused).
+ *
+ * While a buffer is pending its contents are not final: call apms_finalize before reading it
+ * (checkpoint, test) or before handing a different buffer to the same context; a call that would lose
+ * or read pending state returns APMS_ESTATE.
  */
-int apms_set_error_mode(apms_ctx *ctx, int mode);
+int apms_set_deferral(apms_ctx *ctx, int flags);
 
 /*
- * Bring pending error buffers to the paper's delta.  Either pointer may be
- * NULL (skip).  A buffer that is not pending is left untouched.
- *   worker_err [n][d], server_err [d].
+ * Bring pending buffers to their final contents: the paper's delta in worker_err / server_err, the
+ * gathered momentum in m.  Any pointer may be NULL (skip).  A buffer that is not pending is untouched.
+ *   worker_err [n][d], server_err [d], m [n][d].
  */
-int apms_finalize_errors(apms_ctx *ctx, float *worker_err, float *server_err, void *stream);
+int apms_finalize(apms_ctx *ctx, float *worker_err, float *server_err, float *m, void *stream);
 
 /*
  * Warm-up: one step of the original Adam (Section 3.2; Algorithm 1 line 2)
@@ -184,14 +192,16 @@ int apms_freeze(apms_ctx *ctx, float *m, float *worker_err, float *server_err, v
  *   scale  = fl32( sqrt( sum_chunk u^2 / chunk_elems ) )        (Section 5.1)
  *   bit    = (u >= 0)
  *   delta_i <- u - (bit ? +scale : -scale)
- *   m, g        [n][d] in (the local momentum is not stored: the gather of
- *               apms_apply overwrites m)
+ *   m           [n][d] in (written only when a deferred gather is pending on it)
+ *   g           [n][d] in (the local momentum m_t^(i) is not stored: the gather overwrites m)
  *   worker_err  [n][d] in/out
  *   packed      [n][d/32] out, sign words
  *   scales      [n][C] out
+ * With a gather pending on m (APMS_DEFER_GATHER) the kernel decodes the pending server message,
+ * writes it to m and uses it as m_i; otherwise m is read only.
  * Errors: EINVAL (beta outside [0,1), null), EALIGN, EALIAS, ESTATE, EHIP.
  */
-int apms_compress(apms_ctx *ctx, const float *m, const float *g, float *worker_err,
+int apms_compress(apms_ctx *ctx, float *m, const float *g, float *worker_err,
                   uint32_t *packed, float *scales, float beta, void *stream);
 
 /*

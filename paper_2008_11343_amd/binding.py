@@ -18,13 +18,13 @@ APMS_OK = 0
 APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS_EALIAS, APMS_ESTATE = (
     -1, -2, -3, -4, -5, -6, -7, -8)
 APMS_DEVICE_NONE = -1
-APMS_ERRORS_EAGER = 0
-APMS_ERRORS_DEFERRED = 1
+APMS_DEFER_ERRORS = 1
+APMS_DEFER_GATHER = 2
 APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE = 0, 1, 2, 3
 
 EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
-    "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_error_mode", "apms_finalize_errors", "apms_warmup_step",
+    "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
     "apms_freeze", "apms_compress", "apms_server_reduce", "apms_apply",
 )
 
@@ -81,8 +81,8 @@ def load():
         "apms_get_plan": (ci, [vp, ctypes.POINTER(apms_plan)]),
         "apms_set_tiles_per_block": (ci, [vp, i32, i32]),
         "apms_set_occupancy_pad": (ci, [vp, ci, i32]),
-        "apms_set_error_mode": (ci, [vp, ci]),
-        "apms_finalize_errors": (ci, [vp, vp, vp, vp]),
+        "apms_set_deferral": (ci, [vp, ci]),
+        "apms_finalize": (ci, [vp, vp, vp, vp, vp]),
         "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "apms_freeze": (ci, [vp, vp, vp, vp, vp]),
         "apms_compress": (ci, [vp, vp, vp, vp, vp, vp, f32, vp]),
@@ -155,13 +155,13 @@ def apms_set_occupancy_pad(ctx, kernel: int, lds_bytes: int):
     _check(ctx, load().apms_set_occupancy_pad(ctx, kernel, lds_bytes), "apms_set_occupancy_pad")
 
 
-def apms_set_error_mode(ctx, mode: int):
-    _check(ctx, load().apms_set_error_mode(ctx, mode), "apms_set_error_mode")
+def apms_set_deferral(ctx, flags: int):
+    _check(ctx, load().apms_set_deferral(ctx, flags), "apms_set_deferral")
 
 
-def apms_finalize_errors(ctx, worker_err=None, server_err=None, stream=None):
-    _check(ctx, load().apms_finalize_errors(ctx, _ptr(worker_err), _ptr(server_err), _stream(stream)),
-           "apms_finalize_errors")
+def apms_finalize(ctx, worker_err=None, server_err=None, m=None, stream=None):
+    _check(ctx, load().apms_finalize(ctx, _ptr(worker_err), _ptr(server_err), _ptr(m), _stream(stream)),
+           "apms_finalize")
 
 
 def apms_warmup_step(ctx, x, m, v, g, lr, beta1, beta2, eps, t, stream=None):

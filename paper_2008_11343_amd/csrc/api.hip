@@ -26,12 +26,15 @@ struct apms_ctx {
     double* w_partials = nullptr;     // [n*C][w_tiles_per_chunk] (sized for 1 tile per block)
     double* s_partials = nullptr;     // [C][s_tiles_per_chunk]
     float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
-    float* s_pending = nullptr;       // [C]
+    float* s_pending = nullptr;       // [C]   same for the server error buffer
+    float* g_pending = nullptr;       // [C]   server scales of a gather that has not been carried out yet
     int64_t scratch_bytes = 0;
-    // deferred-error bookkeeping (host side, follows call order = stream order)
-    const void* pending_werr = nullptr;
+    // deferral bookkeeping (host side, follows call order = stream order)
+    const void* pending_werr = nullptr;       // error buffers that hold u instead of delta
     const void* pending_serr = nullptr;
-    int error_mode = APMS_ERRORS_EAGER;
+    const void* pending_m = nullptr;          // momentum buffer whose gather is still to be written ...
+    const uint32_t* pending_spacked = nullptr;  // ... from these sign words (caller's buffer) and g_pending
+    int deferral = 0;                         // APMS_DEFER_* flags
     int last_hip = 0;
 };
 
@@ -42,9 +45,10 @@ namespace {
 constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
-// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize): measured on MI355X,
-// these streams are fastest with 2 workgroups (8 waves) per CU.
-constexpr int32_t kDefaultLdsPad[4] = {64 * 1024, 0, 0, 0};
+// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize).  Measured on MI355X:
+// the worker kernel streams fastest with 3 workgroups (12 waves) per CU, the small-tile kernels with as
+// many as fit.
+constexpr int32_t kDefaultLdsPad[4] = {40 * 1024, 0, 0, 0};
 
 struct Range {
     const void* p;
@@ -116,8 +120,9 @@ void free_scratch(apms_ctx* c) {
     if (c->s_partials) (void)hipFree(c->s_partials);
     if (c->w_pending) (void)hipFree(c->w_pending);
     if (c->s_pending) (void)hipFree(c->s_pending);
+    if (c->g_pending) (void)hipFree(c->g_pending);
     c->w_partials = c->s_partials = nullptr;
-    c->w_pending = c->s_pending = nullptr;
+    c->w_pending = c->s_pending = c->g_pending = nullptr;
 }
 
 // Common tail of validation: empty problem -> OK (done), validation-only context -> ENODEV.
@@ -186,7 +191,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     const int64_t sp = C * c->s_tiles_per_chunk * static_cast<int64_t>(sizeof(double));
     const int64_t wq = pairs * static_cast<int64_t>(sizeof(float));
     const int64_t sq = C * static_cast<int64_t>(sizeof(float));
-    c->scratch_bytes = wp + sp + wq + sq;
+    c->scratch_bytes = wp + sp + wq + 2 * sq;
     if (device != APMS_DEVICE_NONE && d > 0) {
         DeviceScope scope(device);
         hipError_t e = scope.err;
@@ -195,6 +200,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_partials), sp);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_pending), sq);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->g_pending), sq);
         if (e != hipSuccess) {
             free_scratch(c);
             delete c;
@@ -252,15 +258,16 @@ int apms_set_occupancy_pad(apms_ctx* c, int kernel, int32_t lds_bytes) {
     return APMS_OK;
 }
 
-int apms_set_error_mode(apms_ctx* c, int mode) {
-    if (!c || (mode != APMS_ERRORS_EAGER && mode != APMS_ERRORS_DEFERRED)) return APMS_EINVAL;
-    c->error_mode = mode;
+int apms_set_deferral(apms_ctx* c, int flags) {
+    if (!c || (flags & ~(APMS_DEFER_ERRORS | APMS_DEFER_GATHER)) != 0) return APMS_EINVAL;
+    c->deferral = flags;
     return APMS_OK;
 }
 
-int apms_finalize_errors(apms_ctx* c, float* worker_err, float* server_err, void* stream) {
+int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, void* stream) {
     if (!c) return APMS_EINVAL;
-    if ((worker_err && misaligned(worker_err)) || (server_err && misaligned(server_err))) return APMS_EALIGN;
+    if ((worker_err && misaligned(worker_err)) || (server_err && misaligned(server_err)) || (m && misaligned(m)))
+        return APMS_EALIGN;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -277,6 +284,14 @@ int apms_finalize_errors(apms_ctx* c, float* worker_err, float* server_err, void
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_serr = nullptr;
     }
+    if (m && c->pending_m == m) {
+        hipError_t e = apms::launch_apply(geo, c->pending_spacked, c->g_pending, nullptr, nullptr, m, nullptr,
+                                          /*write_m=*/true, /*model_step=*/false, 0.0f, 0.0f,
+                                          c->lds_pad[APMS_KERNEL_APPLY], s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_m = nullptr;
+        c->pending_spacked = nullptr;
+    }
     return APMS_OK;
 }
 
@@ -288,6 +303,7 @@ int apms_warmup_step(apms_ctx* c, float* x, float* m, float* v, const float* g, 
     if (int rc = check_arrays(r, 4)) return rc;
     if (!unit_interval(beta1) || !unit_interval(beta2) || t < 1 || !(lr == lr) || !(eps == eps))
         return APMS_EINVAL;
+    if (c->pending_m && c->pending_m == m) return APMS_ESTATE;   // slice 0 is not final yet
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -305,6 +321,7 @@ int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, voi
     const int64_t vec = c->d * 4;
     const Range r[] = {{m, vec * c->n}, {worker_err, vec * c->n}, {server_err, vec}};
     if (int rc = check_arrays(r, 3)) return rc;
+    if (c->pending_m && c->pending_m == m) return APMS_ESTATE;   // slice 0 is not final yet
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -316,14 +333,17 @@ int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, voi
     return APMS_OK;
 }
 
-int apms_compress(apms_ctx* c, const float* m, const float* g, float* worker_err, uint32_t* packed,
-                  float* scales, float beta, void* stream) {
+int apms_compress(apms_ctx* c, float* m, const float* g, float* worker_err, uint32_t* packed, float* scales,
+                  float beta, void* stream) {
     if (!c) return APMS_EINVAL;
     const int64_t all = c->d * 4 * c->n;
-    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4}};
-    if (int rc = check_arrays(r, 5)) return rc;
+    const bool gather = c->pending_m != nullptr;
+    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4},
+                       {c->pending_spacked, gather ? c->d / 8 : 0}};
+    if (int rc = check_arrays(r, 6)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
     if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
+    if (gather && c->pending_m != m) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -332,15 +352,18 @@ int apms_compress(apms_ctx* c, const float* m, const float* g, float* worker_err
     const apms::Geometry geo = geometry(c);
     const float* prev = c->pending_werr ? c->w_pending : nullptr;
     hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, worker_err,
-                                         packed, c->w_partials, prev, beta, 1.0f - beta,
+                                         packed, c->w_partials, prev, gather ? c->pending_spacked : nullptr,
+                                         gather ? c->g_pending : nullptr, beta, 1.0f - beta,
                                          c->lds_pad[APMS_KERNEL_COMPRESS], s);
     if (e != hipSuccess) return hip_fail(c, e);
-    // from here on the buffer holds u and the context holds its scales
+    // from here on m holds the gathered momentum, the error buffer holds u and the context its scales
+    c->pending_m = nullptr;
+    c->pending_spacked = nullptr;
     c->pending_werr = worker_err;
     e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
                             c->w_pending, s);
     if (e != hipSuccess) return hip_fail(c, e);
-    if (c->error_mode == APMS_ERRORS_EAGER) {
+    if (!(c->deferral & APMS_DEFER_ERRORS)) {
         e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_werr = nullptr;
@@ -356,6 +379,8 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
                        {spacked, vec / 32}, {sscales, c->C * 4}};
     if (int rc = check_arrays(r, 5)) return rc;
     if (c->pending_serr && c->pending_serr != server_err) return APMS_ESTATE;
+    // a pending gather still needs the sign words at that address
+    if (c->pending_m && overlap({c->pending_spacked, vec / 32}, {spacked, vec / 32})) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -371,7 +396,7 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     c->pending_serr = server_err;
     e = apms::launch_scales(c->C, c->s_blocks_per_chunk, c->L, c->s_partials, sscales, c->s_pending, s);
     if (e != hipSuccess) return hip_fail(c, e);
-    if (c->error_mode == APMS_ERRORS_EAGER) {
+    if (!(c->deferral & APMS_DEFER_ERRORS)) {
         e = apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_serr = nullptr;
@@ -386,13 +411,21 @@ int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const
     const Range r[] = {{spacked, vec / 32}, {sscales, c->C * 4}, {v, vec}, {x, vec}, {m, vec * c->n}};
     if (int rc = check_arrays(r, 5)) return rc;
     if (!(lr == lr) || !(eps == eps)) return APMS_EINVAL;
+    if (c->pending_m && c->pending_m != m) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = apms::launch_apply(geometry(c), spacked, sscales, v, x, m, lr, eps,
-                                      c->lds_pad[APMS_KERNEL_APPLY], static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+    const bool defer = (c->deferral & APMS_DEFER_GATHER) != 0;
+    hipError_t e = apms::launch_apply(geometry(c), spacked, sscales, v, x, m, c->g_pending, /*write_m=*/!defer,
+                                      /*model_step=*/true, lr, eps, c->lds_pad[APMS_KERNEL_APPLY],
+                                      static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(c, e);
+    // eager: m is final (a gather pending on it from an earlier call is superseded);
+    // deferred: m is to be written from these sign words and the saved scales
+    c->pending_m = defer ? m : nullptr;
+    c->pending_spacked = defer ? spacked : nullptr;
+    return APMS_OK;
 }
 
 }  // extern "C"

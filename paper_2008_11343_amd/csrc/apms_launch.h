@@ -43,11 +43,13 @@ inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L 
 // Worker step over all (worker, chunk) pairs: writes u into werr, sign words into packed, one binary64
 // partial sum of u^2 per workgroup into partials [n*C][blocks_per_chunk]; a workgroup streams
 // tiles_per_block consecutive tiles of kCompressTile elements.  prev_scales (nullable, [n*C]) marks werr
-// as holding last step's u (deferred form).
-hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
-                           const float* m, const float* g, float* werr, uint32_t* packed,
-                           double* partials, const float* prev_scales, float beta, float one_minus_beta,
-                           int32_t lds_pad, hipStream_t stream);
+// as holding last step's u (deferred form).  gather_words ([d/32]) + gather_scales ([C]), both nullable
+// together, mark a deferred gather: the kernel then decodes the momentum from them, writes it to all of
+// m and does not read m.
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
+                           const float* g, float* werr, uint32_t* packed, double* partials,
+                           const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
+                           float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream);
 
 // Reduce partials [pairs][blocks_per_chunk] in fixed order, scale = fl32(sqrt(S / L));
 // writes scales_out[pair] and pending_out[pair] (either may be null).
@@ -65,9 +67,11 @@ hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, in
                                 double* partials, const float* prev_scales, float inv_n, int32_t lds_pad,
                                 hipStream_t stream);
 
-// Gather + model update.
+// Gather (write_m: decoded server message to all n slices of m) and/or model update (model_step).
+// With write_m false the server scales are also saved to scales_copy [C] for a later gather.
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
-                        float* x, float* m, float lr, float eps, int32_t lds_pad, hipStream_t stream);
+                        float* x, float* m, float* scales_copy, bool write_m, bool model_step, float lr,
+                        float eps, int32_t lds_pad, hipStream_t stream);
 
 // Adam warm-up step on the averaged gradient.
 hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,

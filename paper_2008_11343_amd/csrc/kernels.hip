@@ -49,32 +49,46 @@ __device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
     }
 }
 
-template <bool kFull>
-__device__ __forceinline__ void compress_tile(const float* __restrict__ m, const float* __restrict__ g,
+// kGather: a deferred gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum of
+// every worker is the decoded server message (gather_words, gather_scale); write it to m and use it
+// directly instead of reading m back.
+template <bool kFull, bool kGather>
+__device__ __forceinline__ void compress_tile(float* __restrict__ m, const float* __restrict__ g,
                                               float* __restrict__ e, uint32_t* __restrict__ packed,
-                                              int64_t chunk_base, int64_t tile_off, int64_t L, int lane_off,
-                                              int lane, int wave, float beta, float omb, float prev_scale,
-                                              double (&acc)[4]) {
+                                              const uint32_t* __restrict__ gather_words, float gather_scale,
+                                              int64_t vec_base, int64_t chunk_base, int64_t tile_off, int64_t L,
+                                              int lane_off, int lane, int wave, float beta, float omb,
+                                              float prev_scale, double (&acc)[4]) {
     constexpr int ROWS = kCompressRows;
     const int64_t off0 = tile_off + lane_off;             // inside the chunk
     bool ok[ROWS];
     f32x4 vm[ROWS], vg[ROWS], ve[ROWS];
+    uint32_t gw[ROWS];
+    const int shift = 4 * (lane & 7);
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         ok[r] = kFull || (off0 + 32 * r < L);
         if (ok[r]) {
             const int64_t p = chunk_base + off0 + 32 * r;
-            vm[r] = load_stream(m + p);
+            if (kGather)
+                gw[r] = gather_words[(vec_base + off0 + 32 * r) >> 5];
+            else
+                vm[r] = load_stream(m + p);
             vg[r] = load_stream(g + p);
             ve[r] = load_stream(e + p);
         }
     }
     uint32_t words[ROWS];
-    const int shift = 4 * (lane & 7);
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         uint32_t nib = 0u;
         if (ok[r]) {
+            if (kGather) {
+                const uint32_t gn = gw[r] >> shift;
+#pragma unroll
+                for (int c = 0; c < 4; ++c) vm[r][c] = signed_scale((gn >> c) & 1u, gather_scale);
+                store_stream(m + chunk_base + off0 + 32 * r, vm[r]);
+            }
             const f32x4 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
             store_stream(e + chunk_base + off0 + 32 * r, u);
             accumulate_squares(acc, u);
@@ -89,19 +103,23 @@ __device__ __forceinline__ void compress_tile(const float* __restrict__ m, const
     }
 }
 
+template <bool kGather>
 __global__ __launch_bounds__(kThreads) void compress_kernel(
-    const float* __restrict__ m, const float* __restrict__ g, float* __restrict__ e,
-    uint32_t* __restrict__ packed, double* __restrict__ partials, const float* __restrict__ prev_scales,
-    int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk, int32_t tiles_per_block,
-    int32_t blocks_per_chunk, float beta, float omb) {
+    float* __restrict__ m, const float* __restrict__ g, float* __restrict__ e, uint32_t* __restrict__ packed,
+    double* __restrict__ partials, const float* __restrict__ prev_scales,
+    const uint32_t* __restrict__ gather_words, const float* __restrict__ gather_scales, int64_t d, int64_t L,
+    int32_t C, int32_t tiles_per_chunk, int32_t tiles_per_block, int32_t blocks_per_chunk, float beta,
+    float omb) {
     __shared__ double lds[kWaves];
     const int64_t blk = blockIdx.x;
     const int64_t pair = blk / blocks_per_chunk;          // worker * C + chunk
     const int32_t b = static_cast<int32_t>(blk - pair * blocks_per_chunk);
     const int64_t worker = pair / C;
     const int64_t chunk = pair - worker * C;
-    const int64_t chunk_base = worker * d + chunk * L;
+    const int64_t vec_base = chunk * L;                   // inside one [d] vector
+    const int64_t chunk_base = worker * d + vec_base;     // inside [n][d]
     const float prev_scale = prev_scales ? prev_scales[pair] : 0.0f;
+    const float gather_scale = kGather ? gather_scales[chunk] : 0.0f;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     const int lane_off = packing_lane_offset<kCompressRows>(wave, lane);
@@ -111,11 +129,11 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     for (int32_t t = t0; t < t1; ++t) {
         const int64_t tile_off = static_cast<int64_t>(t) * kCompressTile;
         if (tile_off + kCompressTile <= L)
-            compress_tile<true>(m, g, e, packed, chunk_base, tile_off, L, lane_off, lane, wave, beta, omb,
-                                prev_scale, acc);
+            compress_tile<true, kGather>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+                                         tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
         else
-            compress_tile<false>(m, g, e, packed, chunk_base, tile_off, L, lane_off, lane, wave, beta, omb,
-                                 prev_scale, acc);
+            compress_tile<false, kGather>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+                                          tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
     }
     const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     const double total = block_sum_f64(mine, lds);
@@ -275,24 +293,30 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
 
 // One workgroup = one tile of ONE worker's momentum slice, slice-major, so the n slices are written as
 // one long contiguous fill of m[n][d]; the workgroups of slice 0 also take the model step for their tile.
+//   <kWriteM = true,  kModelStep = true >  eager apms_apply (grid: n slices)
+//   <kWriteM = false, kModelStep = true >  apms_apply with the gather deferred (grid: 1 slice); also saves
+//                                          the server scales for the kernel that will carry out the gather
+//   <kWriteM = true,  kModelStep = false>  the gather alone (apms_finalize on m)
+template <bool kWriteM, bool kModelStep>
 __global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restrict__ spacked,
                                                          const float* __restrict__ sscales,
                                                          const float* __restrict__ v, float* __restrict__ x,
-                                                         float* __restrict__ m, int64_t d, int64_t L,
-                                                         int64_t tiles_per_slice, int32_t tiles_per_chunk,
-                                                         float lr, float eps) {
+                                                         float* __restrict__ m, float* __restrict__ scales_copy,
+                                                         int64_t d, int64_t L, int64_t tiles_per_slice,
+                                                         int32_t tiles_per_chunk, float lr, float eps) {
+    constexpr int ROWS = kApplyRows;
+    constexpr int kRowStride = kThreads * 4;              // plain layout
     const int64_t blk = blockIdx.x;
     const int64_t slice = blk / tiles_per_slice;
     const int64_t ct = blk - slice * tiles_per_slice;     // chunk * tiles_per_chunk + tile
     const int64_t chunk = ct / tiles_per_chunk;
     const int64_t tile = ct - chunk * tiles_per_chunk;
-    constexpr int ROWS = kApplyRows;
-    constexpr int kRowStride = kThreads * 4;              // plain layout
     const int64_t chunk_base = chunk * L;
     const float s = sscales[chunk];
+    if (!kWriteM && tile == 0 && threadIdx.x == 0) scales_copy[chunk] = s;
     const int64_t off0 = tile * kApplyTile + threadIdx.x * 4;
     const int shift = 4 * (threadIdx.x & 7);
-    const bool model_step = (slice == 0);
+    const bool model_step = kModelStep && (slice == 0);
     float* __restrict__ mslice = m + slice * d;
     bool ok[ROWS];
     f32x4 vv[ROWS], vx[ROWS];
@@ -317,7 +341,7 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restr
         f32x4 mom;
 #pragma unroll
         for (int c = 0; c < 4; ++c) mom[c] = signed_scale((nib >> c) & 1u, s);   // decoded server message
-        store_stream(mslice + p, mom);
+        if (kWriteM) store_stream(mslice + p, mom);
         if (model_step) {
             f32x4 xn;
 #pragma unroll
@@ -408,8 +432,13 @@ inline uint32_t stride_grid(int64_t d) {
 }  // namespace
 
 hipError_t enable_large_lds_pads() {
-    const void* kernels[] = {reinterpret_cast<const void*>(compress_kernel), reinterpret_cast<const void*>(server_kernel),
-                             reinterpret_cast<const void*>(apply_kernel), reinterpret_cast<const void*>(finalize_kernel)};
+    const void* kernels[] = {reinterpret_cast<const void*>(compress_kernel<false>),
+                             reinterpret_cast<const void*>(compress_kernel<true>),
+                             reinterpret_cast<const void*>(server_kernel),
+                             reinterpret_cast<const void*>(apply_kernel<true, true>),
+                             reinterpret_cast<const void*>(apply_kernel<false, true>),
+                             reinterpret_cast<const void*>(apply_kernel<true, false>),
+                             reinterpret_cast<const void*>(finalize_kernel)};
     for (const void* k : kernels) {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
         if (e != hipSuccess) return e;
@@ -417,16 +446,21 @@ hipError_t enable_large_lds_pads() {
     return hipSuccess;
 }
 
-hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk,
-                           const float* m, const float* g, float* werr, uint32_t* packed, double* partials,
-                           const float* prev_scales, float beta, float one_minus_beta, int32_t lds_pad,
-                           hipStream_t stream) {
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
+                           const float* g, float* werr, uint32_t* packed, double* partials,
+                           const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
+                           float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream) {
     const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(compress_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, m, g,
-                       werr, packed, partials, prev_scales, geo.d, geo.L, geo.C,
-                       static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile)), tiles_per_block,
-                       blocks_per_chunk, beta, one_minus_beta);
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile));
+    if (gather_words)
+        hipLaunchKernelGGL(compress_kernel<true>, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream,
+                           m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
+                           geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
+    else
+        hipLaunchKernelGGL(compress_kernel<false>, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream,
+                           m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
+                           geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
     return hipGetLastError();
 }
 
@@ -462,13 +496,22 @@ hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, in
 }
 
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
-                        float* x, float* m, float lr, float eps, int32_t lds_pad, hipStream_t stream) {
+                        float* x, float* m, float* scales_copy, bool write_m, bool model_step, float lr,
+                        float eps, int32_t lds_pad, hipStream_t stream) {
     const int64_t tpc = tiles_per_chunk(geo, kApplyTile);
     const int64_t tiles_per_slice = static_cast<int64_t>(geo.C) * tpc;
-    const int64_t grid = tiles_per_slice * geo.n;
-    if (grid <= 0) return hipSuccess;
-    hipLaunchKernelGGL(apply_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream, spacked,
-                       sscales, v, x, m, geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
+    const int64_t grid = tiles_per_slice * (write_m ? geo.n : 1);
+    if (grid <= 0 || !(write_m || model_step)) return hipSuccess;
+    const dim3 g(static_cast<uint32_t>(grid)), b(kThreads);
+    if (write_m && model_step)
+        hipLaunchKernelGGL((apply_kernel<true, true>), g, b, lds_pad, stream, spacked, sscales, v, x, m, scales_copy,
+                           geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
+    else if (model_step)
+        hipLaunchKernelGGL((apply_kernel<false, true>), g, b, lds_pad, stream, spacked, sscales, v, x, m, scales_copy,
+                           geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
+    else
+        hipLaunchKernelGGL((apply_kernel<true, false>), g, b, lds_pad, stream, spacked, sscales, v, x, m, scales_copy,
+                           geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
     return hipGetLastError();
 }
 

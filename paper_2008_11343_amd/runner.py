@@ -18,13 +18,15 @@ class DeviceRun:
     """
 
     def __init__(self, d, n, L, device="cuda:0", deferred=False, state=None):
+        """deferred: False (everything eager), True (errors and gather deferred) or an int of APMS_DEFER_* flags."""
         self.d, self.n, self.L = d, n, L
         self.C = d // L if L else 0
         self.device = torch.device(device)
         idx = self.device.index if self.device.index is not None else torch.cuda.current_device()
         self.ctx = B.apms_create(d, n, L, idx)
-        if deferred:
-            B.apms_set_error_mode(self.ctx, B.APMS_ERRORS_DEFERRED)
+        self.deferral = (B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER) if deferred is True else int(deferred)
+        if self.deferral:
+            B.apms_set_deferral(self.ctx, self.deferral)
         f = dict(dtype=torch.float32, device=self.device)
         i = dict(dtype=torch.int32, device=self.device)
         if state is not None:
@@ -70,8 +72,9 @@ class DeviceRun:
         self.server_reduce(stream)
         self.apply(lr, eps, stream)
 
-    def finalize_errors(self, stream=None):
-        B.apms_finalize_errors(self.ctx, self.werr, self.serr, stream)
+    def finalize(self, stream=None):
+        """Bring every pending buffer (both errors, the momentum) to its final contents."""
+        B.apms_finalize(self.ctx, self.werr, self.serr, self.m, stream)
 
     # warm-up (Algorithm 1 line 2) works on worker 0's momentum slice
     def warmup_step(self, g, lr, beta1, beta2, eps, t, stream=None):

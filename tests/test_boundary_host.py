@@ -86,7 +86,7 @@ def test_valid_calls_on_validation_only_context_report_no_device(ctx):
     assert status_of(B.apms_warmup_step, ctx, fake(0), fake(1), fake(2), fake(3), 1e-3, 0.9, 0.999, 1e-8, 1) == \
         B.APMS_ENODEV
     assert status_of(B.apms_freeze, ctx, fake(0), fake(1), fake(2)) == B.APMS_ENODEV
-    assert status_of(B.apms_finalize_errors, ctx, fake(0), fake(1)) == B.APMS_ENODEV
+    assert status_of(B.apms_finalize, ctx, fake(0), fake(1), fake(2)) == B.APMS_ENODEV
 
 
 def test_null_misaligned_and_overlapping_arrays(ctx):
@@ -124,7 +124,8 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_warmup_step, ctx, *w, 1e-3, 0.9, -0.5, 1e-8, 1) == B.APMS_EINVAL
     assert status_of(B.apms_warmup_step, ctx, *w, float("nan"), 0.9, 0.999, 1e-8, 1) == B.APMS_EINVAL
     assert status_of(B.apms_apply, ctx, *good, float("nan"), 1e-8) == B.APMS_EINVAL
-    assert status_of(B.apms_set_error_mode, ctx, 7) == B.APMS_EINVAL
+    assert status_of(B.apms_set_deferral, ctx, 4) == B.APMS_EINVAL
+    assert status_of(B.apms_set_deferral, ctx, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER) == B.APMS_OK
     assert status_of(B.apms_set_tiles_per_block, ctx, -1, 0) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, 4, 0) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 200 * 1024) == B.APMS_EINVAL

@@ -1,5 +1,5 @@
 """GPU parity at the benchmark's full sizes, in the launch configuration bench.py times
-(deferred-error mode, default tiling): chunks are independent parameter-server problems
+(errors and gather deferred, default tiling): chunks are independent parameter-server problems
 (supplement, first paragraph of 'Proof to the Updating Form'), so the oracle follows a sample of
 whole chunks (first, last, one seeded pick) through the steps on the very bits the GPU consumes,
 and whole-buffer properties are checked on the device.
@@ -38,9 +38,9 @@ def check_chunk(run, ost, k, L, tag, errors):
     np.testing.assert_allclose(run.scales[:, k].cpu().numpy(), ost.scales[:, 0], rtol=RTOL, atol=ATOL, err_msg=tag)
     np.testing.assert_allclose(run.sscales[k].item(), ost.sscales[0], rtol=RTOL, atol=ATOL, err_msg=tag)
     np.testing.assert_allclose(run.x[sl].cpu().numpy(), ost.x, rtol=RTOL, atol=ATOL, err_msg=tag + " x")
-    for i in (0, n - 1):
-        np.testing.assert_allclose(run.m[i, sl].cpu().numpy(), ost.m[i], rtol=RTOL, atol=ATOL, err_msg=tag + " m")
-    if errors:
+    if errors:       # = everything pending has been finalized
+        for i in (0, n - 1):
+            np.testing.assert_allclose(run.m[i, sl].cpu().numpy(), ost.m[i], rtol=RTOL, atol=ATOL, err_msg=tag + " m")
         for i in range(n):
             np.testing.assert_allclose(run.werr[i, sl].cpu().numpy(), ost.werr[i], rtol=RTOL, atol=ATOL,
                                        err_msg=tag + " worker_err[%d]" % i)
@@ -85,7 +85,7 @@ def test_sampled_chunks_at_full_size(wl, steps):
         run.step(g, wl.beta, wl.lr, wl.eps)
         last = step == steps - 1
         if last:
-            run.finalize_errors()
+            run.finalize()
         torch.cuda.synchronize()
         for k in picks:
             say("%s step %d: oracle on chunk %d" % (wl.name, step, k))

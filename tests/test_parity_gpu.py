@@ -44,17 +44,26 @@ def oracle_state(d, n, L, st):
     return oracle.State(d, n, L, st["x"], st["m"], st["v"], st["werr"], st["serr"])
 
 
-def compare_all(run, ost, tag, errors=True):
+MODES = [0, B.APMS_DEFER_ERRORS, B.APMS_DEFER_GATHER, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER]
+MODE_IDS = ["eager", "defer-errors", "defer-gather", "defer-all"]
+
+
+def compare_momentum(run, om, sscales_equal, tag):
+    # the gathered momentum is a copy of +-sscale: exact given equal server scales
+    gm = host(run.m)
+    close(gm, om, tag + " m")
+    if sscales_equal:
+        assert np.array_equal(gm, om), tag + " m must be a bit-exact copy"
+
+
+def compare_all(run, ost, tag, errors=True, momentum=True):
     same_words(host(run.packed), ost.packed, tag + " packed")
     same_words(host(run.spacked), ost.spacked, tag + " spacked")
     close(host(run.scales), ost.scales, tag + " scales")
     close(host(run.sscales), ost.sscales, tag + " sscales")
     close(host(run.x), ost.x, tag + " x")
-    # the gathered momentum is a copy of +-sscale: exact given equal server scales
-    gm, om = host(run.m), ost.m
-    close(gm, om, tag + " m")
-    if np.array_equal(host(run.sscales), ost.sscales):
-        assert np.array_equal(gm, om), tag + " m must be a bit-exact copy"
+    if momentum:
+        compare_momentum(run, ost.m, np.array_equal(host(run.sscales), ost.sscales), tag)
     if errors:
         close(host(run.werr), ost.werr, tag + " worker_err")
         close(host(run.serr), ost.serr, tag + " server_err")
@@ -86,9 +95,10 @@ SHAPES = [
 
 
 @pytest.mark.parametrize("n,L,C", SHAPES)
-@pytest.mark.parametrize("deferred", [False, True], ids=["eager", "deferred"])
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
 def test_stagewise_parity(n, L, C, deferred):
-    """Each call fed the oracle's inputs for that stage: signs must match exactly."""
+    """Each call fed the oracle's inputs for that stage: signs must match exactly.  A second compress then
+    consumes whatever the first step left pending (errors in u form, the gather not yet written)."""
     d = L * C
     say("stagewise n=%d L=%d C=%d deferred=%s" % (n, L, C, deferred))
     st, g = random_case(100 + n + L, d, n, L)
@@ -115,34 +125,49 @@ def test_stagewise_parity(n, L, C, deferred):
     run.sscales.copy_(torch.from_numpy(ost.sscales))
     run.apply(lr, eps)
     oracle.apply(d, n, L, ost.spacked, ost.sscales, ost.v, ost.x, ost.m, lr, eps)
-    assert np.array_equal(host(run.m), ost.m), "gathered momentum must be a bit-exact copy"
     close(host(run.x), ost.x, "x")
-    if deferred:
-        run.finalize_errors()
+    # second worker step: reads the (possibly pending) error and momentum left by the first
+    g2 = np.ascontiguousarray(g[::-1] * F(0.5))
+    run.compress(torch.from_numpy(g2).to(DEV), beta)
+    m_after_gather = ost.m.copy()
+    oracle.compress(d, n, L, ost.m, g2, ost.werr, ost.packed, ost.scales, beta)
+    assert np.array_equal(host(run.m), m_after_gather), "gathered momentum must be a bit-exact copy"
+    same_words(host(run.packed), ost.packed, "packed (second step)")
+    close(host(run.scales), ost.scales, "scales (second step)")
+    run.finalize()
     close(host(run.werr), ost.werr, "worker_err")
     close(host(run.serr), ost.serr, "server_err")
     torch.cuda.synchronize()
     run.close()
 
 
-@pytest.mark.parametrize("deferred", [False, True], ids=["eager", "deferred"])
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
 def test_tiny_trajectory(deferred):
-    """Config 'tiny' (d = 2^20, n = 4, chunk 2^16): 10 compressed steps, every buffer, every step."""
+    """Config 'tiny' (d = 2^20, n = 4, chunk 2^16): 10 compressed steps, every buffer, every step.
+    Pending buffers are compared where they become final: the momentum right after the compress that
+    writes it, the errors at a mid-run and at the closing finalize."""
     wl = W.TINY
     st = W.host_state(wl)
     ost = oracle_state(wl.d_pad, wl.n, wl.L, st)
     run = from_host_state(wl, st, DEV, deferred=deferred)
     gd = torch.empty(wl.n, wl.d_pad, dtype=torch.float32, device=DEV)
     equal_scales = 0
+    sscales_equal = True
     for step in range(wl.steps):
-        say("tiny trajectory step %d deferred=%s" % (step, deferred))
+        say("tiny trajectory step %d mode=%d" % (step, deferred))
         g = W.host_grad(wl, step)
         gd.copy_(torch.from_numpy(g))
-        run.step(gd, wl.beta, wl.lr, wl.eps)
+        run.compress(gd, wl.beta)
+        compare_momentum(run, ost.m, sscales_equal, "after compress of step %d" % step)
+        run.server_reduce()
+        run.apply(wl.lr, wl.eps)
         ost.step(g, wl.beta, wl.lr, wl.eps)
-        if deferred and step in (4, wl.steps - 1):
-            run.finalize_errors()            # mid-run and final: pending -> delta, then carry on
-        compare_all(run, ost, "step %d" % step, errors=(not deferred) or step in (4, wl.steps - 1))
+        final = step in (4, wl.steps - 1)
+        if final:
+            run.finalize()                   # mid-run and at the end: pending -> final, then carry on
+        compare_all(run, ost, "step %d" % step, errors=final or not (deferred & B.APMS_DEFER_ERRORS),
+                    momentum=final or not (deferred & B.APMS_DEFER_GATHER))
+        sscales_equal = np.array_equal(host(run.sscales), ost.sscales)
         equal_scales += int(np.array_equal(host(run.scales), ost.scales))
     assert equal_scales >= wl.steps - 1
     run.close()
@@ -162,7 +187,7 @@ def test_worker_counts(n):
         g = W.host_grad(wl, step)
         run.step(torch.from_numpy(g).to(DEV), 0.9, 1e-4, 1e-8)
         ost.step(g, 0.9, 1e-4, 1e-8)
-    run.finalize_errors()
+    run.finalize()
     compare_all(run, ost, "n=%d" % n)
     run.close()
 
@@ -190,7 +215,7 @@ def test_empty_problem_on_device():
     run = DeviceRun(0, 3, 64, DEV)
     g = torch.empty(3, 0, dtype=torch.float32, device=DEV)
     run.step(g, 0.9, 1e-4, 1e-8)
-    run.finalize_errors()
+    run.finalize()
     torch.cuda.synchronize()
     run.close()
 
@@ -218,7 +243,8 @@ def test_determinism_and_tile_plan_independence():
 
 
 def test_pending_buffer_state_machine():
-    """Deferred mode remembers which buffer holds u; a different buffer is refused until finalize."""
+    """Deferred modes remember which buffer is pending; a call that would lose or read pending state is
+    refused until apms_finalize."""
     n, L, C = 2, 4096, 1
     d = L * C
     st, g = random_case(77, d, n, L)
@@ -229,9 +255,23 @@ def test_pending_buffer_state_machine():
     with pytest.raises(B.ApmsError) as ei:
         B.apms_compress(run.ctx, run.m, gd, other, run.packed, run.scales, 0.9)
     assert ei.value.status == B.APMS_ESTATE
-    run.finalize_errors()
+    run.finalize()
     B.apms_compress(run.ctx, run.m, gd, other, run.packed, run.scales, 0.9)    # now fine
-    B.apms_finalize_errors(run.ctx, other, None)
+    B.apms_finalize(run.ctx, other, None, None)
+    # gather pending after apply: the sign words must survive, m must be the same buffer
+    run.server_reduce()
+    run.apply(1e-4, 1e-8)
+    other_m = torch.zeros_like(run.m)
+    for call in (lambda: run.server_reduce(),
+                 lambda: B.apms_compress(run.ctx, other_m, gd, run.werr, run.packed, run.scales, 0.9),
+                 lambda: run.freeze(),
+                 lambda: run.warmup_step(gd, 1e-3, 0.9, 0.999, 1e-8, 1)):
+        with pytest.raises(B.ApmsError) as ei:
+            call()
+        assert ei.value.status == B.APMS_ESTATE
+    run.finalize()
+    run.server_reduce()                                                        # now fine
+    run.finalize()
     torch.cuda.synchronize()
     run.close()
 
@@ -292,7 +332,7 @@ def test_warmup_freeze_then_compressed():
         g = W.host_grad(wl, wl.warmup_steps + step)
         run.step(torch.from_numpy(g).to(DEV), wl.beta, wl.lr, wl.eps)
         ost.step(g, wl.beta, wl.lr, wl.eps)
-        compare_all(run, ost, "pipeline step %d" % step, errors=False)
-    run.finalize_errors()
+        compare_all(run, ost, "pipeline step %d" % step, errors=False, momentum=False)
+    run.finalize()
     compare_all(run, ost, "pipeline end")
     run.close()
