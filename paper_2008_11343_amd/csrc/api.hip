@@ -46,9 +46,9 @@ constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
 // Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize).  Measured on MI355X:
-// the worker kernel streams fastest with 3 workgroups (12 waves) per CU, the small-tile kernels with as
+// the worker kernel streams fastest with 2 workgroups (8 waves) per CU, the small-tile kernels with as
 // many as fit.
-constexpr int32_t kDefaultLdsPad[4] = {40 * 1024, 0, 0, 0};
+constexpr int32_t kDefaultLdsPad[4] = {64 * 1024, 0, 0, 0};
 
 struct Range {
     const void* p;
