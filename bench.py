@@ -114,11 +114,18 @@ def main():
     d, n, L = wl.d_pad, wl.n, wl.L
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))
-    st = W.device_state(wl, dev)
     deferral = {"deferred": B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, "deferred-errors": B.APMS_DEFER_ERRORS,
                 "eager": 0}[args.mode]
-    run = DeviceRun(d, n, L, dev, deferred=deferral, state=st)
-    del st
+    warm = None
+    if wl.warmup_steps:
+        # full pipeline: Adam warm-up on the averaged gradients (Algorithm 1 line 2), then freeze v
+        st = W.device_state(wl, dev, warm_start=True)
+        run = DeviceRun(d, n, L, dev, deferred=deferral)
+        run.x.copy_(st["x"])
+        run.v.zero_()
+        del st
+    else:
+        run = DeviceRun(d, n, L, dev, deferred=deferral, state=W.device_state(wl, dev))
     if args.compress_tiles or args.server_tiles:
         B.apms_set_tiles_per_block(run.ctx, args.compress_tiles, args.server_tiles)
     kernel_ids = {"compress": B.APMS_KERNEL_COMPRESS, "server": B.APMS_KERNEL_SERVER,
@@ -132,7 +139,7 @@ def main():
 
     def one_step(step, events=None):
         if step == 0 or not args.reuse_grad:
-            W.device_grad_(wl, step, g)
+            W.device_grad_(wl, wl.warmup_steps + step, g)
         if events is not None:
             events[0].record(stream)
         run.compress(g, wl.beta)
@@ -145,6 +152,19 @@ def main():
         if events is not None:
             events[3].record(stream)
 
+    if wl.warmup_steps:
+        wev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * wl.warmup_steps)]
+        for t in range(1, wl.warmup_steps + 1):
+            W.device_grad_(wl, t - 1, g)
+            wev[2 * t - 2].record(stream)
+            run.warmup_step(g, 1e-3, wl.beta, wl.beta2, wl.eps, t)
+            wev[2 * t - 1].record(stream)
+        run.freeze()
+        torch.cuda.synchronize()
+        wms = sorted(wev[2 * i].elapsed_time(wev[2 * i + 1]) for i in range(wl.warmup_steps))
+        warm = {"steps": wl.warmup_steps, "ms_per_step_median": wms[len(wms) // 2],
+                "GBps": d * (4.0 * n + 24.0) / (wms[len(wms) // 2] * 1e-3) / 1e9}
+        log("Adam warm-up: %d steps, median %.3f ms (%.0f GB/s), then freeze" % (warm["steps"], warm["ms_per_step_median"], warm["GBps"]))
     if args.calibration_copy:
         W.device_grad_(wl, 0, g)
         run.werr.copy_(g)
@@ -206,6 +226,7 @@ def main():
             "plan": {k: plan[k] for k in ("compress_tiles_per_block", "compress_grid", "server_tiles_per_block",
                                           "server_grid", "apply_grid", "occupancy_pad")},
             "wall_s_including_input_generation": wall,
+            "adam_warmup": warm,
             "device": torch.cuda.get_device_name(0),
         },
         "roofline": {

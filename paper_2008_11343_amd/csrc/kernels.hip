@@ -366,41 +366,40 @@ __global__ __launch_bounds__(kThreads) void warmup_kernel(float* __restrict__ x,
                                                           int64_t d, int32_t n, float lr, float beta1,
                                                           float omb1, float beta2, float omb2, float bc1,
                                                           float bc2, float eps, float inv_n) {
-    const int64_t quads = d >> 2;
-    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    for (int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; q < quads; q += stride) {
-        const int64_t p = q << 2;
-        f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll 4
-        for (int32_t i = 0; i < n; ++i) {
-            const f32x4 gi = load_stream(g + static_cast<int64_t>(i) * d + p);
+    // one 128-bit quad per thread, one short-lived workgroup per 1024 elements
+    const int64_t q = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (q >= (d >> 2)) return;
+    const int64_t p = q << 2;
+    f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+    for (int32_t i = 0; i < n; ++i) {
+        const f32x4 gi = load_stream(g + static_cast<int64_t>(i) * d + p);
 #pragma unroll
-            for (int c = 0; c < 4; ++c) acc[c] = acc[c] + gi[c];
-        }
-        const f32x4 mo = load_stream(m + p), vo = load_stream(v + p), xo = load_stream(x + p);
-        f32x4 mn, vn, xn;
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            const float gbar = acc[c] * inv_n;
-            const float m_keep = beta1 * mo[c];
-            const float m_inc = omb1 * gbar;
-            mn[c] = m_keep + m_inc;
-            const float gsq = gbar * gbar;
-            const float v_keep = beta2 * vo[c];
-            const float v_inc = omb2 * gsq;
-            vn[c] = v_keep + v_inc;
-            const float mhat = mn[c] / bc1;
-            const float vhat = vn[c] / bc2;
-            const float root = sqrtf(vhat);
-            const float denom = root + eps;
-            const float ratio = mhat / denom;
-            const float step = lr * ratio;
-            xn[c] = xo[c] - step;
-        }
-        store_stream(m + p, mn);
-        store_stream(v + p, vn);
-        store_stream(x + p, xn);
+        for (int c = 0; c < 4; ++c) acc[c] = acc[c] + gi[c];      // worker order 0..n-1
     }
+    const f32x4 mo = load_stream(m + p), vo = load_stream(v + p), xo = load_stream(x + p);
+    f32x4 mn, vn, xn;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const float gbar = acc[c] * inv_n;
+        const float m_keep = beta1 * mo[c];
+        const float m_inc = omb1 * gbar;
+        mn[c] = m_keep + m_inc;
+        const float gsq = gbar * gbar;
+        const float v_keep = beta2 * vo[c];
+        const float v_inc = omb2 * gsq;
+        vn[c] = v_keep + v_inc;
+        const float mhat = mn[c] / bc1;
+        const float vhat = vn[c] / bc2;
+        const float root = sqrtf(vhat);
+        const float denom = root + eps;
+        const float ratio = mhat / denom;
+        const float step = lr * ratio;
+        xn[c] = xo[c] - step;
+    }
+    store_stream(m + p, mn);
+    store_stream(v + p, vn);
+    store_stream(x + p, xn);
 }
 
 __global__ __launch_bounds__(kThreads) void freeze_kernel(float* __restrict__ m, float* __restrict__ werr,
@@ -519,7 +518,8 @@ hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, con
                          float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
                          float bc2, float eps, float inv_n, hipStream_t stream) {
     if (d <= 0) return hipSuccess;
-    hipLaunchKernelGGL(warmup_kernel, dim3(stride_grid(d)), dim3(kThreads), 0, stream, x, m, v, g, d, n, lr,
+    const int64_t blocks = ((d >> 2) + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(warmup_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, x, m, v, g, d, n, lr,
                        beta1, one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
     return hipGetLastError();
 }

@@ -336,3 +336,42 @@ def test_warmup_freeze_then_compressed():
     run.finalize()
     compare_all(run, ost, "pipeline end")
     run.close()
+
+
+def test_hip_graph_replay_matches_eager():
+    """The step allocates nothing, never synchronises and records no memset, so a steady-state step can be
+    captured in a HIP graph: replays (with fresh gradients in the same buffer, and the program's own
+    eager work and synchronisations in between) must give the bits of the eager path, every time."""
+    wl = W.scaled(W.TINY, 4096 * 40, chunk=4096 * 10)
+    st = W.host_state(wl)
+    runs = [from_host_state(wl, st, DEV, deferred=True) for _ in range(2)]
+    graphed, eager = runs
+    gd = torch.empty(wl.n, wl.d_pad, dtype=torch.float32, device=DEV)
+    for step in range(2):                       # reach the steady state: errors and gather pending
+        gd.copy_(torch.from_numpy(W.host_grad(wl, step)))
+        for r in runs:
+            r.step(gd, wl.beta, wl.lr, wl.eps)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        graphed.step(gd, wl.beta, wl.lr, wl.eps)
+    torch.cuda.synchronize()
+    scratch = torch.empty(1 << 20, device=DEV)
+    for step in range(2, 7):
+        say("graph replay for step %d" % step)
+        gd.copy_(torch.from_numpy(W.host_grad(wl, step)))
+        torch.cuda.synchronize()
+        graph.replay()
+        scratch.normal_()                       # unrelated eager work between replays
+        eager.step(gd, wl.beta, wl.lr, wl.eps)
+        torch.cuda.synchronize()
+        for name in ("packed", "scales", "spacked", "sscales", "x"):
+            assert torch.equal(getattr(graphed, name), getattr(eager, name)), "replay of step %d: %s" % (step, name)
+    for r in runs:
+        r.finalize()
+    torch.cuda.synchronize()
+    for name in ("m", "werr", "serr"):
+        assert torch.equal(getattr(graphed, name), getattr(eager, name)), name
+    for r in runs:
+        r.close()
