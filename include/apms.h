@@ -63,6 +63,10 @@ typedef enum apms_status {
 
 #define APMS_DEVICE_NONE (-1)
 
+/* Element type of 16-bit gradient inputs (apms_compress_g16, apms_warmup_step_g16). */
+#define APMS_GRAD_F16 1  /* IEEE binary16 */
+#define APMS_GRAD_BF16 2 /* bfloat16: the upper 16 bits of a binary32 */
+
 /* Deferral flags for apms_set_deferral (0 = everything eager, the default). */
 #define APMS_DEFER_ERRORS 1 /* error buffers hold the compensated vector u; delta = u - C[u] is formed on next read */
 #define APMS_DEFER_GATHER 2 /* apms_apply leaves m untouched; the next apms_compress writes the gathered momentum */
@@ -177,6 +181,14 @@ int apms_warmup_step(apms_ctx *ctx, float *x, float *m, float *v, const float *g
                      float lr, float beta1, float beta2, float eps, int64_t t, void *stream);
 
 /*
+ * The same step with 16-bit gradients (Section 5.1 reports "float16 type training"): g is [n][d]
+ * binary16 or bfloat16 values (grad_format = APMS_GRAD_F16 / APMS_GRAD_BF16).  Every value is widened
+ * to binary32 exactly, then the arithmetic is that of apms_warmup_step.  EINVAL for another format.
+ */
+int apms_warmup_step_g16(apms_ctx *ctx, float *x, float *m, float *v, const uint16_t *g, int grad_format,
+                         float lr, float beta1, float beta2, float eps, int64_t t, void *stream);
+
+/*
  * Hand-over from warm-up to the compression stage (Algorithm 1, line 1
  * initial errors = 0, and line 3): replicate worker 0's momentum slice to all
  * n slices and zero both error buffers; v is frozen simply by no longer
@@ -203,6 +215,14 @@ int apms_freeze(apms_ctx *ctx, float *m, float *worker_err, float *server_err, v
  */
 int apms_compress(apms_ctx *ctx, float *m, const float *g, float *worker_err,
                   uint32_t *packed, float *scales, float beta, void *stream);
+
+/*
+ * apms_compress with 16-bit gradients: g is [n][d] binary16 or bfloat16 values, widened to binary32
+ * exactly before the same arithmetic; everything else as apms_compress (2n fewer bytes read per
+ * parameter).  EINVAL for another format.
+ */
+int apms_compress_g16(apms_ctx *ctx, float *m, const uint16_t *g, int grad_format, float *worker_err,
+                      uint32_t *packed, float *scales, float beta, void *stream);
 
 /*
  * Server side (Algorithm 1 line 9; supplement step 2), for all C chunks:

@@ -18,6 +18,8 @@ import numpy as np
 
 ONEBIT = 0
 IDENTITY = 1
+GRAD_F16 = 1
+GRAD_BF16 = 2
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "apms_oracle.c")
@@ -49,6 +51,8 @@ def _load():
         lib.apms_oracle_apply.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32, f32]
         lib.apms_oracle_warmup_step.argtypes = [i64, i32, ptr, ptr, ptr, ptr, f32, f32, f32, f32, i64]
         lib.apms_oracle_freeze.argtypes = [i64, i32, ptr, ptr, ptr, ptr]
+        lib.apms_oracle_widen_g16.argtypes = [ctypes.c_int, i64, ptr, ptr]
+        lib.apms_oracle_widen_g16.restype = ctypes.c_int
         for fn in (lib.apms_oracle_compress, lib.apms_oracle_server_reduce, lib.apms_oracle_apply,
                    lib.apms_oracle_warmup_step, lib.apms_oracle_freeze):
             fn.restype = ctypes.c_int
@@ -121,6 +125,18 @@ def freeze(d, n, m_warm, m, werr, serr):
     """Warm-up -> compression stage hand-over: replicate m, zero both errors."""
     f = np.float32
     _load().apms_oracle_freeze(d, n, _p(m_warm, f, d), _p(m, f, n * d), _p(werr, f, n * d), _p(serr, f, d))
+
+
+def widen_g16(g16, fmt):
+    """binary16 (GRAD_F16) or bfloat16 (GRAD_BF16) bit patterns (uint16 array) -> float32 array, same shape."""
+    if not (isinstance(g16, np.ndarray) and g16.dtype == np.uint16 and g16.flags["C_CONTIGUOUS"]):
+        raise TypeError("expected a C-contiguous uint16 array")
+    out = np.empty(g16.shape, np.float32)
+    rc = _load().apms_oracle_widen_g16(fmt, g16.size, g16.ctypes.data_as(ctypes.c_void_p),
+                                       out.ctypes.data_as(ctypes.c_void_p))
+    if rc:
+        raise ValueError("unknown 16-bit gradient format %r" % (fmt,))
+    return out
 
 
 class State:

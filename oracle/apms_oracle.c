@@ -316,3 +316,42 @@ int apms_oracle_freeze(int64_t d, int32_t n, const float *m_warm, float *m,
     memset(serr, 0, (size_t)d * sizeof(float));
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* 16-bit gradient inputs (Section 5.1 mentions "float16 type training").   */
+/* ------------------------------------------------------------------------ */
+
+#define APMS_ORACLE_GRAD_F16 1  /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
+#define APMS_ORACLE_GRAD_BF16 2 /* bfloat16: 1 sign, 8 exponent (bias 127), 7 fraction bits     */
+
+/*
+ * Widen 16-bit gradient values to binary32.  Every binary16 / bfloat16 value is
+ * exactly representable in binary32, so this is the value map of the formats'
+ * definitions, written out with ldexp; the step itself then runs on the widened
+ * values with the arithmetic stated at the top of this file.  NaN payloads are
+ * not preserved (NaN is outside the contract).
+ */
+int apms_oracle_widen_g16(int format, int64_t count, const uint16_t *in, float *out)
+{
+    const int exp_bits = (format == APMS_ORACLE_GRAD_F16) ? 5 : 8;
+    const int frac_bits = 15 - exp_bits;
+    const int bias = (1 << (exp_bits - 1)) - 1;
+    const int exp_max = (1 << exp_bits) - 1;
+    if (format != APMS_ORACLE_GRAD_F16 && format != APMS_ORACLE_GRAD_BF16)
+        return -1;
+    for (int64_t j = 0; j < count; ++j) {
+        const unsigned h = in[j];
+        const int negative = (h >> 15) & 1;
+        const int e = (h >> frac_bits) & exp_max;
+        const int f = h & ((1 << frac_bits) - 1);
+        double value;
+        if (e == exp_max)
+            value = f ? NAN : INFINITY;
+        else if (e == 0)
+            value = ldexp((double)f, 1 - bias - frac_bits);              /* zero and subnormals */
+        else
+            value = ldexp((double)((1 << frac_bits) + f), e - bias - frac_bits);
+        out[j] = (float)(negative ? -value : value);
+    }
+    return 0;
+}

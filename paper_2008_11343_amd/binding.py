@@ -18,6 +18,8 @@ APMS_OK = 0
 APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS_EALIAS, APMS_ESTATE = (
     -1, -2, -3, -4, -5, -6, -7, -8)
 APMS_DEVICE_NONE = -1
+APMS_GRAD_F16 = 1
+APMS_GRAD_BF16 = 2
 APMS_DEFER_ERRORS = 1
 APMS_DEFER_GATHER = 2
 APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE = 0, 1, 2, 3
@@ -25,7 +27,7 @@ APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZ
 EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
     "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
-    "apms_freeze", "apms_compress", "apms_server_reduce", "apms_apply",
+    "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
 )
 
 
@@ -84,6 +86,8 @@ def load():
         "apms_set_deferral": (ci, [vp, ci]),
         "apms_finalize": (ci, [vp, vp, vp, vp, vp]),
         "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
+        "apms_warmup_step_g16": (ci, [vp, vp, vp, vp, vp, ci, f32, f32, f32, f32, i64, vp]),
+        "apms_compress_g16": (ci, [vp, vp, vp, ci, vp, vp, vp, f32, vp]),
         "apms_freeze": (ci, [vp, vp, vp, vp, vp]),
         "apms_compress": (ci, [vp, vp, vp, vp, vp, vp, f32, vp]),
         "apms_server_reduce": (ci, [vp, vp, vp, vp, vp, vp, vp]),
@@ -167,6 +171,16 @@ def apms_finalize(ctx, worker_err=None, server_err=None, m=None, stream=None):
 def apms_warmup_step(ctx, x, m, v, g, lr, beta1, beta2, eps, t, stream=None):
     _check(ctx, load().apms_warmup_step(ctx, _ptr(x), _ptr(m), _ptr(v), _ptr(g), lr, beta1, beta2, eps, t,
                                         _stream(stream)), "apms_warmup_step")
+
+
+def apms_warmup_step_g16(ctx, x, m, v, g, grad_format, lr, beta1, beta2, eps, t, stream=None):
+    _check(ctx, load().apms_warmup_step_g16(ctx, _ptr(x), _ptr(m), _ptr(v), _ptr(g), grad_format, lr, beta1, beta2,
+                                            eps, t, _stream(stream)), "apms_warmup_step_g16")
+
+
+def apms_compress_g16(ctx, m, g, grad_format, worker_err, packed, scales, beta, stream=None):
+    _check(ctx, load().apms_compress_g16(ctx, _ptr(m), _ptr(g), grad_format, _ptr(worker_err), _ptr(packed),
+                                         _ptr(scales), beta, _stream(stream)), "apms_compress_g16")
 
 
 def apms_freeze(ctx, m, worker_err, server_err, stream=None):

@@ -295,11 +295,26 @@ int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, v
     return APMS_OK;
 }
 
-int apms_warmup_step(apms_ctx* c, float* x, float* m, float* v, const float* g, float lr, float beta1,
-                     float beta2, float eps, int64_t t, void* stream) {
+}  // extern "C"
+
+namespace {
+
+int grad_elem_bytes(int grad_format) {
+    switch (grad_format) {
+        case apms::kGradF32: return 4;
+        case APMS_GRAD_F16:
+        case APMS_GRAD_BF16: return 2;
+        default: return 0;
+    }
+}
+
+int warmup_impl(apms_ctx* c, float* x, float* m, float* v, const void* g, int grad_format, float lr, float beta1,
+                float beta2, float eps, int64_t t, void* stream) {
     if (!c) return APMS_EINVAL;
+    const int gbytes = grad_elem_bytes(grad_format);
+    if (!gbytes) return APMS_EINVAL;
     const int64_t vec = c->d * 4;
-    const Range r[] = {{x, vec}, {m, vec}, {v, vec}, {g, vec * c->n}};
+    const Range r[] = {{x, vec}, {m, vec}, {v, vec}, {g, c->d * gbytes * c->n}};
     if (int rc = check_arrays(r, 4)) return rc;
     if (!unit_interval(beta1) || !unit_interval(beta2) || t < 1 || !(lr == lr) || !(eps == eps))
         return APMS_EINVAL;
@@ -311,9 +326,64 @@ int apms_warmup_step(apms_ctx* c, float* x, float* m, float* v, const float* g, 
     const float bc1 = static_cast<float>(1.0 - std::pow(static_cast<double>(beta1), static_cast<double>(t)));
     const float bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(t)));
     const float inv_n = 1.0f / static_cast<float>(c->n);
-    hipError_t e = apms::launch_warmup(c->d, c->n, x, m, v, g, lr, beta1, 1.0f - beta1, beta2, 1.0f - beta2,
-                                       bc1, bc2, eps, inv_n, static_cast<hipStream_t>(stream));
+    hipError_t e = apms::launch_warmup(c->d, c->n, x, m, v, g, grad_format, lr, beta1, 1.0f - beta1, beta2,
+                                       1.0f - beta2, bc1, bc2, eps, inv_n, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
+int compress_impl(apms_ctx* c, float* m, const void* g, int grad_format, float* worker_err, uint32_t* packed,
+                  float* scales, float beta, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int gbytes = grad_elem_bytes(grad_format);
+    if (!gbytes) return APMS_EINVAL;
+    const int64_t all = c->d * 4 * c->n;
+    const bool gather = c->pending_m != nullptr;
+    const Range r[] = {{m, all}, {g, c->d * gbytes * c->n}, {worker_err, all}, {packed, all / 32},
+                       {scales, c->n * c->C * 4}, {c->pending_spacked, gather ? c->d / 8 : 0}};
+    if (int rc = check_arrays(r, 6)) return rc;
+    if (!unit_interval(beta)) return APMS_EINVAL;
+    if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
+    if (gather && c->pending_m != m) return APMS_ESTATE;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const apms::Geometry geo = geometry(c);
+    const float* prev = c->pending_werr ? c->w_pending : nullptr;
+    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, grad_format,
+                                         worker_err, packed, c->w_partials, prev,
+                                         gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
+                                         beta, 1.0f - beta, c->lds_pad[APMS_KERNEL_COMPRESS], s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    // from here on m holds the gathered momentum, the error buffer holds u and the context its scales
+    c->pending_m = nullptr;
+    c->pending_spacked = nullptr;
+    c->pending_werr = worker_err;
+    e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
+                            c->w_pending, s);
+    if (e != hipSuccess) return hip_fail(c, e);
+    if (!(c->deferral & APMS_DEFER_ERRORS)) {
+        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
+        if (e != hipSuccess) return hip_fail(c, e);
+        c->pending_werr = nullptr;
+    }
+    return APMS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int apms_warmup_step(apms_ctx* c, float* x, float* m, float* v, const float* g, float lr, float beta1,
+                     float beta2, float eps, int64_t t, void* stream) {
+    return warmup_impl(c, x, m, v, g, apms::kGradF32, lr, beta1, beta2, eps, t, stream);
+}
+
+int apms_warmup_step_g16(apms_ctx* c, float* x, float* m, float* v, const uint16_t* g, int grad_format, float lr,
+                         float beta1, float beta2, float eps, int64_t t, void* stream) {
+    if (grad_format != APMS_GRAD_F16 && grad_format != APMS_GRAD_BF16) return APMS_EINVAL;
+    return warmup_impl(c, x, m, v, g, grad_format, lr, beta1, beta2, eps, t, stream);
 }
 
 int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, void* stream) {
@@ -335,40 +405,13 @@ int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, voi
 
 int apms_compress(apms_ctx* c, float* m, const float* g, float* worker_err, uint32_t* packed, float* scales,
                   float beta, void* stream) {
-    if (!c) return APMS_EINVAL;
-    const int64_t all = c->d * 4 * c->n;
-    const bool gather = c->pending_m != nullptr;
-    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4},
-                       {c->pending_spacked, gather ? c->d / 8 : 0}};
-    if (int rc = check_arrays(r, 6)) return rc;
-    if (!unit_interval(beta)) return APMS_EINVAL;
-    if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
-    if (gather && c->pending_m != m) return APMS_ESTATE;
-    int status;
-    if (!ready_to_launch(c, &status)) return status;
-    DeviceScope scope(c->device);
-    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    const apms::Geometry geo = geometry(c);
-    const float* prev = c->pending_werr ? c->w_pending : nullptr;
-    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, worker_err,
-                                         packed, c->w_partials, prev, gather ? c->pending_spacked : nullptr,
-                                         gather ? c->g_pending : nullptr, beta, 1.0f - beta,
-                                         c->lds_pad[APMS_KERNEL_COMPRESS], s);
-    if (e != hipSuccess) return hip_fail(c, e);
-    // from here on m holds the gathered momentum, the error buffer holds u and the context its scales
-    c->pending_m = nullptr;
-    c->pending_spacked = nullptr;
-    c->pending_werr = worker_err;
-    e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
-                            c->w_pending, s);
-    if (e != hipSuccess) return hip_fail(c, e);
-    if (!(c->deferral & APMS_DEFER_ERRORS)) {
-        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
-        if (e != hipSuccess) return hip_fail(c, e);
-        c->pending_werr = nullptr;
-    }
-    return APMS_OK;
+    return compress_impl(c, m, g, apms::kGradF32, worker_err, packed, scales, beta, stream);
+}
+
+int apms_compress_g16(apms_ctx* c, float* m, const uint16_t* g, int grad_format, float* worker_err,
+                      uint32_t* packed, float* scales, float beta, void* stream) {
+    if (grad_format != APMS_GRAD_F16 && grad_format != APMS_GRAD_BF16) return APMS_EINVAL;
+    return compress_impl(c, m, g, grad_format, worker_err, packed, scales, beta, stream);
 }
 
 int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales, float* server_err,

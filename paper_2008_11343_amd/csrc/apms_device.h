@@ -43,6 +43,26 @@ __device__ __forceinline__ void store_stream(float* p, f32x4 v) {
     __builtin_nontemporal_store(v, reinterpret_cast<f32x4*>(p));
 }
 
+// Four consecutive gradient values starting at element p, widened to binary32 (exact for both 16-bit
+// formats: binary16 through the hardware conversion, bfloat16 by placing its bits in the upper half).
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x4 __attribute__((ext_vector_type(4)));
+template <int G>
+__device__ __forceinline__ f32x4 load_grad4(const void* g, int64_t p) {
+    if constexpr (G == kGradF32) {
+        return load_stream(static_cast<const float*>(g) + p);
+    } else if constexpr (G == kGradF16) {
+        const f16x4 h = __builtin_nontemporal_load(reinterpret_cast<const f16x4*>(static_cast<const _Float16*>(g) + p));
+        return f32x4{static_cast<float>(h.x), static_cast<float>(h.y), static_cast<float>(h.z), static_cast<float>(h.w)};
+    } else {
+        const u16x4 h = __builtin_nontemporal_load(reinterpret_cast<const u16x4*>(static_cast<const uint16_t*>(g) + p));
+        f32x4 out;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) out[c] = __builtin_bit_cast(float, static_cast<uint32_t>(h[c]) << 16);
+        return out;
+    }
+}
+
 // +s where the bit is set, -s where it is clear.
 __device__ __forceinline__ float signed_scale(bool positive, float s) {
     return positive ? s : -s;

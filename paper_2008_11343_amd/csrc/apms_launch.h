@@ -22,6 +22,11 @@ constexpr int kServerTile = tile_elems(kServerRows);
 constexpr int kApplyTile = tile_elems(kApplyRows);
 constexpr int kFinalizeTile = tile_elems(kFinalizeRows);
 
+// Element type of the gradient input (values match APMS_GRAD_* of the C ABI, 0 = binary32).
+constexpr int kGradF32 = 0;
+constexpr int kGradF16 = 1;
+constexpr int kGradBF16 = 2;
+
 // Problem geometry shared by the chunked kernels.
 struct Geometry {
     int64_t d;   // vector length
@@ -45,9 +50,9 @@ inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L 
 // tiles_per_block consecutive tiles of kCompressTile elements.  prev_scales (nullable, [n*C]) marks werr
 // as holding last step's u (deferred form).  gather_words ([d/32]) + gather_scales ([C]), both nullable
 // together, mark a deferred gather: the kernel then decodes the momentum from them, writes it to all of
-// m and does not read m.
+// m and does not read m.  g holds grad_format elements (kGradF32 / kGradF16 / kGradBF16).
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
-                           const float* g, float* werr, uint32_t* packed, double* partials,
+                           const void* g, int grad_format, float* werr, uint32_t* packed, double* partials,
                            const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
                            float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream);
 
@@ -73,8 +78,8 @@ hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const floa
                         float* x, float* m, float* scales_copy, bool write_m, bool model_step, float lr,
                         float eps, int32_t lds_pad, hipStream_t stream);
 
-// Adam warm-up step on the averaged gradient.
-hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,
+// Adam warm-up step on the averaged gradient (g in grad_format).
+hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const void* g, int grad_format, float lr,
                          float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
                          float bc2, float eps, float inv_n, hipStream_t stream);
 

@@ -52,8 +52,8 @@ __device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
 // kGather: a deferred gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum of
 // every worker is the decoded server message (gather_words, gather_scale); write it to m and use it
 // directly instead of reading m back.
-template <bool kFull, bool kGather>
-__device__ __forceinline__ void compress_tile(float* __restrict__ m, const float* __restrict__ g,
+template <bool kFull, bool kGather, int G>
+__device__ __forceinline__ void compress_tile(float* __restrict__ m, const void* __restrict__ g,
                                               float* __restrict__ e, uint32_t* __restrict__ packed,
                                               const uint32_t* __restrict__ gather_words, float gather_scale,
                                               int64_t vec_base, int64_t chunk_base, int64_t tile_off, int64_t L,
@@ -74,7 +74,7 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const float
                 gw[r] = gather_words[(vec_base + off0 + 32 * r) >> 5];
             else
                 vm[r] = load_stream(m + p);
-            vg[r] = load_stream(g + p);
+            vg[r] = load_grad4<G>(g, p);
             ve[r] = load_stream(e + p);
         }
     }
@@ -103,9 +103,9 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const float
     }
 }
 
-template <bool kGather>
+template <bool kGather, int G>
 __global__ __launch_bounds__(kThreads) void compress_kernel(
-    float* __restrict__ m, const float* __restrict__ g, float* __restrict__ e, uint32_t* __restrict__ packed,
+    float* __restrict__ m, const void* __restrict__ g, float* __restrict__ e, uint32_t* __restrict__ packed,
     double* __restrict__ partials, const float* __restrict__ prev_scales,
     const uint32_t* __restrict__ gather_words, const float* __restrict__ gather_scales, int64_t d, int64_t L,
     int32_t C, int32_t tiles_per_chunk, int32_t tiles_per_block, int32_t blocks_per_chunk, float beta,
@@ -129,10 +129,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     for (int32_t t = t0; t < t1; ++t) {
         const int64_t tile_off = static_cast<int64_t>(t) * kCompressTile;
         if (tile_off + kCompressTile <= L)
-            compress_tile<true, kGather>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+            compress_tile<true, kGather, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
                                          tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
         else
-            compress_tile<false, kGather>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+            compress_tile<false, kGather, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
                                           tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
     }
     const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
@@ -361,8 +361,9 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restr
 // Warm-up: original Adam on the averaged gradient (Section 3.2).
 // ------------------------------------------------------------------------
 
+template <int G>
 __global__ __launch_bounds__(kThreads) void warmup_kernel(float* __restrict__ x, float* __restrict__ m,
-                                                          float* __restrict__ v, const float* __restrict__ g,
+                                                          float* __restrict__ v, const void* __restrict__ g,
                                                           int64_t d, int32_t n, float lr, float beta1,
                                                           float omb1, float beta2, float omb2, float bc1,
                                                           float bc2, float eps, float inv_n) {
@@ -373,7 +374,7 @@ __global__ __launch_bounds__(kThreads) void warmup_kernel(float* __restrict__ x,
     f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 8
     for (int32_t i = 0; i < n; ++i) {
-        const f32x4 gi = load_stream(g + static_cast<int64_t>(i) * d + p);
+        const f32x4 gi = load_grad4<G>(g, static_cast<int64_t>(i) * d + p);
 #pragma unroll
         for (int c = 0; c < 4; ++c) acc[c] = acc[c] + gi[c];      // worker order 0..n-1
     }
@@ -430,36 +431,64 @@ inline uint32_t stride_grid(int64_t d) {
 
 }  // namespace
 
+namespace {
+
+template <bool kGather, int G>
+void launch_compress_as(int64_t grid, int32_t lds_pad, hipStream_t stream, float* m, const void* g, float* werr,
+                        uint32_t* packed, double* partials, const float* prev_scales, const uint32_t* gather_words,
+                        const float* gather_scales, const Geometry& geo, int32_t tpc, int32_t tiles_per_block,
+                        int32_t blocks_per_chunk, float beta, float omb) {
+    hipLaunchKernelGGL((compress_kernel<kGather, G>), dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad,
+                       stream, m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
+                       geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, omb);
+}
+
+template <int G>
+hipError_t set_compress_lds_limit() {
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(compress_kernel<false, G>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+    if (e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(compress_kernel<true, G>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+}
+
+}  // namespace
+
 hipError_t enable_large_lds_pads() {
-    const void* kernels[] = {reinterpret_cast<const void*>(compress_kernel<false>),
-                             reinterpret_cast<const void*>(compress_kernel<true>),
-                             reinterpret_cast<const void*>(server_kernel),
+    hipError_t e = set_compress_lds_limit<kGradF32>();
+    if (e == hipSuccess) e = set_compress_lds_limit<kGradF16>();
+    if (e == hipSuccess) e = set_compress_lds_limit<kGradBF16>();
+    if (e != hipSuccess) return e;
+    const void* kernels[] = {reinterpret_cast<const void*>(server_kernel),
                              reinterpret_cast<const void*>(apply_kernel<true, true>),
                              reinterpret_cast<const void*>(apply_kernel<false, true>),
                              reinterpret_cast<const void*>(apply_kernel<true, false>),
                              reinterpret_cast<const void*>(finalize_kernel)};
     for (const void* k : kernels) {
-        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+        e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
         if (e != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
-                           const float* g, float* werr, uint32_t* packed, double* partials,
+                           const void* g, int grad_format, float* werr, uint32_t* packed, double* partials,
                            const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
                            float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream) {
     const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile));
-    if (gather_words)
-        hipLaunchKernelGGL(compress_kernel<true>, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream,
-                           m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
-                           geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
-    else
-        hipLaunchKernelGGL(compress_kernel<false>, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream,
-                           m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
-                           geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta);
+#define APMS_COMPRESS_CASE(GATHER, G)                                                                         \
+    launch_compress_as<GATHER, G>(grid, lds_pad, stream, m, g, werr, packed, partials, prev_scales, gather_words, \
+                                  gather_scales, geo, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta)
+    const bool gather = gather_words != nullptr;
+    switch (grad_format) {
+        case kGradF32: if (gather) APMS_COMPRESS_CASE(true, kGradF32); else APMS_COMPRESS_CASE(false, kGradF32); break;
+        case kGradF16: if (gather) APMS_COMPRESS_CASE(true, kGradF16); else APMS_COMPRESS_CASE(false, kGradF16); break;
+        case kGradBF16: if (gather) APMS_COMPRESS_CASE(true, kGradBF16); else APMS_COMPRESS_CASE(false, kGradBF16); break;
+        default: return hipErrorInvalidValue;
+    }
+#undef APMS_COMPRESS_CASE
     return hipGetLastError();
 }
 
@@ -514,13 +543,26 @@ hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const floa
     return hipGetLastError();
 }
 
-hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const float* g, float lr,
+hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const void* g, int grad_format, float lr,
                          float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
                          float bc2, float eps, float inv_n, hipStream_t stream) {
     if (d <= 0) return hipSuccess;
-    const int64_t blocks = ((d >> 2) + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(warmup_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, x, m, v, g, d, n, lr,
-                       beta1, one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
+    const dim3 grid(static_cast<uint32_t>(((d >> 2) + kThreads - 1) / kThreads)), block(kThreads);
+    switch (grad_format) {
+        case kGradF32:
+            hipLaunchKernelGGL(warmup_kernel<kGradF32>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+                               one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
+            break;
+        case kGradF16:
+            hipLaunchKernelGGL(warmup_kernel<kGradF16>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+                               one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
+            break;
+        case kGradBF16:
+            hipLaunchKernelGGL(warmup_kernel<kGradBF16>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+                               one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
+            break;
+        default: return hipErrorInvalidValue;
+    }
     return hipGetLastError();
 }
 

@@ -58,8 +58,17 @@ class DeviceRun:
             pass
 
     # the three calls of one compressed step (Algorithm 1 lines 6-11)
+    @staticmethod
+    def _grad_format(g):
+        """0 for float32 gradients, APMS_GRAD_F16 / APMS_GRAD_BF16 for torch.float16 / torch.bfloat16."""
+        return {torch.float32: 0, torch.float16: B.APMS_GRAD_F16, torch.bfloat16: B.APMS_GRAD_BF16}[g.dtype]
+
     def compress(self, g, beta, stream=None):
-        B.apms_compress(self.ctx, self.m, g, self.werr, self.packed, self.scales, beta, stream)
+        fmt = self._grad_format(g)
+        if fmt:
+            B.apms_compress_g16(self.ctx, self.m, g, fmt, self.werr, self.packed, self.scales, beta, stream)
+        else:
+            B.apms_compress(self.ctx, self.m, g, self.werr, self.packed, self.scales, beta, stream)
 
     def server_reduce(self, stream=None):
         B.apms_server_reduce(self.ctx, self.packed, self.scales, self.serr, self.spacked, self.sscales, stream)
@@ -78,7 +87,11 @@ class DeviceRun:
 
     # warm-up (Algorithm 1 line 2) works on worker 0's momentum slice
     def warmup_step(self, g, lr, beta1, beta2, eps, t, stream=None):
-        B.apms_warmup_step(self.ctx, self.x, self.m[0], self.v, g, lr, beta1, beta2, eps, t, stream)
+        fmt = self._grad_format(g)
+        if fmt:
+            B.apms_warmup_step_g16(self.ctx, self.x, self.m[0], self.v, g, fmt, lr, beta1, beta2, eps, t, stream)
+        else:
+            B.apms_warmup_step(self.ctx, self.x, self.m[0], self.v, g, lr, beta1, beta2, eps, t, stream)
 
     def freeze(self, stream=None):
         B.apms_freeze(self.ctx, self.m, self.werr, self.serr, stream)

@@ -234,3 +234,26 @@ def device_grad_(wl: Workload, step: int, out, seed: int = BASE_SEED):
     for off, size in wl.layernorm_segments():
         out[:, off:off + size].mul_(0.1)
     return out
+
+
+# ----------------------------------------------------------------------------
+# 16-bit gradient inputs: the same draws, rounded to binary16 / bfloat16 (round to nearest even).
+# Returned as raw uint16 bit patterns so that both sides widen them by their own means.
+# ----------------------------------------------------------------------------
+
+def host_grad_g16(wl: Workload, step: int, fmt: str, seed: int = BASE_SEED) -> np.ndarray:
+    """Per-worker gradients [n][d_pad] of one step as 'f16' or 'bf16' bit patterns (uint16)."""
+    g = host_grad(wl, step, seed)
+    if fmt == "f16":
+        return g.astype(np.float16).view(np.uint16)
+    if fmt == "bf16":
+        import torch
+        return torch.from_numpy(g).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    raise ValueError(fmt)
+
+
+def g16_bits_to_tensor(bits: np.ndarray, fmt: str, device="cuda"):
+    """uint16 bit patterns -> torch tensor of dtype float16 / bfloat16 on `device` (same bits)."""
+    import torch
+    t = torch.from_numpy(bits.view(np.int16)).to(device)
+    return t.view(torch.float16 if fmt == "f16" else torch.bfloat16)

@@ -39,7 +39,7 @@ def status_of(fn, *args, **kw):
 def test_library_exports_every_declared_symbol():
     header = open(os.path.join(ROOT, "include", "apms.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(apms_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(apms_[a-z0-9_]+)\s*\(", header))
     assert declared == set(B.EXPORTS)
     lib = ctypes.CDLL(B.library_path())
     for name in declared:
@@ -131,6 +131,23 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 200 * 1024) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 4096) == B.APMS_OK
     assert B.apms_get_plan(ctx)["occupancy_pad"][B.APMS_KERNEL_APPLY] == 4096
+
+
+def test_sixteen_bit_gradient_entry_points(ctx):
+    good = [fake(i) for i in range(5)]
+    m, g, e, p, sc = good
+    for fmt in (B.APMS_GRAD_F16, B.APMS_GRAD_BF16):
+        assert status_of(B.apms_compress_g16, ctx, m, g, fmt, e, p, sc, 0.9) == B.APMS_ENODEV
+        assert status_of(B.apms_warmup_step_g16, ctx, m, g, e, p, fmt, 1e-3, 0.9, 0.999, 1e-8, 1) == B.APMS_ENODEV
+    for fmt in (0, 3, -1):
+        assert status_of(B.apms_compress_g16, ctx, m, g, fmt, e, p, sc, 0.9) == B.APMS_EINVAL
+        assert status_of(B.apms_warmup_step_g16, ctx, m, g, e, p, fmt, 1e-3, 0.9, 0.999, 1e-8, 1) == B.APMS_EINVAL
+    assert status_of(B.apms_compress_g16, ctx, m, None, B.APMS_GRAD_F16, e, p, sc, 0.9) == B.APMS_EINVAL
+    assert status_of(B.apms_compress_g16, ctx, m, g + 2, B.APMS_GRAD_F16, e, p, sc, 0.9) == B.APMS_EALIGN
+    # g is [n][d] 16-bit values = 32768 bytes here: a buffer right behind it does not overlap, one inside does
+    assert status_of(B.apms_compress_g16, ctx, m, g, B.APMS_GRAD_BF16, g + 32768, p, sc, 0.9) == B.APMS_ENODEV
+    assert status_of(B.apms_compress_g16, ctx, m, g, B.APMS_GRAD_BF16, g + 32768 - 16, p, sc, 0.9) == B.APMS_EALIAS
+    assert status_of(B.apms_compress, ctx, m, g, g + 32768, p, sc, 0.9) == B.APMS_EALIAS      # fp32 g is twice as long
 
 
 def test_empty_problem_is_ok_without_a_device():

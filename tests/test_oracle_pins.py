@@ -457,3 +457,30 @@ def test_empty_input():
                          np.zeros(0, np.uint32), np.zeros(0, F))
     oracle.apply(0, 1, 32, np.zeros(0, np.uint32), np.zeros(0, F), np.zeros(0, F), np.zeros(0, F), e.copy(),
                  1e-4, 1e-8)
+
+
+# ------------------------------------------------- 16-bit gradient inputs ---
+
+def test_widen_f16_all_patterns_against_numpy():
+    """Every one of the 65536 binary16 patterns widens to the value numpy's float16 gives it."""
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen_g16(bits, oracle.GRAD_F16)
+    want = bits.view(np.float16).astype(np.float32)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))     # incl. the sign of zero
+    assert got[0x0001] == 2.0 ** -24 and got[0x3C00] == 1.0 and got[0xC000] == -2.0 and got[0x7BFF] == 65504.0
+
+
+def test_widen_bf16_all_patterns_against_torch():
+    """Every bfloat16 pattern widens to the value torch's bfloat16 gives it (= the pattern shifted left by 16)."""
+    import torch
+    bits = np.arange(65536, dtype=np.uint16)
+    got = oracle.widen_g16(bits, oracle.GRAD_BF16)
+    want = torch.from_numpy(bits.view(np.int16)).view(torch.bfloat16).to(torch.float32).numpy()
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), want[~nan].view(np.uint32))
+    assert np.array_equal(got[~nan].view(np.uint32), (bits.astype(np.uint32) << 16)[~nan])
+    with pytest.raises(ValueError):
+        oracle.widen_g16(bits, 7)

@@ -375,3 +375,43 @@ def test_hip_graph_replay_matches_eager():
         assert torch.equal(getattr(graphed, name), getattr(eager, name)), name
     for r in runs:
         r.close()
+
+
+@pytest.mark.parametrize("fmt", ["f16", "bf16"])
+def test_sixteen_bit_gradients(fmt):
+    """16-bit gradient inputs (binary16 / bfloat16, widened exactly): 3 Adam warm-up steps, freeze, 5
+    compressed steps in the fully deferred mode, ragged chunks; subnormal, zero and extreme 16-bit values
+    planted in the first step."""
+    ofmt = {"f16": oracle.GRAD_F16, "bf16": oracle.GRAD_BF16}[fmt]
+    wl = W.Workload("g16", 0, d=3 * (4096 * 3 + 96), n=3, chunk=4096 * 3 + 96, steps=5, warmup_steps=3)
+    d, n, L = wl.d_pad, wl.n, wl.L
+    st = W.host_state(wl, warm_start=True)
+    run = DeviceRun(d, n, L, DEV, deferred=True)
+    run.x.copy_(torch.from_numpy(st["x"]))
+    run.v.zero_()
+    ox, om, ov = st["x"].copy(), st["m"].copy(), st["v"].copy()
+    special = np.array([0x0000, 0x8000, 0x0001, 0x8001, 0x03FF, 0x0400, 0x7BFF, 0xFBFF] if fmt == "f16" else
+                       [0x0000, 0x8000, 0x0001, 0x8001, 0x007F, 0x0080, 0x4F00, 0xCF00], np.uint16)
+    for t in range(1, wl.warmup_steps + 1):
+        say("g16 %s warm-up step %d" % (fmt, t))
+        bits = W.host_grad_g16(wl, t - 1, fmt)
+        if t == 1:
+            bits[1, 5:5 + special.size] = special
+        run.warmup_step(W.g16_bits_to_tensor(bits, fmt, DEV), 1e-3, wl.beta, wl.beta2, wl.eps, t)
+        oracle.warmup_step(d, n, ox, om, ov, oracle.widen_g16(bits, ofmt), 1e-3, wl.beta, wl.beta2, wl.eps, t)
+        close(host(run.x), ox, "warm-up x")
+        close(host(run.m[0]), om, "warm-up m")
+        np.testing.assert_allclose(host(run.v), ov, rtol=RTOL, atol=1e-12, err_msg="warm-up v")
+    run.freeze()
+    ost = oracle.State(d, n, L, host(run.x), host(run.m), host(run.v))
+    for step in range(wl.steps):
+        say("g16 %s compressed step %d" % (fmt, step))
+        bits = W.host_grad_g16(wl, wl.warmup_steps + step, fmt)
+        if step == 0:
+            bits[2, L + 7:L + 7 + special.size] = special
+        run.step(W.g16_bits_to_tensor(bits, fmt, DEV), wl.beta, wl.lr, wl.eps)
+        ost.step(oracle.widen_g16(bits, ofmt), wl.beta, wl.lr, wl.eps)
+        compare_all(run, ost, "g16 %s step %d" % (fmt, step), errors=False, momentum=False)
+    run.finalize()
+    compare_all(run, ost, "g16 %s end" % fmt)
+    run.close()
