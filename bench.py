@@ -89,6 +89,8 @@ def main():
                          "(apms_set_deferral); eager: every buffer is final when its call's work ends")
     ap.add_argument("--compress-tiles", type=int, default=0)
     ap.add_argument("--server-tiles", type=int, default=0)
+    ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
+                    help="element type of the gradient input (f32 is the benchmark's configuration)")
     ap.add_argument("--occupancy-pad", default="", help="e.g. compress=65536,apply=0 (apms_set_occupancy_pad)")
     ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -134,12 +136,20 @@ def main():
         name, val = item.split("=")
         B.apms_set_occupancy_pad(run.ctx, kernel_ids[name], int(val))
     plan = B.apms_get_plan(run.ctx)
-    g = torch.empty(n, d, dtype=torch.float32, device=dev)
+    g32 = torch.empty(n, d, dtype=torch.float32, device=dev)
+    gdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.grad_dtype]
+    g = g32 if gdt == torch.float32 else torch.empty(n, d, dtype=gdt, device=dev)
+    gbytes = g.element_size()
     stream = torch.cuda.current_stream()
+
+    def draw(step):
+        W.device_grad_(wl, step, g32)
+        if g is not g32:
+            g.copy_(g32)                    # round to nearest even, untimed (input generation)
 
     def one_step(step, events=None):
         if step == 0 or not args.reuse_grad:
-            W.device_grad_(wl, wl.warmup_steps + step, g)
+            draw(wl.warmup_steps + step)
         if events is not None:
             events[0].record(stream)
         run.compress(g, wl.beta)
@@ -155,7 +165,7 @@ def main():
     if wl.warmup_steps:
         wev = [torch.cuda.Event(enable_timing=True) for _ in range(2 * wl.warmup_steps)]
         for t in range(1, wl.warmup_steps + 1):
-            W.device_grad_(wl, t - 1, g)
+            draw(t - 1)
             wev[2 * t - 2].record(stream)
             run.warmup_step(g, 1e-3, wl.beta, wl.beta2, wl.eps, t)
             wev[2 * t - 1].record(stream)
@@ -163,11 +173,11 @@ def main():
         torch.cuda.synchronize()
         wms = sorted(wev[2 * i].elapsed_time(wev[2 * i + 1]) for i in range(wl.warmup_steps))
         warm = {"steps": wl.warmup_steps, "ms_per_step_median": wms[len(wms) // 2],
-                "GBps": d * (4.0 * n + 24.0) / (wms[len(wms) // 2] * 1e-3) / 1e9}
+                "GBps": d * (gbytes * n + 24.0) / (wms[len(wms) // 2] * 1e-3) / 1e9}
         log("Adam warm-up: %d steps, median %.3f ms (%.0f GB/s), then freeze" % (warm["steps"], warm["ms_per_step_median"], warm["GBps"]))
     if args.calibration_copy:
-        W.device_grad_(wl, 0, g)
-        run.werr.copy_(g)
+        W.device_grad_(wl, 0, g32)
+        run.werr.copy_(g32)
         run.werr.zero_()
         torch.cuda.synchronize()
         log("calibration copy done: %d bytes read, %d bytes written" % (4 * n * d, 4 * n * d))
@@ -197,6 +207,7 @@ def main():
     ms_per_step = total_ms / args.steps
     value = d * args.steps / (total_ms * 1e-3)
     ab = call_bytes(n, gather_deferred=bool(deferral & B.APMS_DEFER_GATHER))
+    ab["compress"] -= (4 - gbytes) * n             # 16-bit gradients: 2n fewer bytes read
     spec_bytes = sum(call_bytes(n).values())       # the workload's own accounting (eager gather)
     mean = lambda xs: sum(xs) / len(xs)
     step_bytes = d * sum(ab.values())
@@ -211,7 +222,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": "%s: d_pad=%d n=%d chunk=%d" % (wl.name, d, n, L),
-            "mode": args.mode, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
+            "mode": args.mode, "grad_dtype": args.grad_dtype, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
             "worker_params_per_s": value * n,
             "bytes_per_param_step": sum(ab.values()),
             "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -233,7 +244,7 @@ def main():
             "kernel": "compress_kernel<%s> (apms_compress)" % ("true" if deferral & B.APMS_DEFER_GATHER else "false"),
             "bound": "hbm", "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)),
+            "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)) if args.grad_dtype == "f32" else None,
             "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/bench_bert-large-flat_hbm_traffic.txt",
             "bytes_per_launch": d * ab["compress"],
             "avg_launch_ms": compress_ms,
@@ -241,7 +252,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline(wl, run, g, min(args.cpu_sample, L), args.cpu_steps)
+        out["cpu_baseline"] = cpu_baseline(wl, run, g32, min(args.cpu_sample, L), args.cpu_steps)
     run.close()
     print(json.dumps(out), flush=True)
 
