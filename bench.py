@@ -84,9 +84,10 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert-large-flat")
-    ap.add_argument("--mode", choices=["deferred", "deferred-errors", "eager"], default="deferred",
+    ap.add_argument("--mode", choices=["deferred", "deferred-errors", "eager", "implicit"], default="deferred",
                     help="deferred: error buffers and the momentum gather are written one call later "
-                         "(apms_set_deferral); eager: every buffer is final when its call's work ends")
+                         "(apms_set_deferral); eager: every buffer is final when its call's work ends; implicit: as "
+                         "deferred, but m[n][d] is never written (departs from the benchmark's state model)")
     ap.add_argument("--compress-tiles", type=int, default=0)
     ap.add_argument("--server-tiles", type=int, default=0)
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
@@ -117,7 +118,8 @@ def main():
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))
     deferral = {"deferred": B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, "deferred-errors": B.APMS_DEFER_ERRORS,
-                "eager": 0}[args.mode]
+                "eager": 0,
+                "implicit": B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM}[args.mode]
     warm = None
     if wl.warmup_steps:
         # full pipeline: Adam warm-up on the averaged gradients (Algorithm 1 line 2), then freeze v
@@ -208,6 +210,8 @@ def main():
     value = d * args.steps / (total_ms * 1e-3)
     ab = call_bytes(n, gather_deferred=bool(deferral & B.APMS_DEFER_GATHER))
     ab["compress"] -= (4 - gbytes) * n             # 16-bit gradients: 2n fewer bytes read
+    if deferral & B.APMS_IMPLICIT_MOMENTUM:
+        ab["compress"] -= 4.0 * n                  # m is not written
     spec_bytes = sum(call_bytes(n).values())       # the workload's own accounting (eager gather)
     mean = lambda xs: sum(xs) / len(xs)
     step_bytes = d * sum(ab.values())

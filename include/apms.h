@@ -70,6 +70,7 @@ typedef enum apms_status {
 /* Deferral flags for apms_set_deferral (0 = everything eager, the default). */
 #define APMS_DEFER_ERRORS 1 /* error buffers hold the compensated vector u; delta = u - C[u] is formed on next read */
 #define APMS_DEFER_GATHER 2 /* apms_apply leaves m untouched; the next apms_compress writes the gathered momentum */
+#define APMS_IMPLICIT_MOMENTUM 4 /* with APMS_DEFER_GATHER: that apms_compress does not write m either */
 
 /* Launch geometry of a context (read-only report; see apms_get_plan). */
 typedef struct apms_plan {
@@ -152,6 +153,12 @@ int apms_set_occupancy_pad(apms_ctx *ctx, int kernel, int32_t lds_bytes);
  * decoded values in place of reading m: the momentum state is still materialised in m[n][d] every step,
  * it is just not read back.  Until then `spacked` must stay untouched (apms_server_reduce with that
  * address is refused).
+ *
+ * APMS_IMPLICIT_MOMENTUM (only together with APMS_DEFER_GATHER; EINVAL otherwise).  The momentum is
+ * kept ONLY as the server's sign words and scales: the apms_compress that consumes a pending gather
+ * decodes them and writes nothing to m, so m[n][d] is never touched by a step (4n fewer bytes written
+ * per parameter).  This departs from the state model "per-worker fp32 momentum resident in memory":
+ * m is defined only if apms_finalize(m) is called between apms_apply and the next apms_compress.
  *
  * While a buffer is pending its contents are not final: call apms_finalize before reading it
  * (checkpoint, test) or before handing a different buffer to the same context; a call that would lose

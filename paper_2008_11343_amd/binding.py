@@ -22,6 +22,7 @@ APMS_GRAD_F16 = 1
 APMS_GRAD_BF16 = 2
 APMS_DEFER_ERRORS = 1
 APMS_DEFER_GATHER = 2
+APMS_IMPLICIT_MOMENTUM = 4
 APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE = 0, 1, 2, 3
 
 EXPORTS = (

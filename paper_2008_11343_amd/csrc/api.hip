@@ -259,7 +259,8 @@ int apms_set_occupancy_pad(apms_ctx* c, int kernel, int32_t lds_bytes) {
 }
 
 int apms_set_deferral(apms_ctx* c, int flags) {
-    if (!c || (flags & ~(APMS_DEFER_ERRORS | APMS_DEFER_GATHER)) != 0) return APMS_EINVAL;
+    if (!c || (flags & ~(APMS_DEFER_ERRORS | APMS_DEFER_GATHER | APMS_IMPLICIT_MOMENTUM)) != 0) return APMS_EINVAL;
+    if ((flags & APMS_IMPLICIT_MOMENTUM) && !(flags & APMS_DEFER_GATHER)) return APMS_EINVAL;
     c->deferral = flags;
     return APMS_OK;
 }
@@ -351,12 +352,15 @@ int compress_impl(apms_ctx* c, float* m, const void* g, int grad_format, float* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const apms::Geometry geo = geometry(c);
     const float* prev = c->pending_werr ? c->w_pending : nullptr;
-    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m, g, grad_format,
+    // implicit momentum: the pending gather is consumed without materialising m
+    float* m_arg = (gather && (c->deferral & APMS_IMPLICIT_MOMENTUM)) ? nullptr : m;
+    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m_arg, g, grad_format,
                                          worker_err, packed, c->w_partials, prev,
                                          gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
                                          beta, 1.0f - beta, c->lds_pad[APMS_KERNEL_COMPRESS], s);
     if (e != hipSuccess) return hip_fail(c, e);
-    // from here on m holds the gathered momentum, the error buffer holds u and the context its scales
+    // from here on m holds the gathered momentum (unless implicit), the error buffer holds u and the
+    // context its scales
     c->pending_m = nullptr;
     c->pending_spacked = nullptr;
     c->pending_werr = worker_err;

@@ -50,7 +50,7 @@ inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L 
 // tiles_per_block consecutive tiles of kCompressTile elements.  prev_scales (nullable, [n*C]) marks werr
 // as holding last step's u (deferred form).  gather_words ([d/32]) + gather_scales ([C]), both nullable
 // together, mark a deferred gather: the kernel then decodes the momentum from them, writes it to all of
-// m and does not read m.  g holds grad_format elements (kGradF32 / kGradF16 / kGradBF16).
+// m (m may be null then: nothing is written) and does not read m.  g holds grad_format elements (kGradF32 / kGradF16 / kGradBF16).
 hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
                            const void* g, int grad_format, float* werr, uint32_t* packed, double* partials,
                            const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,

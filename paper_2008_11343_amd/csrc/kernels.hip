@@ -50,8 +50,8 @@ __device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
 }
 
 // kGather: a deferred gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum of
-// every worker is the decoded server message (gather_words, gather_scale); write it to m and use it
-// directly instead of reading m back.
+// every worker is the decoded server message (gather_words, gather_scale); write it to m (unless m is
+// null: implicit-momentum mode) and use it directly instead of reading m back.
 template <bool kFull, bool kGather, int G>
 __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void* __restrict__ g,
                                               float* __restrict__ e, uint32_t* __restrict__ packed,
@@ -87,7 +87,7 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void*
                 const uint32_t gn = gw[r] >> shift;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) vm[r][c] = signed_scale((gn >> c) & 1u, gather_scale);
-                store_stream(m + chunk_base + off0 + 32 * r, vm[r]);
+                if (m) store_stream(m + chunk_base + off0 + 32 * r, vm[r]);
             }
             const f32x4 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
             store_stream(e + chunk_base + off0 + 32 * r, u);

@@ -124,7 +124,9 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_warmup_step, ctx, *w, 1e-3, 0.9, -0.5, 1e-8, 1) == B.APMS_EINVAL
     assert status_of(B.apms_warmup_step, ctx, *w, float("nan"), 0.9, 0.999, 1e-8, 1) == B.APMS_EINVAL
     assert status_of(B.apms_apply, ctx, *good, float("nan"), 1e-8) == B.APMS_EINVAL
-    assert status_of(B.apms_set_deferral, ctx, 4) == B.APMS_EINVAL
+    assert status_of(B.apms_set_deferral, ctx, 8) == B.APMS_EINVAL
+    assert status_of(B.apms_set_deferral, ctx, B.APMS_IMPLICIT_MOMENTUM) == B.APMS_EINVAL      # needs DEFER_GATHER
+    assert status_of(B.apms_set_deferral, ctx, B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM) == B.APMS_OK
     assert status_of(B.apms_set_deferral, ctx, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER) == B.APMS_OK
     assert status_of(B.apms_set_tiles_per_block, ctx, -1, 0) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, 4, 0) == B.APMS_EINVAL

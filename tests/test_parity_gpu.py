@@ -415,3 +415,32 @@ def test_sixteen_bit_gradients(fmt):
     run.finalize()
     compare_all(run, ost, "g16 %s end" % fmt)
     run.close()
+
+
+def test_implicit_momentum_mode():
+    """APMS_IMPLICIT_MOMENTUM: the momentum lives only in the server's sign words and scales; steps never
+    touch m[n][d], yet every output matches the oracle, and apms_finalize right after apms_apply still
+    materialises the gathered momentum on demand."""
+    wl = W.scaled(W.TINY, 4 * (4096 * 5 + 160), chunk=4096 * 5 + 160)
+    st = W.host_state(wl)
+    ost = oracle_state(wl.d_pad, wl.n, wl.L, st)
+    flags = B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM
+    run = from_host_state(wl, st, DEV, deferred=flags)
+    m_before = run.m.clone()
+    for step in range(6):
+        say("implicit momentum step %d" % step)
+        g = W.host_grad(wl, step)
+        run.step(torch.from_numpy(g).to(DEV), wl.beta, wl.lr, wl.eps)
+        ost.step(g, wl.beta, wl.lr, wl.eps)
+        compare_all(run, ost, "implicit step %d" % step, errors=False, momentum=False)
+        if step < 3:
+            assert torch.equal(run.m, m_before), "a step wrote m in implicit mode"
+        elif step == 3:
+            B.apms_finalize(run.ctx, None, None, run.m)        # on demand, between apply and the next compress
+            compare_momentum(run, ost.m, np.array_equal(host(run.sscales), ost.sscales), "implicit, materialised")
+            m_before = run.m.clone()
+        else:
+            assert torch.equal(run.m, m_before)
+    run.finalize()
+    compare_all(run, ost, "implicit end")
+    run.close()
