@@ -190,6 +190,22 @@ def test_launch_plan_of_every_config(wl):
         B.apms_destroy(c)
 
 
+def test_maximum_sizes():
+    """Sizes whose launch grids would not fit a 1-D launch are refused at creation; the largest that fit
+    are planned without 32-bit overflow."""
+    assert status_of(B.apms_create, 1 << 40, 64, 1 << 34, B.APMS_DEVICE_NONE) == B.APMS_ESHAPE
+    assert status_of(B.apms_create, 1 << 42, 1, 1 << 42, B.APMS_DEVICE_NONE) == B.APMS_ESHAPE
+    c = B.apms_create(1 << 36, 8, 1 << 33, B.APMS_DEVICE_NONE)       # 64 G elements, 8 workers, 8 chunks
+    try:
+        p = B.apms_get_plan(c)
+        assert p["chunks"] == 8
+        assert p["compress_grid"] == 8 * 8 * ((1 << 33) // p["compress_tile_elems"]) < 2 ** 31
+        assert p["apply_grid"] == 8 * 8 * ((1 << 33) // p["apply_tile_elems"]) < 2 ** 31
+        assert p["scratch_bytes"] > 0
+    finally:
+        B.apms_destroy(c)
+
+
 def test_ragged_chunk_plan():
     c = B.apms_create(3 * (4096 * 2 + 160), 2, 4096 * 2 + 160, B.APMS_DEVICE_NONE)
     try:

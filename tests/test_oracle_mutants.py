@@ -45,6 +45,9 @@ MUTANTS = [
     ("adam_t_off_by_one", "pow((double)beta2, (double)t)", "pow((double)beta2, (double)(t - 1) + 1e-9)"),
     ("adam_eps_inside_sqrt", "float root = sqrtf(vhat);", "float root = sqrtf(vhat + 1e-6f);"),
     ("adam_sum_not_mean", "float gbar = acc * inv_n;", "float gbar = acc;"),
+    ("f16_bias_off_by_one", "const int bias = (1 << (exp_bits - 1)) - 1;", "const int bias = (1 << (exp_bits - 1));"),
+    ("g16_subnormal_as_normal", "value = ldexp((double)f, 1 - bias - frac_bits);", "value = ldexp((double)((1 << frac_bits) + f), e - bias - frac_bits);"),
+    ("g16_sign_dropped", "out[j] = (float)(negative ? -value : value);", "out[j] = (float)value;"),
     ("freeze_keeps_errors", "memset(serr, 0, (size_t)d * sizeof(float));", ""),
 ]
 
@@ -92,7 +95,7 @@ def test_pins_catch_planted_mistake(mutant, tmp_path, monkeypatch):
     good = oracle._load()
     bad = ctypes.CDLL(str(so_path))
     for fname in ("apms_oracle_compress", "apms_oracle_server_reduce", "apms_oracle_apply",
-                  "apms_oracle_warmup_step", "apms_oracle_freeze"):
+                  "apms_oracle_warmup_step", "apms_oracle_freeze", "apms_oracle_widen_g16"):
         getattr(bad, fname).argtypes = getattr(good, fname).argtypes
         getattr(bad, fname).restype = getattr(good, fname).restype
     monkeypatch.setattr(oracle, "_lib", bad)

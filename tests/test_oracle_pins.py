@@ -484,3 +484,4 @@ def test_widen_bf16_all_patterns_against_torch():
     assert np.array_equal(got[~nan].view(np.uint32), (bits.astype(np.uint32) << 16)[~nan])
     with pytest.raises(ValueError):
         oracle.widen_g16(bits, 7)
+
