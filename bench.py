@@ -90,6 +90,8 @@ def main():
                          "deferred, but m[n][d] is never written (departs from the benchmark's state model)")
     ap.add_argument("--compress-tiles", type=int, default=0)
     ap.add_argument("--server-tiles", type=int, default=0)
+    ap.add_argument("--algo", choices=["momentum", "gradient"], default="momentum",
+                    help="momentum: APMSqueeze (the benchmark); gradient: the APGSqueeze variant of Section 5.3")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient input (f32 is the benchmark's configuration)")
     ap.add_argument("--occupancy-pad", default="", help="e.g. compress=65536,apply=0 (apms_set_occupancy_pad)")
@@ -154,13 +156,19 @@ def main():
             draw(wl.warmup_steps + step)
         if events is not None:
             events[0].record(stream)
-        run.compress(g, wl.beta)
+        if args.algo == "gradient":
+            B.apms_compress_gradient(run.ctx, g, run._grad_format(g), run.werr, run.packed, run.scales)
+        else:
+            run.compress(g, wl.beta)
         if events is not None:
             events[1].record(stream)
         run.server_reduce()
         if events is not None:
             events[2].record(stream)
-        run.apply(wl.lr, wl.eps)
+        if args.algo == "gradient":
+            B.apms_apply_gradient(run.ctx, run.spacked, run.sscales, run.v, run.x, run.m, wl.lr, wl.beta, wl.eps)
+        else:
+            run.apply(wl.lr, wl.eps)
         if events is not None:
             events[3].record(stream)
 
@@ -212,6 +220,10 @@ def main():
     ab["compress"] -= (4 - gbytes) * n             # 16-bit gradients: 2n fewer bytes read
     if deferral & B.APMS_IMPLICIT_MOMENTUM:
         ab["compress"] -= 4.0 * n                  # m is not written
+    if args.algo == "gradient":
+        # worker: read g, delta; write delta, n/8 signs.  apply: read + write m per worker, n/8 signs, v, x, x
+        ab["compress"] = (8.0 + gbytes) * n + n / 8.0
+        ab["apply"] = 8.125 * n + 12.0
     spec_bytes = sum(call_bytes(n).values())       # the workload's own accounting (eager gather)
     mean = lambda xs: sum(xs) / len(xs)
     step_bytes = d * sum(ab.values())
@@ -226,7 +238,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": "%s: d_pad=%d n=%d chunk=%d" % (wl.name, d, n, L),
-            "mode": args.mode, "grad_dtype": args.grad_dtype, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
+            "algo": args.algo, "mode": args.mode, "grad_dtype": args.grad_dtype, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
             "worker_params_per_s": value * n,
             "bytes_per_param_step": sum(ab.values()),
             "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,
@@ -248,7 +260,7 @@ def main():
             "kernel": "compress_kernel<%s> (apms_compress)" % ("true" if deferral & B.APMS_DEFER_GATHER else "false"),
             "bound": "hbm", "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)) if args.grad_dtype == "f32" else None,
+            "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)) if (args.grad_dtype == "f32" and args.algo == "momentum") else None,
             "traffic_source": "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, profiles/bench_bert-large-flat_hbm_traffic.txt",
             "bytes_per_launch": d * ab["compress"],
             "avg_launch_ms": compress_ms,

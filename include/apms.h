@@ -253,6 +253,30 @@ int apms_server_reduce(apms_ctx *ctx, const uint32_t *packed, const float *scale
 int apms_apply(apms_ctx *ctx, const uint32_t *spacked, const float *sscales, const float *v,
                float *x, float *m, float lr, float eps, void *stream);
 
+/*
+ * APGSqueeze variant (Section 5.3, item 4: "instead of communicating the momentum, use the
+ * error-compensated compression strategy for communicating the gradient").  The paper gives it one
+ * sentence; this reading keeps everything else of the compression stage: the worker compensates and
+ * compresses its gradient, the server step is apms_server_reduce unchanged, and every worker forms the
+ * momentum from the decoded averaged gradient before the frozen-variance model step.
+ *
+ * apms_compress_gradient, for all n workers and C chunks:
+ *   u = g_i + delta_i;  scale, bit as in apms_compress;  delta_i <- u - (bit ? +scale : -scale)
+ *   g [n][d] in, of type grad_format (0 = binary32, APMS_GRAD_F16, APMS_GRAD_BF16);
+ *   worker_err [n][d] in/out;  packed [n][d/32], scales [n][C] out.  APMS_DEFER_ERRORS applies.
+ *
+ * apms_apply_gradient:
+ *   ghat = (sbit ? +sscale : -sscale)
+ *   m_i <- fl(beta*m_i) + fl(fl(1-beta)*ghat)      for every worker i
+ *   x   <- x - lr * ( m_0 / (sqrt(v) + eps) )
+ *   spacked [d/32], sscales [C], v [d] in;  x [d], m [n][d] in/out.  ESTATE if a deferred gather is
+ *   pending on m.
+ */
+int apms_compress_gradient(apms_ctx *ctx, const void *g, int grad_format, float *worker_err, uint32_t *packed,
+                           float *scales, void *stream);
+int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *sscales, const float *v, float *x,
+                        float *m, float lr, float beta, float eps, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

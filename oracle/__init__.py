@@ -49,6 +49,8 @@ def _load():
         lib.apms_oracle_compress.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32]
         lib.apms_oracle_server_reduce.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, ptr]
         lib.apms_oracle_apply.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32, f32]
+        lib.apms_oracle_apply_gradient.argtypes = [ctypes.c_int, i64, i32, i64, ptr, ptr, ptr, ptr, ptr, ptr, f32, f32, f32]
+        lib.apms_oracle_apply_gradient.restype = ctypes.c_int
         lib.apms_oracle_warmup_step.argtypes = [i64, i32, ptr, ptr, ptr, ptr, f32, f32, f32, f32, i64]
         lib.apms_oracle_freeze.argtypes = [i64, i32, ptr, ptr, ptr, ptr]
         lib.apms_oracle_widen_g16.argtypes = [ctypes.c_int, i64, ptr, ptr]
@@ -77,7 +79,8 @@ def _check_shape(d, n, L):
 
 
 def compress(d, n, L, m, g, werr, packed, scales, beta, compressor=ONEBIT, dense=None):
-    """Worker step for all n workers and all chunks; werr, packed, scales (, dense) written in place."""
+    """Worker step for all n workers and all chunks; werr, packed, scales (, dense) written in place.
+    m=None selects the APGSqueeze variant (the gradient itself is compensated and compressed)."""
     _check_shape(d, n, L)
     C = d // L
     f, u = np.float32, np.uint32
@@ -109,6 +112,16 @@ def apply(d, n, L, spacked, sscales, v, x, m, lr, eps, compressor=ONEBIT, sdense
     _load().apms_oracle_apply(
         compressor, d, n, L, _p(spacked, u, d // 32), _p(sscales, f, C), _p(sdense, f, d),
         _p(v, f, d), _p(x, f, d), _p(m, f, n * d), np.float32(lr), np.float32(eps))
+
+
+def apply_gradient(d, n, L, spacked, sscales, v, x, m, lr, beta, eps, compressor=ONEBIT, sdense=None):
+    """APGSqueeze: momentum step on the decoded averaged gradient + frozen-variance model update; x, m in place."""
+    _check_shape(d, n, L)
+    C = d // L
+    f, u = np.float32, np.uint32
+    _load().apms_oracle_apply_gradient(
+        compressor, d, n, L, _p(spacked, u, d // 32), _p(sscales, f, C), _p(sdense, f, d),
+        _p(v, f, d), _p(x, f, d), _p(m, f, n * d), np.float32(lr), np.float32(beta), np.float32(eps))
 
 
 def warmup_step(d, n, x, m, v, g, lr, beta1, beta2, eps, t):
@@ -169,3 +182,16 @@ class State:
         server_reduce(d, n, L, self.packed, self.scales, self.serr, self.spacked, self.sscales,
                       compressor, self.dense, self.sdense)
         apply(d, n, L, self.spacked, self.sscales, self.v, self.x, self.m, lr, eps, compressor, self.sdense)
+
+    def step_gradient(self, g, beta, lr, eps, compressor=ONEBIT):
+        """One APGSqueeze step: compress g + delta, server reduce, momentum + model update."""
+        d, n, L = self.d, self.n, self.L
+        g = np.ascontiguousarray(g, dtype=np.float32).reshape(n, d)
+        if compressor == IDENTITY and self.dense is None:
+            self.dense = np.zeros((n, d), np.float32)
+            self.sdense = np.zeros(d, np.float32)
+        compress(d, n, L, None, g, self.werr, self.packed, self.scales, 0.0, compressor, self.dense)
+        server_reduce(d, n, L, self.packed, self.scales, self.serr, self.spacked, self.sscales,
+                      compressor, self.dense, self.sdense)
+        apply_gradient(d, n, L, self.spacked, self.sscales, self.v, self.x, self.m, lr, beta, eps, compressor,
+                       self.sdense)

@@ -104,7 +104,9 @@ static float decode_elem(int compressor, const uint32_t *words, float scale,
  *
  * d       vector length, a multiple of L;  L a multiple of 32
  * m       [n][d] momentum slices (read only: the local m_i is never stored,
- *         the gather of step 3 overwrites it)
+ *         the gather of step 3 overwrites it).  NULL selects the APGSqueeze
+ *         variant of Section 5.3 (item 4), which error-compensates and
+ *         compresses the GRADIENT instead of the momentum: u = g_i + delta_i.
  * g       [n][d] local stochastic gradients
  * werr    [n][d] worker errors delta_i, updated in place
  * packed  [n][d/32] sign words out            (ONEBIT)
@@ -133,6 +135,10 @@ int apms_oracle_compress(int compressor, int64_t d, int32_t n, int64_t L,
         for (int64_t k = 0; k < C; ++k) {
             const int64_t base = (int64_t)i * d + k * L;
             for (int64_t j = 0; j < L; ++j) {
+                if (!m) {
+                    u[j] = g[base + j] + werr[base + j];
+                    continue;
+                }
                 float bm = beta * m[base + j];
                 float bg = one_minus_beta * g[base + j];
                 float mi = bm + bg;
@@ -247,6 +253,40 @@ int apms_oracle_apply(int compressor, int64_t d, int32_t n, int64_t L,
         float ratio = mj / denom;
         float step = lr * ratio;
         x[j] = x[j] - step;
+    }
+    return 0;
+}
+
+/*
+ * APGSqueeze (Section 5.3, item 4) after the gather: the decoded server message is the averaged,
+ * doubly compressed GRADIENT ghat; every worker then takes the momentum step itself,
+ *     m_i <- beta * m_i + (1 - beta) * ghat      for all i
+ *     x   <- x - lr * m / (sqrt(v) + eps)         (worker 0's m; all slices agree if they started equal)
+ * The paper gives the variant one sentence; that the momentum is formed from the decoded gradient and
+ * the variance stays frozen is this build's reading.
+ */
+int apms_oracle_apply_gradient(int compressor, int64_t d, int32_t n, int64_t L,
+                               const uint32_t *spacked, const float *sscales,
+                               const float *sdense, const float *v, float *x, float *m,
+                               float lr, float beta, float eps)
+{
+    const float one_minus_beta = 1.0f - beta;
+    for (int64_t j = 0; j < d; ++j) {
+        const int64_t k = j / L;
+        const int64_t base = k * L;
+        const uint32_t *chunk_words = spacked ? spacked + base / 32 : NULL;
+        const float *chunk_dense = sdense ? sdense + base : NULL;
+        float ghat = decode_elem(compressor, chunk_words, sscales[k], chunk_dense, j - base);
+        for (int32_t i = 0; i < n; ++i) {
+            float keep = beta * m[(int64_t)i * d + j];
+            float inc = one_minus_beta * ghat;
+            m[(int64_t)i * d + j] = keep + inc;
+        }
+        float root_v = sqrtf(v[j]);
+        float precond = root_v + eps;
+        float direction = m[j] / precond;
+        float delta_x = lr * direction;
+        x[j] = x[j] - delta_x;
     }
     return 0;
 }

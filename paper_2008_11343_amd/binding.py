@@ -29,6 +29,7 @@ EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
     "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
     "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
+    "apms_compress_gradient", "apms_apply_gradient",
 )
 
 
@@ -89,6 +90,8 @@ def load():
         "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "apms_warmup_step_g16": (ci, [vp, vp, vp, vp, vp, ci, f32, f32, f32, f32, i64, vp]),
         "apms_compress_g16": (ci, [vp, vp, vp, ci, vp, vp, vp, f32, vp]),
+        "apms_compress_gradient": (ci, [vp, vp, ci, vp, vp, vp, vp]),
+        "apms_apply_gradient": (ci, [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp]),
         "apms_freeze": (ci, [vp, vp, vp, vp, vp]),
         "apms_compress": (ci, [vp, vp, vp, vp, vp, vp, f32, vp]),
         "apms_server_reduce": (ci, [vp, vp, vp, vp, vp, vp, vp]),
@@ -202,3 +205,13 @@ def apms_server_reduce(ctx, packed, scales, server_err, spacked, sscales, stream
 def apms_apply(ctx, spacked, sscales, v, x, m, lr, eps, stream=None):
     _check(ctx, load().apms_apply(ctx, _ptr(spacked), _ptr(sscales), _ptr(v), _ptr(x), _ptr(m), lr, eps,
                                   _stream(stream)), "apms_apply")
+
+
+def apms_compress_gradient(ctx, g, grad_format, worker_err, packed, scales, stream=None):
+    _check(ctx, load().apms_compress_gradient(ctx, _ptr(g), grad_format, _ptr(worker_err), _ptr(packed),
+                                              _ptr(scales), _stream(stream)), "apms_compress_gradient")
+
+
+def apms_apply_gradient(ctx, spacked, sscales, v, x, m, lr, beta, eps, stream=None):
+    _check(ctx, load().apms_apply_gradient(ctx, _ptr(spacked), _ptr(sscales), _ptr(v), _ptr(x), _ptr(m), lr, beta,
+                                           eps, _stream(stream)), "apms_apply_gradient")

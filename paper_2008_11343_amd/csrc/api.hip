@@ -296,6 +296,23 @@ int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, v
     return APMS_OK;
 }
 
+int apms_apply_gradient(apms_ctx* c, const uint32_t* spacked, const float* sscales, const float* v, float* x,
+                        float* m, float lr, float beta, float eps, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{spacked, vec / 32}, {sscales, c->C * 4}, {v, vec}, {x, vec}, {m, vec * c->n}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!(lr == lr) || !(eps == eps) || !unit_interval(beta)) return APMS_EINVAL;
+    if (c->pending_m && c->pending_m == m) return APMS_ESTATE;   // m is read here and is not final yet
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_apply_gradient(geometry(c), spacked, sscales, v, x, m, lr, beta, 1.0f - beta, eps,
+                                               c->lds_pad[APMS_KERNEL_APPLY], static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
 }  // extern "C"
 
 namespace {
@@ -332,15 +349,17 @@ int warmup_impl(apms_ctx* c, float* x, float* m, float* v, const void* g, int gr
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
-int compress_impl(apms_ctx* c, float* m, const void* g, int grad_format, float* worker_err, uint32_t* packed,
-                  float* scales, float beta, void* stream) {
+// with_momentum false: APGSqueeze variant, u = g + delta; m is not an argument and a pending gather is
+// neither used nor disturbed.
+int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int grad_format, float* worker_err,
+                  uint32_t* packed, float* scales, float beta, void* stream) {
     if (!c) return APMS_EINVAL;
     const int gbytes = grad_elem_bytes(grad_format);
     if (!gbytes) return APMS_EINVAL;
     const int64_t all = c->d * 4 * c->n;
-    const bool gather = c->pending_m != nullptr;
-    const Range r[] = {{m, all}, {g, c->d * gbytes * c->n}, {worker_err, all}, {packed, all / 32},
-                       {scales, c->n * c->C * 4}, {c->pending_spacked, gather ? c->d / 8 : 0}};
+    const bool gather = with_momentum && c->pending_m != nullptr;
+    const Range r[] = {{g, c->d * gbytes * c->n}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4},
+                       {m, with_momentum ? all : 0}, {c->pending_spacked, gather ? c->d / 8 : 0}};
     if (int rc = check_arrays(r, 6)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
     if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
@@ -352,17 +371,20 @@ int compress_impl(apms_ctx* c, float* m, const void* g, int grad_format, float* 
     hipStream_t s = static_cast<hipStream_t>(stream);
     const apms::Geometry geo = geometry(c);
     const float* prev = c->pending_werr ? c->w_pending : nullptr;
+    const int momentum = !with_momentum ? apms::kMomNone : gather ? apms::kMomGather : apms::kMomRead;
     // implicit momentum: the pending gather is consumed without materialising m
     float* m_arg = (gather && (c->deferral & APMS_IMPLICIT_MOMENTUM)) ? nullptr : m;
-    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, m_arg, g, grad_format,
-                                         worker_err, packed, c->w_partials, prev,
+    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, momentum, m_arg, g,
+                                         grad_format, worker_err, packed, c->w_partials, prev,
                                          gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
                                          beta, 1.0f - beta, c->lds_pad[APMS_KERNEL_COMPRESS], s);
     if (e != hipSuccess) return hip_fail(c, e);
     // from here on m holds the gathered momentum (unless implicit), the error buffer holds u and the
     // context its scales
-    c->pending_m = nullptr;
-    c->pending_spacked = nullptr;
+    if (gather) {
+        c->pending_m = nullptr;
+        c->pending_spacked = nullptr;
+    }
     c->pending_werr = worker_err;
     e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
                             c->w_pending, s);
@@ -409,13 +431,18 @@ int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, voi
 
 int apms_compress(apms_ctx* c, float* m, const float* g, float* worker_err, uint32_t* packed, float* scales,
                   float beta, void* stream) {
-    return compress_impl(c, m, g, apms::kGradF32, worker_err, packed, scales, beta, stream);
+    return compress_impl(c, true, m, g, apms::kGradF32, worker_err, packed, scales, beta, stream);
 }
 
 int apms_compress_g16(apms_ctx* c, float* m, const uint16_t* g, int grad_format, float* worker_err,
                       uint32_t* packed, float* scales, float beta, void* stream) {
     if (grad_format != APMS_GRAD_F16 && grad_format != APMS_GRAD_BF16) return APMS_EINVAL;
-    return compress_impl(c, m, g, grad_format, worker_err, packed, scales, beta, stream);
+    return compress_impl(c, true, m, g, grad_format, worker_err, packed, scales, beta, stream);
+}
+
+int apms_compress_gradient(apms_ctx* c, const void* g, int grad_format, float* worker_err, uint32_t* packed,
+                           float* scales, void* stream) {
+    return compress_impl(c, false, nullptr, g, grad_format, worker_err, packed, scales, 0.0f, stream);
 }
 
 int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales, float* server_err,

@@ -27,6 +27,11 @@ constexpr int kGradF32 = 0;
 constexpr int kGradF16 = 1;
 constexpr int kGradBF16 = 2;
 
+// Source of the momentum term in the worker kernel.
+constexpr int kMomRead = 0;    // read m
+constexpr int kMomGather = 1;  // decode the pending server message, write it to m (if non-null), use it
+constexpr int kMomNone = 2;    // no momentum term: u = g + delta (APGSqueeze variant, Section 5.3)
+
 // Problem geometry shared by the chunked kernels.
 struct Geometry {
     int64_t d;   // vector length
@@ -48,13 +53,13 @@ inline int64_t tiles_per_chunk(const Geometry& g, int tile) { return g.C ? (g.L 
 // Worker step over all (worker, chunk) pairs: writes u into werr, sign words into packed, one binary64
 // partial sum of u^2 per workgroup into partials [n*C][blocks_per_chunk]; a workgroup streams
 // tiles_per_block consecutive tiles of kCompressTile elements.  prev_scales (nullable, [n*C]) marks werr
-// as holding last step's u (deferred form).  gather_words ([d/32]) + gather_scales ([C]), both nullable
-// together, mark a deferred gather: the kernel then decodes the momentum from them, writes it to all of
-// m (m may be null then: nothing is written) and does not read m.  g holds grad_format elements (kGradF32 / kGradF16 / kGradBF16).
-hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
-                           const void* g, int grad_format, float* werr, uint32_t* packed, double* partials,
-                           const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
-                           float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream);
+// as holding last step's u (deferred form).  `momentum` is kMomRead, kMomGather (gather_words [d/32] and
+// gather_scales [C] describe the pending gather; m may be null: nothing is written) or kMomNone.  g holds grad_format elements (kGradF32 / kGradF16 / kGradBF16).
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, int momentum,
+                           float* m, const void* g, int grad_format, float* werr, uint32_t* packed,
+                           double* partials, const float* prev_scales, const uint32_t* gather_words,
+                           const float* gather_scales, float beta, float one_minus_beta, int32_t lds_pad,
+                           hipStream_t stream);
 
 // Reduce partials [pairs][blocks_per_chunk] in fixed order, scale = fl32(sqrt(S / L));
 // writes scales_out[pair] and pending_out[pair] (either may be null).
@@ -77,6 +82,11 @@ hipError_t launch_server_reduce(const Geometry& geo, int32_t tiles_per_block, in
 hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const float* sscales, const float* v,
                         float* x, float* m, float* scales_copy, bool write_m, bool model_step, float lr,
                         float eps, int32_t lds_pad, hipStream_t stream);
+
+// APGSqueeze variant: m_i <- beta*m_i + (1-beta)*ghat for all n slices, model step with the new momentum.
+hipError_t launch_apply_gradient(const Geometry& geo, const uint32_t* spacked, const float* sscales,
+                                 const float* v, float* x, float* m, float lr, float beta, float one_minus_beta,
+                                 float eps, int32_t lds_pad, hipStream_t stream);
 
 // Adam warm-up step on the averaged gradient (g in grad_format).
 hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const void* g, int grad_format, float lr,

@@ -49,10 +49,13 @@ __device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
     }
 }
 
-// kGather: a deferred gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum of
-// every worker is the decoded server message (gather_words, gather_scale); write it to m (unless m is
-// null: implicit-momentum mode) and use it directly instead of reading m back.
-template <bool kFull, bool kGather, int G>
+// Where the momentum term of u comes from:
+//   kMomRead    m is read.
+//   kMomGather  a deferred gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum
+//               of every worker is the decoded server message (gather_words, gather_scale); write it to m
+//               (unless m is null: implicit-momentum mode) and use it directly instead of reading m back.
+//   kMomNone    APGSqueeze variant (Section 5.3): the gradient itself is compensated, u = g + delta.
+template <bool kFull, int MOM, int G>
 __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void* __restrict__ g,
                                               float* __restrict__ e, uint32_t* __restrict__ packed,
                                               const uint32_t* __restrict__ gather_words, float gather_scale,
@@ -70,9 +73,9 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void*
         ok[r] = kFull || (off0 + 32 * r < L);
         if (ok[r]) {
             const int64_t p = chunk_base + off0 + 32 * r;
-            if (kGather)
+            if (MOM == kMomGather)
                 gw[r] = gather_words[(vec_base + off0 + 32 * r) >> 5];
-            else
+            else if (MOM == kMomRead)
                 vm[r] = load_stream(m + p);
             vg[r] = load_grad4<G>(g, p);
             ve[r] = load_stream(e + p);
@@ -83,13 +86,19 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void*
     for (int r = 0; r < ROWS; ++r) {
         uint32_t nib = 0u;
         if (ok[r]) {
-            if (kGather) {
+            if (MOM == kMomGather) {
                 const uint32_t gn = gw[r] >> shift;
 #pragma unroll
                 for (int c = 0; c < 4; ++c) vm[r][c] = signed_scale((gn >> c) & 1u, gather_scale);
                 if (m) store_stream(m + chunk_base + off0 + 32 * r, vm[r]);
             }
-            const f32x4 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
+            f32x4 u;
+            if (MOM == kMomNone) {
+#pragma unroll
+                for (int c = 0; c < 4; ++c) u[c] = vg[r][c] + read_error(ve[r][c], prev_scale);
+            } else {
+                u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
+            }
             store_stream(e + chunk_base + off0 + 32 * r, u);
             accumulate_squares(acc, u);
             nib = sign_nibble(u) << shift;
@@ -103,7 +112,7 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void*
     }
 }
 
-template <bool kGather, int G>
+template <int MOM, int G>
 __global__ __launch_bounds__(kThreads) void compress_kernel(
     float* __restrict__ m, const void* __restrict__ g, float* __restrict__ e, uint32_t* __restrict__ packed,
     double* __restrict__ partials, const float* __restrict__ prev_scales,
@@ -119,7 +128,7 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     const int64_t vec_base = chunk * L;                   // inside one [d] vector
     const int64_t chunk_base = worker * d + vec_base;     // inside [n][d]
     const float prev_scale = prev_scales ? prev_scales[pair] : 0.0f;
-    const float gather_scale = kGather ? gather_scales[chunk] : 0.0f;
+    const float gather_scale = (MOM == kMomGather) ? gather_scales[chunk] : 0.0f;
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     const int lane_off = packing_lane_offset<kCompressRows>(wave, lane);
@@ -129,10 +138,10 @@ __global__ __launch_bounds__(kThreads) void compress_kernel(
     for (int32_t t = t0; t < t1; ++t) {
         const int64_t tile_off = static_cast<int64_t>(t) * kCompressTile;
         if (tile_off + kCompressTile <= L)
-            compress_tile<true, kGather, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+            compress_tile<true, MOM, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
                                          tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
         else
-            compress_tile<false, kGather, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+            compress_tile<false, MOM, G>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
                                           tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc);
     }
     const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
@@ -357,6 +366,64 @@ __global__ __launch_bounds__(kThreads) void apply_kernel(const uint32_t* __restr
     }
 }
 
+// APGSqueeze variant (Section 5.3): the decoded server message is the averaged gradient ghat; every
+// worker's momentum slice takes m <- beta*m + (1-beta)*ghat, and slice 0's workgroups take the model step
+// with the new momentum.  Same slice-major tiling as apply_kernel.
+__global__ __launch_bounds__(kThreads) void apply_gradient_kernel(const uint32_t* __restrict__ spacked,
+                                                                  const float* __restrict__ sscales,
+                                                                  const float* __restrict__ v,
+                                                                  float* __restrict__ x, float* __restrict__ m,
+                                                                  int64_t d, int64_t L, int64_t tiles_per_slice,
+                                                                  int32_t tiles_per_chunk, float lr, float beta,
+                                                                  float omb, float eps) {
+    constexpr int ROWS = kApplyRows;
+    constexpr int kRowStride = kThreads * 4;              // plain layout
+    const int64_t blk = blockIdx.x;
+    const int64_t slice = blk / tiles_per_slice;
+    const int64_t ct = blk - slice * tiles_per_slice;
+    const int64_t chunk = ct / tiles_per_chunk;
+    const int64_t tile = ct - chunk * tiles_per_chunk;
+    const int64_t chunk_base = chunk * L;
+    const float s = sscales[chunk];
+    const int64_t off0 = tile * kApplyTile + threadIdx.x * 4;
+    const int shift = 4 * (threadIdx.x & 7);
+    const bool model_step = (slice == 0);
+    float* __restrict__ mslice = m + slice * d;
+#pragma unroll
+    for (int r = 0; r < ROWS; ++r) {
+        if (off0 + r * kRowStride >= L) continue;
+        const int64_t p = chunk_base + off0 + r * kRowStride;
+        const uint32_t nib = spacked[p >> 5] >> shift;
+        const f32x4 mo = load_stream(mslice + p);
+        f32x4 vv, vx;
+        if (model_step) {
+            vv = load_stream(v + p);
+            vx = load_stream(x + p);
+        }
+        f32x4 mn;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float ghat = signed_scale((nib >> c) & 1u, s);
+            const float keep = beta * mo[c];
+            const float inc = omb * ghat;
+            mn[c] = keep + inc;
+        }
+        store_stream(mslice + p, mn);
+        if (model_step) {
+            f32x4 xn;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float root = sqrtf(vv[c]);
+                const float denom = root + eps;
+                const float ratio = mn[c] / denom;
+                const float step = lr * ratio;
+                xn[c] = vx[c] - step;
+            }
+            store_stream(x + p, xn);
+        }
+    }
+}
+
 // ------------------------------------------------------------------------
 // Warm-up: original Adam on the averaged gradient (Section 3.2).
 // ------------------------------------------------------------------------
@@ -433,23 +500,53 @@ inline uint32_t stride_grid(int64_t d) {
 
 namespace {
 
-template <bool kGather, int G>
+template <int MOM, int G>
 void launch_compress_as(int64_t grid, int32_t lds_pad, hipStream_t stream, float* m, const void* g, float* werr,
                         uint32_t* packed, double* partials, const float* prev_scales, const uint32_t* gather_words,
                         const float* gather_scales, const Geometry& geo, int32_t tpc, int32_t tiles_per_block,
                         int32_t blocks_per_chunk, float beta, float omb) {
-    hipLaunchKernelGGL((compress_kernel<kGather, G>), dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad,
+    hipLaunchKernelGGL((compress_kernel<MOM, G>), dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad,
                        stream, m, g, werr, packed, partials, prev_scales, gather_words, gather_scales, geo.d, geo.L,
                        geo.C, tpc, tiles_per_block, blocks_per_chunk, beta, omb);
 }
 
 template <int G>
 hipError_t set_compress_lds_limit() {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(compress_kernel<false, G>),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
-    if (e != hipSuccess) return e;
-    return hipFuncSetAttribute(reinterpret_cast<const void*>(compress_kernel<true, G>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+    const void* kernels[] = {reinterpret_cast<const void*>(compress_kernel<kMomRead, G>),
+                             reinterpret_cast<const void*>(compress_kernel<kMomGather, G>),
+                             reinterpret_cast<const void*>(compress_kernel<kMomNone, G>)};
+    for (const void* k : kernels) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+template <int G>
+hipError_t launch_compress_mom(int momentum, int64_t grid, int32_t lds_pad, hipStream_t stream, float* m,
+                               const void* g, float* werr, uint32_t* packed, double* partials,
+                               const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
+                               const Geometry& geo, int32_t tpc, int32_t tiles_per_block, int32_t blocks_per_chunk,
+                               float beta, float omb) {
+    switch (momentum) {
+        case kMomRead:
+            launch_compress_as<kMomRead, G>(grid, lds_pad, stream, m, g, werr, packed, partials, prev_scales,
+                                            gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                            blocks_per_chunk, beta, omb);
+            break;
+        case kMomGather:
+            launch_compress_as<kMomGather, G>(grid, lds_pad, stream, m, g, werr, packed, partials, prev_scales,
+                                              gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                              blocks_per_chunk, beta, omb);
+            break;
+        case kMomNone:
+            launch_compress_as<kMomNone, G>(grid, lds_pad, stream, m, g, werr, packed, partials, prev_scales,
+                                            gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                            blocks_per_chunk, beta, omb);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 }  // namespace
@@ -463,6 +560,7 @@ hipError_t enable_large_lds_pads() {
                              reinterpret_cast<const void*>(apply_kernel<true, true>),
                              reinterpret_cast<const void*>(apply_kernel<false, true>),
                              reinterpret_cast<const void*>(apply_kernel<true, false>),
+                             reinterpret_cast<const void*>(apply_gradient_kernel),
                              reinterpret_cast<const void*>(finalize_kernel)};
     for (const void* k : kernels) {
         e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
@@ -471,25 +569,29 @@ hipError_t enable_large_lds_pads() {
     return hipSuccess;
 }
 
-hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, float* m,
-                           const void* g, int grad_format, float* werr, uint32_t* packed, double* partials,
-                           const float* prev_scales, const uint32_t* gather_words, const float* gather_scales,
-                           float beta, float one_minus_beta, int32_t lds_pad, hipStream_t stream) {
+hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t blocks_per_chunk, int momentum,
+                           float* m, const void* g, int grad_format, float* werr, uint32_t* packed,
+                           double* partials, const float* prev_scales, const uint32_t* gather_words,
+                           const float* gather_scales, float beta, float one_minus_beta, int32_t lds_pad,
+                           hipStream_t stream) {
     const int64_t grid = static_cast<int64_t>(geo.n) * geo.C * blocks_per_chunk;
     if (grid <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile));
-#define APMS_COMPRESS_CASE(GATHER, G)                                                                         \
-    launch_compress_as<GATHER, G>(grid, lds_pad, stream, m, g, werr, packed, partials, prev_scales, gather_words, \
-                                  gather_scales, geo, tpc, tiles_per_block, blocks_per_chunk, beta, one_minus_beta)
-    const bool gather = gather_words != nullptr;
     switch (grad_format) {
-        case kGradF32: if (gather) APMS_COMPRESS_CASE(true, kGradF32); else APMS_COMPRESS_CASE(false, kGradF32); break;
-        case kGradF16: if (gather) APMS_COMPRESS_CASE(true, kGradF16); else APMS_COMPRESS_CASE(false, kGradF16); break;
-        case kGradBF16: if (gather) APMS_COMPRESS_CASE(true, kGradBF16); else APMS_COMPRESS_CASE(false, kGradBF16); break;
+        case kGradF32:
+            return launch_compress_mom<kGradF32>(momentum, grid, lds_pad, stream, m, g, werr, packed, partials,
+                                                 prev_scales, gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                                 blocks_per_chunk, beta, one_minus_beta);
+        case kGradF16:
+            return launch_compress_mom<kGradF16>(momentum, grid, lds_pad, stream, m, g, werr, packed, partials,
+                                                 prev_scales, gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                                 blocks_per_chunk, beta, one_minus_beta);
+        case kGradBF16:
+            return launch_compress_mom<kGradBF16>(momentum, grid, lds_pad, stream, m, g, werr, packed, partials,
+                                                  prev_scales, gather_words, gather_scales, geo, tpc, tiles_per_block,
+                                                  blocks_per_chunk, beta, one_minus_beta);
         default: return hipErrorInvalidValue;
     }
-#undef APMS_COMPRESS_CASE
-    return hipGetLastError();
 }
 
 hipError_t launch_scales(int64_t pairs, int32_t blocks_per_chunk, int64_t L, const double* partials,
@@ -540,6 +642,19 @@ hipError_t launch_apply(const Geometry& geo, const uint32_t* spacked, const floa
     else
         hipLaunchKernelGGL((apply_kernel<true, false>), g, b, lds_pad, stream, spacked, sscales, v, x, m, scales_copy,
                            geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_apply_gradient(const Geometry& geo, const uint32_t* spacked, const float* sscales,
+                                 const float* v, float* x, float* m, float lr, float beta, float one_minus_beta,
+                                 float eps, int32_t lds_pad, hipStream_t stream) {
+    const int64_t tpc = tiles_per_chunk(geo, kApplyTile);
+    const int64_t tiles_per_slice = static_cast<int64_t>(geo.C) * tpc;
+    const int64_t grid = tiles_per_slice * geo.n;
+    if (grid <= 0) return hipSuccess;
+    hipLaunchKernelGGL(apply_gradient_kernel, dim3(static_cast<uint32_t>(grid)), dim3(kThreads), lds_pad, stream,
+                       spacked, sscales, v, x, m, geo.d, geo.L, tiles_per_slice, static_cast<int32_t>(tpc), lr, beta,
+                       one_minus_beta, eps);
     return hipGetLastError();
 }
 

@@ -81,6 +81,12 @@ class DeviceRun:
         self.server_reduce(stream)
         self.apply(lr, eps, stream)
 
+    def step_gradient(self, g, beta, lr, eps, stream=None):
+        """One step of the APGSqueeze variant (Section 5.3): the gradient is what gets compressed."""
+        B.apms_compress_gradient(self.ctx, g, self._grad_format(g), self.werr, self.packed, self.scales, stream)
+        self.server_reduce(stream)
+        B.apms_apply_gradient(self.ctx, self.spacked, self.sscales, self.v, self.x, self.m, lr, beta, eps, stream)
+
     def finalize(self, stream=None):
         """Bring every pending buffer (both errors, the momentum) to its final contents."""
         B.apms_finalize(self.ctx, self.werr, self.serr, self.m, stream)

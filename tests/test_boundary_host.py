@@ -152,6 +152,19 @@ def test_sixteen_bit_gradient_entry_points(ctx):
     assert status_of(B.apms_compress, ctx, m, g, g + 32768, p, sc, 0.9) == B.APMS_EALIAS      # fp32 g is twice as long
 
 
+def test_gradient_variant_entry_points(ctx):
+    g, e, p, sc, m = [fake(i) for i in range(5)]
+    for fmt in (0, B.APMS_GRAD_F16, B.APMS_GRAD_BF16):
+        assert status_of(B.apms_compress_gradient, ctx, g, fmt, e, p, sc) == B.APMS_ENODEV
+    assert status_of(B.apms_compress_gradient, ctx, g, 9, e, p, sc) == B.APMS_EINVAL
+    assert status_of(B.apms_compress_gradient, ctx, None, 0, e, p, sc) == B.APMS_EINVAL
+    assert status_of(B.apms_compress_gradient, ctx, g, 0, g + 16, p, sc) == B.APMS_EALIAS
+    assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m, 1e-4, 0.9, 1e-8) == B.APMS_ENODEV
+    assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m, 1e-4, 1.0, 1e-8) == B.APMS_EINVAL
+    assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, e, 1e-4, 0.9, 1e-8) == B.APMS_EALIAS
+    assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m + 8, 1e-4, 0.9, 1e-8) == B.APMS_EALIGN
+
+
 def test_empty_problem_is_ok_without_a_device():
     c = B.apms_create(0, 4, 64, B.APMS_DEVICE_NONE)
     try:

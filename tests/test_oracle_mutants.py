@@ -35,9 +35,11 @@ MUTANTS = [
     ("gather_one_worker", "for (int32_t i = 0; i < n; ++i)\n            m[(int64_t)i * d + j] = mj;",
      "for (int32_t i = 0; i < 1; ++i)\n            m[(int64_t)i * d + j] = mj;"),
     ("no_sqrt_of_v", "float root = sqrtf(v[j]);", "float root = v[j];"),
-    ("ascent", "x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----", "x[j] = x[j] + step;\n    }\n    return 0;\n}\n\n/* ----"),
-    ("apply_no_lr", "float step = lr * ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----",
-     "float step = ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/* ----"),
+    ("ascent", "x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/*\n * APGSqueeze",
+     "x[j] = x[j] + step;\n    }\n    return 0;\n}\n\n/*\n * APGSqueeze"),
+    ("apply_no_lr", "float step = lr * ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/*\n * APGSqueeze",
+     "float step = ratio;\n        x[j] = x[j] - step;\n    }\n    return 0;\n}\n\n/*\n * APGSqueeze"),
+    ("apg_ascent", "x[j] = x[j] - delta_x;", "x[j] = x[j] + delta_x;"),
     ("apply_scale_of_chunk0", "sscales[k], sdense ? sdense + base : NULL,", "sscales[0], sdense ? sdense + base : NULL,"),
     ("adam_v_uses_g_not_gsq", "float v_inc = omb2 * gsq;", "float v_inc = omb2 * gbar;"),
     ("adam_no_bias_correction_m", "float mhat = m_new / bc1;", "float mhat = m_new;"),
@@ -45,6 +47,12 @@ MUTANTS = [
     ("adam_t_off_by_one", "pow((double)beta2, (double)t)", "pow((double)beta2, (double)(t - 1) + 1e-9)"),
     ("adam_eps_inside_sqrt", "float root = sqrtf(vhat);", "float root = sqrtf(vhat + 1e-6f);"),
     ("adam_sum_not_mean", "float gbar = acc * inv_n;", "float gbar = acc;"),
+    ("apg_compensate_minus", "u[j] = g[base + j] + werr[base + j];", "u[j] = g[base + j] - werr[base + j];"),
+    ("apg_momentum_not_decayed", "float keep = beta * m[(int64_t)i * d + j];", "float keep = m[(int64_t)i * d + j];"),
+    ("apg_beta_on_gradient", "float inc = one_minus_beta * ghat;", "float inc = beta * ghat;"),
+    ("apg_step_uses_gradient", "float direction = m[j] / precond;", "float direction = ghat / precond;"),
+    ("apg_no_sqrt_of_v", "float root_v = sqrtf(v[j]);", "float root_v = v[j];"),
+    ("apg_one_worker", "for (int32_t i = 0; i < n; ++i) {\n            float keep", "for (int32_t i = 0; i < 1; ++i) {\n            float keep"),
     ("f16_bias_off_by_one", "const int bias = (1 << (exp_bits - 1)) - 1;", "const int bias = (1 << (exp_bits - 1));"),
     ("g16_subnormal_as_normal", "value = ldexp((double)f, 1 - bias - frac_bits);", "value = ldexp((double)((1 << frac_bits) + f), e - bias - frac_bits);"),
     ("g16_sign_dropped", "out[j] = (float)(negative ? -value : value);", "out[j] = (float)value;"),
@@ -95,7 +103,8 @@ def test_pins_catch_planted_mistake(mutant, tmp_path, monkeypatch):
     good = oracle._load()
     bad = ctypes.CDLL(str(so_path))
     for fname in ("apms_oracle_compress", "apms_oracle_server_reduce", "apms_oracle_apply",
-                  "apms_oracle_warmup_step", "apms_oracle_freeze", "apms_oracle_widen_g16"):
+                  "apms_oracle_warmup_step", "apms_oracle_freeze", "apms_oracle_widen_g16",
+                  "apms_oracle_apply_gradient"):
         getattr(bad, fname).argtypes = getattr(good, fname).argtypes
         getattr(bad, fname).restype = getattr(good, fname).restype
     monkeypatch.setattr(oracle, "_lib", bad)

@@ -459,6 +459,59 @@ def test_empty_input():
                  1e-4, 1e-8)
 
 
+# ------------------------------------------- APGSqueeze variant (Sec. 5.3) ---
+
+def test_apgsqueeze_identity_is_momentum_sgd_and_recursion_holds():
+    """Section 5.3 item 4: error-compensated compression of the gradient.  With C = identity it is momentum
+    SGD preconditioned by the frozen v; with the 1-bit compressor the double error feedback telescopes:
+    ghat_t + D_t = gbar_t + D_{t-1}, D = mean_i delta_i + delta_server, ghat = decoded server message."""
+    rng = np.random.default_rng(21)
+    d, n, L, T = 2048, 4, 512, 6
+    beta, lr, eps = F(0.9), F(1e-4), F(1e-8)
+    x, m, v = rand_state(rng, d, n, shared_m=True)
+    ident = oracle.State(d, n, L, x, m, v)
+    onebit = oracle.State(d, n, L, x, m, v)
+    x64, m64 = x.astype(np.float64), m[0].astype(np.float64)
+    P = 1.0 / (np.sqrt(v.astype(np.float64)) + np.float64(eps))
+    for t in range(T):
+        g = rng.normal(0, 1e-2, (n, d)).astype(F)
+        gbar = g.astype(np.float64).mean(axis=0)
+        ident.step_gradient(g, beta, lr, eps, compressor=oracle.IDENTITY)
+        m64 = np.float64(beta) * m64 + np.float64(F(1) - beta) * gbar
+        x64 = x64 - np.float64(lr) * m64 * P
+        assert not ident.werr.any() and not ident.serr.any()
+        D_prev = _delta(onebit)
+        m_prev = onebit.m[0].astype(np.float64)
+        onebit.step_gradient(g, beta, lr, eps)
+        ghat = decode(onebit.spacked, onebit.sscales, L)
+        np.testing.assert_allclose(ghat + _delta(onebit), gbar + D_prev, rtol=0, atol=5e-9)
+        np.testing.assert_allclose(onebit.m[0], np.float64(beta) * m_prev + np.float64(F(1) - beta) * ghat,
+                                   rtol=1e-6, atol=1e-10)
+        for i in range(1, n):
+            np.testing.assert_array_equal(onebit.m[i], onebit.m[0])
+    np.testing.assert_allclose(ident.m[0], m64, rtol=1e-5, atol=1e-9)
+    np.testing.assert_allclose(ident.x, x64, rtol=1e-5, atol=1e-7)
+    assert np.abs(onebit.x - x).max() > 1e-6
+
+
+def test_apgsqueeze_hand_values():
+    """u = g + delta = 3 everywhere -> scale 3, error 0; then m = 0.75*4 + 0.25*3 = 3.75 and, with v = 1,
+    eps = 0.25, lr = 0.5: x = 1 - 0.5*3.75/1.25 = -0.5, all exact."""
+    d, L, n = 64, 32, 2
+    g = np.full((n, d), 2.0, F)
+    werr = np.full((n, d), 1.0, F)
+    b = bufs(d, n, L)
+    oracle.compress(d, n, L, None, g, werr, b["packed"], b["scales"], 0.0)
+    assert np.all(b["scales"] == 3.0) and np.all(werr == 0) and np.all(b["packed"] == 0xFFFFFFFF)
+    serr = np.zeros(d, F)
+    oracle.server_reduce(d, n, L, b["packed"], b["scales"], serr, b["spacked"], b["sscales"])
+    assert np.all(b["sscales"] == 3.0) and not serr.any()
+    m = np.full((n, d), 4.0, F)
+    x = np.ones(d, F)
+    oracle.apply_gradient(d, n, L, b["spacked"], b["sscales"], np.ones(d, F), x, m, 0.5, 0.75, 0.25)
+    assert np.all(m == 3.75) and np.all(x == -0.5)
+
+
 # ------------------------------------------------- 16-bit gradient inputs ---
 
 def test_widen_f16_all_patterns_against_numpy():

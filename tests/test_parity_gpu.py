@@ -444,3 +444,33 @@ def test_implicit_momentum_mode():
     run.finalize()
     compare_all(run, ost, "implicit end")
     run.close()
+
+
+@pytest.mark.parametrize("deferred", [0, B.APMS_DEFER_ERRORS], ids=["eager", "defer-errors"])
+@pytest.mark.parametrize("fmt", ["f32", "bf16"])
+def test_gradient_variant(deferred, fmt):
+    """APGSqueeze variant (Section 5.3): the gradient is compensated and compressed, every worker forms the
+    momentum from the decoded average.  6 steps on ragged chunks, every buffer against the oracle."""
+    wl = W.Workload("apg", 1, d=2 * (4096 * 4 + 224), n=5, chunk=4096 * 4 + 224, steps=6)
+    d, n, L = wl.d_pad, wl.n, wl.L
+    st = W.host_state(wl)
+    st["m"][:] = st["m"][0]                      # workers share the momentum, as after a warm-up
+    ost = oracle_state(d, n, L, st)
+    run = from_host_state(wl, st, DEV, deferred=deferred)
+    for step in range(wl.steps):
+        say("gradient variant %s step %d mode=%d" % (fmt, step, deferred))
+        if fmt == "f32":
+            g = W.host_grad(wl, step)
+            gd = torch.from_numpy(g).to(DEV)
+        else:
+            bits = W.host_grad_g16(wl, step, fmt)
+            g = oracle.widen_g16(bits, oracle.GRAD_BF16)
+            gd = W.g16_bits_to_tensor(bits, fmt, DEV)
+        run.step_gradient(gd, wl.beta, wl.lr, wl.eps)
+        ost.step_gradient(g, wl.beta, wl.lr, wl.eps)
+        compare_all(run, ost, "apg step %d" % step, errors=not deferred, momentum=False)
+        close(host(run.m), ost.m, "apg momentum")
+    run.finalize()
+    compare_all(run, ost, "apg end", momentum=False)
+    close(host(run.m), ost.m, "apg momentum")
+    run.close()
