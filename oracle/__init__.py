@@ -53,6 +53,11 @@ def _load():
         lib.apms_oracle_apply_gradient.restype = ctypes.c_int
         lib.apms_oracle_warmup_step.argtypes = [i64, i32, ptr, ptr, ptr, ptr, f32, f32, f32, f32, i64]
         lib.apms_oracle_freeze.argtypes = [i64, i32, ptr, ptr, ptr, ptr]
+        lib.apms_oracle_topk_compress.argtypes = [i64, i32, i64, i64, ptr, ptr, ptr, ptr, ptr, f32]
+        lib.apms_oracle_topk_server_reduce.argtypes = [i64, i32, i64, i64, ptr, ptr, ptr, ptr, ptr]
+        lib.apms_oracle_topk_apply.argtypes = [i64, i32, i64, i64, ptr, ptr, ptr, ptr, ptr, f32, f32]
+        for fn in (lib.apms_oracle_topk_compress, lib.apms_oracle_topk_server_reduce, lib.apms_oracle_topk_apply):
+            fn.restype = ctypes.c_int
         lib.apms_oracle_widen_g16.argtypes = [ctypes.c_int, i64, ptr, ptr]
         lib.apms_oracle_widen_g16.restype = ctypes.c_int
         for fn in (lib.apms_oracle_compress, lib.apms_oracle_server_reduce, lib.apms_oracle_apply,
@@ -152,6 +157,43 @@ def widen_g16(g16, fmt):
     return out
 
 
+def _check_topk(d, n, L, K):
+    _check_shape(d, n, L)
+    if not 1 <= K <= L:
+        raise ValueError("need 1 <= K <= L")
+
+
+def topk_compress(d, n, L, K, m, g, werr, idx, val, beta):
+    """Worker step with the top-k compressor; werr, idx, val ([n][C][K]) written in place."""
+    _check_topk(d, n, L, K)
+    C = d // L
+    f, u = np.float32, np.uint32
+    rc = _load().apms_oracle_topk_compress(d, n, L, K, _p(m, f, n * d), _p(g, f, n * d), _p(werr, f, n * d),
+                                           _p(idx, u, n * C * K), _p(val, f, n * C * K), np.float32(beta))
+    if rc:
+        raise MemoryError("oracle topk_compress")
+
+
+def topk_server_reduce(d, n, L, K, idx, val, serr, sidx, sval):
+    """Server step with the top-k compressor; serr, sidx, sval ([C][K]) written in place."""
+    _check_topk(d, n, L, K)
+    C = d // L
+    f, u = np.float32, np.uint32
+    rc = _load().apms_oracle_topk_server_reduce(d, n, L, K, _p(idx, u, n * C * K), _p(val, f, n * C * K),
+                                                _p(serr, f, d), _p(sidx, u, C * K), _p(sval, f, C * K))
+    if rc:
+        raise MemoryError("oracle topk_server_reduce")
+
+
+def topk_apply(d, n, L, K, sidx, sval, v, x, m, lr, eps):
+    """Gather + model update with the top-k compressor; x and all n slices of m written in place."""
+    _check_topk(d, n, L, K)
+    C = d // L
+    f, u = np.float32, np.uint32
+    _load().apms_oracle_topk_apply(d, n, L, K, _p(sidx, u, C * K), _p(sval, f, C * K), _p(v, f, d), _p(x, f, d),
+                                   _p(m, f, n * d), np.float32(lr), np.float32(eps))
+
+
 class State:
     """Host-side state of the compression stage for n simulated workers (numpy arrays)."""
 
@@ -182,6 +224,19 @@ class State:
         server_reduce(d, n, L, self.packed, self.scales, self.serr, self.spacked, self.sscales,
                       compressor, self.dense, self.sdense)
         apply(d, n, L, self.spacked, self.sscales, self.v, self.x, self.m, lr, eps, compressor, self.sdense)
+
+    def step_topk(self, g, K, beta, lr, eps):
+        """One compressed step with the top-k compressor (K kept elements per chunk)."""
+        d, n, L, C = self.d, self.n, self.L, self.C
+        g = np.ascontiguousarray(g, dtype=np.float32).reshape(n, d)
+        if getattr(self, "idx", None) is None or self.idx.shape[-1] != K:
+            self.idx = np.zeros((n, C, K), np.uint32)
+            self.val = np.zeros((n, C, K), np.float32)
+            self.sidx = np.zeros((C, K), np.uint32)
+            self.sval = np.zeros((C, K), np.float32)
+        topk_compress(d, n, L, K, self.m, g, self.werr, self.idx, self.val, beta)
+        topk_server_reduce(d, n, L, K, self.idx, self.val, self.serr, self.sidx, self.sval)
+        topk_apply(d, n, L, K, self.sidx, self.sval, self.v, self.x, self.m, lr, eps)
 
     def step_gradient(self, g, beta, lr, eps, compressor=ONEBIT):
         """One APGSqueeze step: compress g + delta, server reduce, momentum + model update."""

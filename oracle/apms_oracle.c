@@ -395,3 +395,165 @@ int apms_oracle_widen_g16(int format, int64_t count, const uint16_t *in, float *
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------------ */
+/* Top-k compressor (Section 5.1, second bullet) under the same             */
+/* error-compensated worker / server / gather structure.                    */
+/* ------------------------------------------------------------------------ */
+
+/*
+ * "We take top k% elements ... sorted by its absolute magnitude": C[u] keeps
+ * the K elements of largest |u| of a chunk and zeroes the rest.  The paper
+ * does not say what happens between equal magnitudes; this build keeps the
+ * LOWER index first, which makes the result unique.  The wire form of a
+ * chunk is K (index, value) pairs, indices local to the chunk, ascending.
+ * Here: order all L indices by (|u| descending, index ascending) with the
+ * library sort, take the first K, and list them by ascending index.
+ */
+static const float *topk_sort_values; /* qsort has no context argument */
+
+static int topk_by_magnitude(const void *pa, const void *pb)
+{
+    const uint32_t a = *(const uint32_t *)pa, b = *(const uint32_t *)pb;
+    const float ma = fabsf(topk_sort_values[a]), mb = fabsf(topk_sort_values[b]);
+    if (ma > mb) return -1;
+    if (ma < mb) return 1;
+    return (a < b) ? -1 : (a > b);
+}
+
+static int topk_by_index(const void *pa, const void *pb)
+{
+    const uint32_t a = *(const uint32_t *)pa, b = *(const uint32_t *)pb;
+    return (a < b) ? -1 : (a > b);
+}
+
+/* u[0..L) in; idx[0..K), val[0..K) wire form out; c[0..L) decoded C[u] out. */
+static int compress_chunk_topk(const float *u, int64_t L, int64_t K, uint32_t *idx, float *val, float *c)
+{
+    uint32_t *order = (uint32_t *)malloc((size_t)L * sizeof(uint32_t));
+    if (!order)
+        return -1;
+    for (int64_t j = 0; j < L; ++j)
+        order[j] = (uint32_t)j;
+    topk_sort_values = u;
+    qsort(order, (size_t)L, sizeof(uint32_t), topk_by_magnitude);
+    qsort(order, (size_t)K, sizeof(uint32_t), topk_by_index);
+    for (int64_t j = 0; j < L; ++j)
+        c[j] = 0.0f;
+    for (int64_t t = 0; t < K; ++t) {
+        idx[t] = order[t];
+        val[t] = u[order[t]];
+        c[order[t]] = u[order[t]];
+    }
+    free(order);
+    return 0;
+}
+
+/* Value of element j of a chunk decoded from its (idx, val) list (0 if absent). */
+static float decode_topk_elem(const uint32_t *idx, const float *val, int64_t K, int64_t j)
+{
+    for (int64_t t = 0; t < K; ++t)
+        if ((int64_t)idx[t] == j)
+            return val[t];
+    return 0.0f;
+}
+
+/*
+ * Worker step with the top-k compressor (same equations as apms_oracle_compress):
+ *   u = beta*m_i + (1-beta)*g_i + delta_i ;  send C[u] ;  delta_i <- u - C[u]
+ * idx, val: [n][d/L][K] out.  1 <= K <= L.
+ */
+int apms_oracle_topk_compress(int64_t d, int32_t n, int64_t L, int64_t K, const float *m, const float *g,
+                              float *werr, uint32_t *idx, float *val, float beta)
+{
+    if (d == 0)
+        return 0;
+    const int64_t C = d / L;
+    const float one_minus_beta = 1.0f - beta;
+    float *u = (float *)malloc((size_t)L * sizeof(float));
+    float *sent = (float *)malloc((size_t)L * sizeof(float));
+    int rc = (u && sent) ? 0 : -1;
+    for (int32_t i = 0; i < n && !rc; ++i) {
+        for (int64_t k = 0; k < C && !rc; ++k) {
+            const int64_t base = (int64_t)i * d + k * L;
+            for (int64_t j = 0; j < L; ++j) {
+                float keep_m = beta * m[base + j];
+                float new_g = one_minus_beta * g[base + j];
+                float local_m = keep_m + new_g;
+                u[j] = local_m + werr[base + j];
+            }
+            const int64_t out = ((int64_t)i * C + k) * K;
+            rc = compress_chunk_topk(u, L, K, idx + out, val + out, sent);
+            for (int64_t j = 0; j < L && !rc; ++j)
+                werr[base + j] = u[j] - sent[j];
+        }
+    }
+    free(u);
+    free(sent);
+    return rc;
+}
+
+/*
+ * Server step with the top-k compressor: ubar = (1/n) sum_i C[u_i] + deltabar (the n decoded messages
+ * summed in worker order, zeros included) ; send C[ubar] ; deltabar <- ubar - C[ubar].
+ * idx, val: [n][C][K] in;  sidx, sval: [C][K] out.
+ */
+int apms_oracle_topk_server_reduce(int64_t d, int32_t n, int64_t L, int64_t K, const uint32_t *idx,
+                                   const float *val, float *serr, uint32_t *sidx, float *sval)
+{
+    if (d == 0)
+        return 0;
+    const int64_t C = d / L;
+    const float inv_n = 1.0f / (float)n;
+    float *ubar = (float *)malloc((size_t)L * sizeof(float));
+    float *sent = (float *)malloc((size_t)L * sizeof(float));
+    float *dense = (float *)malloc((size_t)L * sizeof(float));
+    int rc = (ubar && sent && dense) ? 0 : -1;
+    for (int64_t k = 0; k < C && !rc; ++k) {
+        const int64_t base = k * L;
+        for (int64_t j = 0; j < L; ++j)
+            ubar[j] = 0.0f;
+        for (int32_t i = 0; i < n; ++i) {
+            /* decode worker i's message densely, then add it: ubar holds the running sum */
+            const int64_t in = ((int64_t)i * C + k) * K;
+            for (int64_t j = 0; j < L; ++j)
+                dense[j] = 0.0f;
+            for (int64_t t = 0; t < K; ++t)
+                dense[idx[in + t]] = val[in + t];
+            for (int64_t j = 0; j < L; ++j)
+                ubar[j] = ubar[j] + dense[j];
+        }
+        for (int64_t j = 0; j < L; ++j) {
+            float mean = ubar[j] * inv_n;
+            ubar[j] = mean + serr[base + j];
+        }
+        rc = compress_chunk_topk(ubar, L, K, sidx + k * K, sval + k * K, sent);
+        for (int64_t j = 0; j < L && !rc; ++j)
+            serr[base + j] = ubar[j] - sent[j];
+    }
+    free(ubar);
+    free(sent);
+    free(dense);
+    return rc;
+}
+
+/*
+ * Gather + model update with the top-k compressor: m_i <- C[ubar] (dense: zero outside the K kept
+ * positions of each chunk), x <- x - lr * m / (sqrt(v) + eps).
+ */
+int apms_oracle_topk_apply(int64_t d, int32_t n, int64_t L, int64_t K, const uint32_t *sidx,
+                           const float *sval, const float *v, float *x, float *m, float lr, float eps)
+{
+    for (int64_t j = 0; j < d; ++j) {
+        const int64_t k = j / L;
+        float gathered = decode_topk_elem(sidx + k * K, sval + k * K, K, j - k * L);
+        for (int32_t i = 0; i < n; ++i)
+            m[(int64_t)i * d + j] = gathered;
+        float root_of_v = sqrtf(v[j]);
+        float divisor = root_of_v + eps;
+        float scaled = gathered / divisor;
+        float move = lr * scaled;
+        x[j] = x[j] - move;
+    }
+    return 0;
+}

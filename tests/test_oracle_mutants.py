@@ -10,6 +10,7 @@ import pytest
 
 import oracle
 import test_oracle_pins as pins
+import test_oracle_topk_pins as topk_pins
 
 MUTANTS = [
     # (id, old text, new text)
@@ -56,23 +57,45 @@ MUTANTS = [
     ("f16_bias_off_by_one", "const int bias = (1 << (exp_bits - 1)) - 1;", "const int bias = (1 << (exp_bits - 1));"),
     ("g16_subnormal_as_normal", "value = ldexp((double)f, 1 - bias - frac_bits);", "value = ldexp((double)((1 << frac_bits) + f), e - bias - frac_bits);"),
     ("g16_sign_dropped", "out[j] = (float)(negative ? -value : value);", "out[j] = (float)value;"),
+    ("topk_smallest_kept", "if (ma > mb) return -1;\n    if (ma < mb) return 1;", "if (ma > mb) return 1;\n    if (ma < mb) return -1;"),
+    ("topk_signed_not_magnitude", "const float ma = fabsf(topk_sort_values[a]), mb = fabsf(topk_sort_values[b]);",
+     "const float ma = topk_sort_values[a], mb = topk_sort_values[b];"),
+    ("topk_ties_higher_index_first", "    return (a < b) ? -1 : (a > b);\n}\n\nstatic int topk_by_index",
+     "    return (a > b) ? -1 : (a < b);\n}\n\nstatic int topk_by_index"),
+    ("topk_wire_not_index_ordered", "qsort(order, (size_t)K, sizeof(uint32_t), topk_by_index);", ""),
+    ("topk_error_keeps_sent_part", "werr[base + j] = u[j] - sent[j];", "werr[base + j] = u[j];"),
+    ("topk_server_error_keeps_sent_part", "serr[base + j] = ubar[j] - sent[j];", "serr[base + j] = ubar[j];"),
+    ("topk_compensate_minus", "u[j] = local_m + werr[base + j];", "u[j] = local_m - werr[base + j];"),
+    ("topk_drop_gradient", "float local_m = keep_m + new_g;", "float local_m = keep_m;"),
+    ("topk_server_no_mean", "float mean = ubar[j] * inv_n;", "float mean = ubar[j];"),
+    ("topk_server_last_worker_only", "ubar[j] = ubar[j] + dense[j];", "ubar[j] = dense[j];"),
+    ("topk_server_error_minus", "ubar[j] = mean + serr[base + j];", "ubar[j] = mean - serr[base + j];"),
+    ("topk_server_chunk0_lists", "const int64_t in = ((int64_t)i * C + k) * K;", "const int64_t in = ((int64_t)i * C) * K;"),
+    ("topk_gather_one_worker", "for (int32_t i = 0; i < n; ++i)\n            m[(int64_t)i * d + j] = gathered;",
+     "for (int32_t i = 0; i < 1; ++i)\n            m[(int64_t)i * d + j] = gathered;"),
+    ("topk_apply_no_sqrt", "float root_of_v = sqrtf(v[j]);", "float root_of_v = v[j];"),
+    ("topk_apply_ascent", "x[j] = x[j] - move;", "x[j] = x[j] + move;"),
     ("freeze_keeps_errors", "memset(serr, 0, (size_t)d * sizeof(float));", ""),
 ]
 
 
 def _pin_calls():
     calls = []
-    for name in sorted(dir(pins)):
-        fn = getattr(pins, name)
-        if not (name.startswith("test_") and callable(fn)):
-            continue
-        marks = [mk for mk in getattr(fn, "pytestmark", []) if mk.name == "parametrize"]
-        if not marks:
-            calls.append((name, fn, ()))
-        else:
-            for val in marks[0].args[1]:
-                calls.append((name, fn, (val,)))
+    for module in (pins, topk_pins):
+        for name in sorted(dir(module)):
+            fn = getattr(module, name)
+            if not (name.startswith("test_") and callable(fn)):
+                continue
+            calls.extend(_expand(name, fn))
     return calls
+
+
+def _expand(name, fn):
+    """One call per parametrize value (single-argument parametrisations only)."""
+    marks = [mk for mk in getattr(fn, "pytestmark", []) if mk.name == "parametrize"]
+    if not marks:
+        return [(name, fn, ())]
+    return [(name, fn, (val,)) for val in marks[0].args[1]]
 
 
 def _first_failure():
@@ -104,7 +127,8 @@ def test_pins_catch_planted_mistake(mutant, tmp_path, monkeypatch):
     bad = ctypes.CDLL(str(so_path))
     for fname in ("apms_oracle_compress", "apms_oracle_server_reduce", "apms_oracle_apply",
                   "apms_oracle_warmup_step", "apms_oracle_freeze", "apms_oracle_widen_g16",
-                  "apms_oracle_apply_gradient"):
+                  "apms_oracle_apply_gradient", "apms_oracle_topk_compress", "apms_oracle_topk_server_reduce",
+                  "apms_oracle_topk_apply"):
         getattr(bad, fname).argtypes = getattr(good, fname).argtypes
         getattr(bad, fname).restype = getattr(good, fname).restype
     monkeypatch.setattr(oracle, "_lib", bad)
