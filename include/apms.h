@@ -277,6 +277,32 @@ int apms_compress_gradient(apms_ctx *ctx, const void *g, int grad_format, float 
 int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *sscales, const float *v, float *x,
                         float *m, float lr, float beta, float eps, void *stream);
 
+/*
+ * Top-k compressor (Section 5.1, second bullet) under the same error-compensated worker / server /
+ * gather structure: C[u] keeps the K elements of largest |u| of every chunk (the paper's "top k%":
+ * K = k% of chunk_elems, chosen by the caller) and zeroes the rest.  Between equal magnitudes the lower
+ * index is kept first (the paper is silent; this makes the result unique).  The wire form of a chunk is
+ * K (index, value) pairs, indices local to the chunk and ascending; the selection is exact.
+ * These calls are eager (no deferral) and return ESTATE while the 1-bit path has a buffer pending;
+ * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31.
+ *
+ * apms_topk_compress:       u = (fl(beta*m_i) + fl(fl(1-beta)*g_i)) + delta_i ;  (idx, val) <- C[u] ;
+ *                           delta_i <- u - C[u]  (zero where kept, u elsewhere)
+ *     m, g [n][d] in;  worker_err [n][d] in/out;  idx, val [n][C][K] out.
+ * apms_topk_server_reduce:  ubar = (sum_{i=0}^{n-1} C[u_i]) * fl(1/n) + deltabar  (decoded lists summed in
+ *                           worker order) ;  (sidx, sval) <- C[ubar] ;  deltabar <- ubar - C[ubar]
+ *     idx, val [n][C][K] in, as written by apms_topk_compress;  server_err [d] in/out;  sidx, sval [C][K] out.
+ * apms_topk_apply:          m_i <- C[ubar] (dense: zero outside the kept positions) for every worker ;
+ *                           x <- x - lr * ( m / (sqrt(v) + eps) )
+ *     sidx, sval [C][K], v [d] in;  x [d] in/out;  m [n][d] out.
+ */
+int apms_topk_compress(apms_ctx *ctx, const float *m, const float *g, float *worker_err, uint32_t *idx,
+                       float *val, int64_t K, float beta, void *stream);
+int apms_topk_server_reduce(apms_ctx *ctx, const uint32_t *idx, const float *val, int64_t K, float *server_err,
+                            uint32_t *sidx, float *sval, void *stream);
+int apms_topk_apply(apms_ctx *ctx, const uint32_t *sidx, const float *sval, int64_t K, const float *v, float *x,
+                    float *m, float lr, float eps, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

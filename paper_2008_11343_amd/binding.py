@@ -30,6 +30,7 @@ EXPORTS = (
     "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
     "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
     "apms_compress_gradient", "apms_apply_gradient",
+    "apms_topk_compress", "apms_topk_server_reduce", "apms_topk_apply",
 )
 
 
@@ -92,6 +93,9 @@ def load():
         "apms_compress_g16": (ci, [vp, vp, vp, ci, vp, vp, vp, f32, vp]),
         "apms_compress_gradient": (ci, [vp, vp, ci, vp, vp, vp, vp]),
         "apms_apply_gradient": (ci, [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp]),
+        "apms_topk_compress": (ci, [vp, vp, vp, vp, vp, vp, i64, f32, vp]),
+        "apms_topk_server_reduce": (ci, [vp, vp, vp, i64, vp, vp, vp, vp]),
+        "apms_topk_apply": (ci, [vp, vp, vp, i64, vp, vp, vp, f32, f32, vp]),
         "apms_freeze": (ci, [vp, vp, vp, vp, vp]),
         "apms_compress": (ci, [vp, vp, vp, vp, vp, vp, f32, vp]),
         "apms_server_reduce": (ci, [vp, vp, vp, vp, vp, vp, vp]),
@@ -215,3 +219,18 @@ def apms_compress_gradient(ctx, g, grad_format, worker_err, packed, scales, stre
 def apms_apply_gradient(ctx, spacked, sscales, v, x, m, lr, beta, eps, stream=None):
     _check(ctx, load().apms_apply_gradient(ctx, _ptr(spacked), _ptr(sscales), _ptr(v), _ptr(x), _ptr(m), lr, beta,
                                            eps, _stream(stream)), "apms_apply_gradient")
+
+
+def apms_topk_compress(ctx, m, g, worker_err, idx, val, K, beta, stream=None):
+    _check(ctx, load().apms_topk_compress(ctx, _ptr(m), _ptr(g), _ptr(worker_err), _ptr(idx), _ptr(val), K, beta,
+                                          _stream(stream)), "apms_topk_compress")
+
+
+def apms_topk_server_reduce(ctx, idx, val, K, server_err, sidx, sval, stream=None):
+    _check(ctx, load().apms_topk_server_reduce(ctx, _ptr(idx), _ptr(val), K, _ptr(server_err), _ptr(sidx),
+                                               _ptr(sval), _stream(stream)), "apms_topk_server_reduce")
+
+
+def apms_topk_apply(ctx, sidx, sval, K, v, x, m, lr, eps, stream=None):
+    _check(ctx, load().apms_topk_apply(ctx, _ptr(sidx), _ptr(sval), K, _ptr(v), _ptr(x), _ptr(m), lr, eps,
+                                       _stream(stream)), "apms_topk_apply")

@@ -11,6 +11,7 @@
 #include <new>
 
 #include "apms_launch.h"
+#include "apms_topk.h"
 
 struct apms_ctx {
     int64_t d = 0;
@@ -28,6 +29,7 @@ struct apms_ctx {
     float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
     float* s_pending = nullptr;       // [C]   same for the server error buffer
     float* g_pending = nullptr;       // [C]   server scales of a gather that has not been carried out yet
+    apms::TopkScratch topk = {nullptr, nullptr, nullptr};   // selection scratch of the top-k compressor
     int64_t scratch_bytes = 0;
     // deferral bookkeeping (host side, follows call order = stream order)
     const void* pending_werr = nullptr;       // error buffers that hold u instead of delta
@@ -121,6 +123,10 @@ void free_scratch(apms_ctx* c) {
     if (c->w_pending) (void)hipFree(c->w_pending);
     if (c->s_pending) (void)hipFree(c->s_pending);
     if (c->g_pending) (void)hipFree(c->g_pending);
+    if (c->topk.hist) (void)hipFree(c->topk.hist);
+    if (c->topk.state) (void)hipFree(c->topk.state);
+    if (c->topk.tile_counts) (void)hipFree(c->topk.tile_counts);
+    c->topk = {nullptr, nullptr, nullptr};
     c->w_partials = c->s_partials = nullptr;
     c->w_pending = c->s_pending = c->g_pending = nullptr;
 }
@@ -191,7 +197,9 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     const int64_t sp = C * c->s_tiles_per_chunk * static_cast<int64_t>(sizeof(double));
     const int64_t wq = pairs * static_cast<int64_t>(sizeof(float));
     const int64_t sq = C * static_cast<int64_t>(sizeof(float));
-    c->scratch_bytes = wp + sp + wq + 2 * sq;
+    const int64_t topk_tiles = apms::tiles_per_chunk(geo, apms::kTopkTile);
+    const int64_t th = pairs * apms::kTopkBins * 4, ts = pairs * apms::kTopkStateWords * 4, tc = pairs * topk_tiles * 4;
+    c->scratch_bytes = wp + sp + wq + 2 * sq + th + ts + tc;
     if (device != APMS_DEVICE_NONE && d > 0) {
         DeviceScope scope(device);
         hipError_t e = scope.err;
@@ -201,6 +209,9 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_pending), sq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->g_pending), sq);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), th);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), ts);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tc);
         if (e != hipSuccess) {
             free_scratch(c);
             delete c;
@@ -500,6 +511,71 @@ int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const
     c->pending_m = defer ? m : nullptr;
     c->pending_spacked = defer ? spacked : nullptr;
     return APMS_OK;
+}
+
+// ---- top-k compressor (Section 5.1, second bullet): eager only -------------------------------------
+
+static int topk_shape_ok(const apms_ctx* c, int64_t K) {
+    if (c->L > (int64_t{1} << 31)) return APMS_ESHAPE;        // chunk-local indices are 32-bit
+    if (K < 1 || K > c->L) return APMS_EINVAL;
+    return APMS_OK;
+}
+
+int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worker_err, uint32_t* idx, float* val,
+                       int64_t K, float beta, void* stream) {
+    if (!c) return APMS_EINVAL;
+    if (c->d > 0)
+        if (int rc = topk_shape_ok(c, K)) return rc;
+    const int64_t all = c->d * 4 * c->n, lists = c->n * c->C * K * 4;
+    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {idx, lists}, {val, lists}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!unit_interval(beta)) return APMS_EINVAL;
+    if (c->pending_werr || c->pending_m) return APMS_ESTATE;   // this path reads m and the error as they are
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
+                                              static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
+int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, int64_t K, float* server_err,
+                            uint32_t* sidx, float* sval, void* stream) {
+    if (!c) return APMS_EINVAL;
+    if (c->d > 0)
+        if (int rc = topk_shape_ok(c, K)) return rc;
+    const int64_t lists = c->n * c->C * K * 4, slists = c->C * K * 4;
+    const Range r[] = {{idx, lists}, {val, lists}, {server_err, c->d * 4}, {sidx, slists}, {sval, slists}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (c->pending_serr) return APMS_ESTATE;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
+                                                   1.0f / static_cast<float>(c->n), c->topk,
+                                                   static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+}
+
+int apms_topk_apply(apms_ctx* c, const uint32_t* sidx, const float* sval, int64_t K, const float* v, float* x,
+                    float* m, float lr, float eps, void* stream) {
+    if (!c) return APMS_EINVAL;
+    if (c->d > 0)
+        if (int rc = topk_shape_ok(c, K)) return rc;
+    const int64_t vec = c->d * 4, slists = c->C * K * 4;
+    const Range r[] = {{sidx, slists}, {sval, slists}, {v, vec}, {x, vec}, {m, vec * c->n}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!(lr == lr) || !(eps == eps)) return APMS_EINVAL;
+    if (c->pending_m) return APMS_ESTATE;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps,
+                                           static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
 }  // extern "C"

@@ -1,0 +1,552 @@
+// Top-k compressor kernels (Section 5.1, second bullet) for gfx950: keep the K elements of largest
+// magnitude of every chunk, ties towards the lower index, and emit them as (index, value) pairs in index
+// order; everything else stays in the error buffer (error feedback, Section 3.1).
+//
+// Exact selection without sorting: the magnitude key of a value is its binary32 pattern without the sign
+// bit, which orders like |u|.  A 3-level radix select (11 + 11 + 9 bits) over per-chunk histograms finds
+// the K-th largest key T and how many elements equal to T may still be kept; only if that is fewer than
+// there are, a second 3-level radix select (11 + 11 + 10 bits) over the chunk-local index finds the last
+// such element to keep.  Histograms use integer atomics (order-independent), the emission order comes from
+// per-tile counts and a scan, so the result does not depend on scheduling.
+//
+// Built with -ffp-contract=off: the elementwise arithmetic is that of the 1-bit path.
+
+#include "apms_device.h"
+#include "apms_topk.h"
+
+namespace apms {
+
+namespace {
+
+// Per-pair selection state (uint32 words).
+enum : int {
+    kStPrefix = 0,        // key bits fixed so far (bits below the current level are zero)
+    kStRemaining = 1,     // how many elements are still to be taken from inside the current prefix
+    kStCountEq = 2,       // number of elements with key == T
+    kStTieNeeded = 3,     // 1 if only some of the elements equal to T may be kept
+    kStIdxPrefix = 4,     // index bits fixed so far (tie selection)
+    kStIdxRemaining = 5,  // how many ties are still to be taken from inside the current index prefix
+    kStKeyT = 6,          // T: the K-th largest key
+    kStIdxT = 7,          // ties are kept up to and including this chunk-local index
+};
+
+struct Level {
+    int shift;
+    int bits;
+    uint32_t match_mask;  // bits above this level: they must equal the prefix for an element to count
+};
+
+__host__ __device__ constexpr Level key_level(int l) {
+    return l == 0 ? Level{20, 11, 0u} : l == 1 ? Level{9, 11, 0x7FF00000u} : Level{0, 9, 0x7FFFFE00u};
+}
+__host__ __device__ constexpr Level idx_level(int l) {
+    return l == 0 ? Level{21, 11, 0u} : l == 1 ? Level{10, 11, 0xFFE00000u} : Level{0, 10, 0xFFFFFC00u};
+}
+
+__device__ __forceinline__ uint32_t key_of(float u) { return __builtin_bit_cast(uint32_t, u) & 0x7FFFFFFFu; }
+
+__device__ __forceinline__ bool kept(uint32_t key, uint32_t j, uint32_t T, uint32_t idxT) {
+    return key > T || (key == T && j <= idxT);
+}
+
+// One atomic per distinct bin per wave.  Must be called by all 64 lanes (inactive ones pass active = false).
+__device__ __forceinline__ void hist_add_aggregated(uint32_t* __restrict__ hist, bool active, uint32_t bin) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    uint64_t todo = __ballot(active);
+    while (todo) {
+        const int leader = __ffsll(static_cast<unsigned long long>(todo)) - 1;
+        const uint32_t lbin = static_cast<uint32_t>(__shfl(static_cast<int>(bin), leader));
+        const uint64_t same = __ballot(active && bin == lbin) & todo;
+        if (lane == leader) atomicAdd(&hist[lbin], static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(same))));
+        todo &= ~same;
+    }
+}
+
+// Exclusive scan of one uint32 per thread over the workgroup (thread order); `total` gets the sum.
+__device__ __forceinline__ uint32_t block_exclusive_scan_u32(uint32_t v, uint32_t* lds /* kWaves */, uint32_t& total) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int off = 1; off < kWaveSize; off <<= 1) {
+        const uint32_t up = static_cast<uint32_t>(__shfl_up(static_cast<int>(inc), off));
+        if (lane >= off) inc += up;
+    }
+    if (lane == kWaveSize - 1) lds[wave] = inc;
+    __syncthreads();
+    uint32_t before = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint32_t t = lds[w];
+        if (w < wave) before += t;
+        sum += t;
+    }
+    __syncthreads();
+    total = sum;
+    return before + inc - v;
+}
+
+// Decomposition of blockIdx into (pair, tile) for kernels that take one kTopkTile tile per workgroup.
+struct TileRef {
+    int64_t pair;        // slice * C + chunk
+    int64_t tile;
+    int64_t base;        // element offset of the chunk inside the [slices][d] buffer
+};
+__device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk) {
+    TileRef r;
+    const int64_t blk = blockIdx.x;
+    r.pair = blk / tiles_per_chunk;
+    r.tile = blk - r.pair * tiles_per_chunk;
+    const int64_t slice = r.pair / C;
+    const int64_t chunk = r.pair - slice * C;
+    r.base = slice * d + chunk * L;
+    return r;
+}
+
+constexpr int kTileRows = kTopkTile / (kThreads * 4);   // 128-bit rows per thread per tile, plain layout
+constexpr int kRowStride = kThreads * 4;
+
+// Flush a workgroup's LDS histogram into the pair's global histogram (non-zero bins only).
+__device__ __forceinline__ void flush_histogram(const uint32_t* lds_hist, uint32_t* __restrict__ hist) {
+    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) {
+        const uint32_t c = lds_hist[b];
+        if (c) atomicAdd(&hist[b], c);
+    }
+}
+
+// ------------------------------------------------------------------------
+// Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
+// ------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __restrict__ m,
+                                                                 const float* __restrict__ g,
+                                                                 float* __restrict__ e, uint32_t* __restrict__ hist,
+                                                                 int64_t d, int64_t L, int32_t C,
+                                                                 int32_t tiles_per_chunk, float beta, float omb) {
+    __shared__ uint32_t lds_hist[kTopkBins];
+    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
+    __syncthreads();
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = off0 + r * kRowStride;
+        if (off >= L) continue;
+        const int64_t p = tr.base + off;
+        const f32x4 vm = load_stream(m + p), vg = load_stream(g + p), ve = load_stream(e + p);
+        f32x4 u;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float bm = beta * vm[c];
+            const float bg = omb * vg[c];
+            const float mi = bm + bg;
+            u[c] = mi + ve[c];
+            atomicAdd(&lds_hist[key_of(u[c]) >> 20], 1u);
+        }
+        store_stream(e + p, u);
+    }
+    __syncthreads();
+    flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
+}
+
+// ------------------------------------------------------------------------
+// Server: decode + average the n sparse messages of a tile in LDS, add the server error, write ubar into
+// the error buffer + level-0 key histogram (Algorithm 1 line 9).
+// ------------------------------------------------------------------------
+__device__ __forceinline__ int lower_bound_u32(const uint32_t* __restrict__ a, int count, uint32_t x) {
+    int lo = 0, hi = count;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
+__global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t* __restrict__ idx,
+                                                                 const float* __restrict__ val,
+                                                                 float* __restrict__ serr, uint32_t* __restrict__ hist,
+                                                                 int64_t d, int64_t L, int32_t C, int32_t n,
+                                                                 int32_t K, int32_t tiles_per_chunk, float inv_n) {
+    __shared__ uint32_t lds_hist[kTopkBins];
+    __shared__ float acc[kTopkTile];
+    __shared__ int range[2];
+    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
+    for (int j = threadIdx.x; j < kTopkTile; j += kThreads) acc[j] = 0.0f;
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // slices = 1: pair = chunk
+    const int64_t tile_lo = tr.tile * kTopkTile;
+    const int64_t tile_hi = min(tile_lo + kTopkTile, L);
+    __syncthreads();
+    for (int32_t i = 0; i < n; ++i) {                         // worker order
+        const int64_t list = (static_cast<int64_t>(i) * C + tr.pair) * K;
+        if (threadIdx.x == 0) {
+            range[0] = lower_bound_u32(idx + list, K, static_cast<uint32_t>(tile_lo));
+            range[1] = lower_bound_u32(idx + list, K, static_cast<uint32_t>(tile_hi));
+        }
+        __syncthreads();
+        // indices are unique inside one worker's list: no two threads touch the same accumulator
+        for (int t = range[0] + threadIdx.x; t < range[1]; t += kThreads) {
+            const uint32_t j = idx[list + t] - static_cast<uint32_t>(tile_lo);
+            if (j < static_cast<uint32_t>(kTopkTile)) acc[j] = acc[j] + val[list + t];   // always true for sorted lists
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int local = threadIdx.x * 4 + r * kRowStride;
+        const int64_t off = tile_lo + local;
+        if (off >= L) continue;
+        const int64_t p = tr.base + off;
+        const f32x4 ve = load_stream(serr + p);
+        f32x4 ubar;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float mean = acc[local + c] * inv_n;
+            ubar[c] = mean + ve[c];
+            atomicAdd(&lds_hist[key_of(ubar[c]) >> 20], 1u);
+        }
+        store_stream(serr + p, ubar);
+    }
+    __syncthreads();
+    flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
+}
+
+// ------------------------------------------------------------------------
+// Radix select: pick the bin that holds the wanted element, refine the histogram inside it.
+// ------------------------------------------------------------------------
+
+// One workgroup per pair.  Scans the level's histogram (from the top bin down for keys, from bin 0 up for
+// indices) to the bin where the running count reaches `remaining`, records it in the state and clears the
+// histogram for the next level.
+template <bool kIdx>
+__global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
+                                                             int level, uint32_t K) {
+    __shared__ uint32_t lds[kWaves];
+    const int64_t pair = blockIdx.x;
+    uint32_t* h = hist + pair * kTopkBins;
+    uint32_t* st = state + pair * kTopkStateWords;
+    const bool tie_needed = kIdx ? (st[kStTieNeeded] != 0u) : true;
+    if (kIdx && !tie_needed) {                                 // every element equal to T is kept
+        if (level == 2 && threadIdx.x == 0) st[kStIdxT] = 0xFFFFFFFFu;
+        return;                                                // the histogram was never filled: still zero
+    }
+    const Level lv = kIdx ? idx_level(level) : key_level(level);
+    const int nb = 1 << lv.bits;
+    const uint32_t remaining = kIdx ? st[kStIdxRemaining] : (level == 0 ? K : st[kStRemaining]);
+    const uint32_t prefix = level == 0 ? 0u : (kIdx ? st[kStIdxPrefix] : st[kStPrefix]);
+    constexpr int kPer = kTopkBins / kThreads;                 // scan positions per thread
+    uint32_t cnt[kPer];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int pos = threadIdx.x * kPer + q;                // position in scan order
+        const int bin = kIdx ? pos : nb - 1 - pos;
+        cnt[q] = (pos < nb) ? h[bin] : 0u;
+        mine += cnt[q];
+    }
+    uint32_t total;
+    const uint32_t before_me = block_exclusive_scan_u32(mine, lds, total);   // contains __syncthreads
+#pragma unroll
+    for (int q = 0; q < kPer; ++q) {
+        const int pos = threadIdx.x * kPer + q;
+        if (pos < nb) h[kIdx ? pos : nb - 1 - pos] = 0u;
+    }
+    if (before_me < remaining && remaining <= before_me + mine) {           // exactly one thread
+        uint32_t before = before_me;
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            if (before < remaining && remaining <= before + cnt[q]) {
+                const int pos = threadIdx.x * kPer + q;
+                const uint32_t bin = static_cast<uint32_t>(kIdx ? pos : nb - 1 - pos);
+                const uint32_t new_prefix = prefix | (bin << lv.shift);
+                const uint32_t left = remaining - before;      // still to take from inside this bin
+                if (kIdx) {
+                    st[kStIdxPrefix] = new_prefix;
+                    st[kStIdxRemaining] = left;
+                    if (level == 2) st[kStIdxT] = new_prefix;
+                } else {
+                    st[kStPrefix] = new_prefix;
+                    st[kStRemaining] = left;
+                    if (level == 2) {
+                        st[kStKeyT] = new_prefix;
+                        st[kStCountEq] = cnt[q];
+                        st[kStTieNeeded] = (left < cnt[q]) ? 1u : 0u;
+                        st[kStIdxPrefix] = 0u;
+                        st[kStIdxRemaining] = left;
+                    }
+                }
+            }
+            before += cnt[q];
+        }
+    }
+}
+
+// One pass over the buffer: histogram of the next radix digit of the elements inside the current prefix.
+template <bool kIdx>
+__global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
+                                                             const uint32_t* __restrict__ state, int64_t d, int64_t L,
+                                                             int32_t C, int32_t tiles_per_chunk, int level) {
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const uint32_t* st = state + tr.pair * kTopkStateWords;
+    if (kIdx && st[kStTieNeeded] == 0u) return;
+    const Level lv = kIdx ? idx_level(level) : key_level(level);
+    const uint32_t prefix = level == 0 ? 0u : (kIdx ? st[kStIdxPrefix] : st[kStPrefix]);
+    const uint32_t T = st[kStKeyT];
+    const int64_t tile_lo = tr.tile * kTopkTile;
+    if (kIdx && level > 0) {
+        // only tiles that intersect the index range of the current prefix can contribute
+        const int64_t span = int64_t{1} << idx_level(level - 1).shift;
+        if (tile_lo + kTopkTile <= static_cast<int64_t>(prefix) || tile_lo >= static_cast<int64_t>(prefix) + span) return;
+    }
+    uint32_t* h = hist + tr.pair * kTopkBins;
+    const uint32_t digit_mask = (1u << lv.bits) - 1u;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tile_lo + threadIdx.x * 4 + r * kRowStride;
+        const bool valid = off < L;                            // uniform per wave-row only by accident: no branch
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (valid) v = load_stream(buf + tr.base + off);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const uint32_t key = key_of(v[c]);
+            const uint32_t j = static_cast<uint32_t>(off + c);
+            bool active;
+            uint32_t bin;
+            if (kIdx) {
+                active = valid && key == T && (j & lv.match_mask) == prefix;
+                bin = (j >> lv.shift) & digit_mask;
+            } else {
+                active = valid && (key & lv.match_mask) == prefix;
+                bin = (key >> lv.shift) & digit_mask;
+            }
+            hist_add_aggregated(h, active, bin);
+        }
+    }
+}
+
+// ------------------------------------------------------------------------
+// Emission in index order: per-tile counts, scan, write.
+// ------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void topk_count_kernel(const float* __restrict__ buf,
+                                                              const uint32_t* __restrict__ state,
+                                                              uint32_t* __restrict__ tile_counts, int64_t d, int64_t L,
+                                                              int32_t C, int32_t tiles_per_chunk) {
+    __shared__ uint32_t lds[kWaves];
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const uint32_t* st = state + tr.pair * kTopkStateWords;
+    const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+    uint32_t mine = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+        if (off >= L) continue;
+        const f32x4 v = load_stream(buf + tr.base + off);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) mine += kept(key_of(v[c]), static_cast<uint32_t>(off + c), T, idxT) ? 1u : 0u;
+    }
+    uint32_t total;
+    (void)block_exclusive_scan_u32(mine, lds, total);
+    if (threadIdx.x == 0) tile_counts[tr.pair * tiles_per_chunk + tr.tile] = total;
+}
+
+// One workgroup per pair: tile_counts -> exclusive offsets, in place.
+__global__ __launch_bounds__(kThreads) void topk_scan_kernel(uint32_t* __restrict__ tile_counts, int32_t tiles_per_chunk) {
+    __shared__ uint32_t lds[kWaves];
+    uint32_t* tc = tile_counts + static_cast<int64_t>(blockIdx.x) * tiles_per_chunk;
+    uint32_t carry = 0;
+    for (int32_t t0 = 0; t0 < tiles_per_chunk; t0 += kThreads) {
+        const int32_t t = t0 + threadIdx.x;
+        const uint32_t c = t < tiles_per_chunk ? tc[t] : 0u;
+        uint32_t total;
+        const uint32_t before = block_exclusive_scan_u32(c, lds, total);
+        if (t < tiles_per_chunk) tc[t] = carry + before;
+        carry += total;
+    }
+}
+
+// Writes the kept elements of a tile to the pair's (idx, val) list at the tile's offset, in index order,
+// and zeroes them in the buffer: what stays there is u - C[u].
+__global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ buf, const uint32_t* __restrict__ state,
+                                                             const uint32_t* __restrict__ tile_offsets,
+                                                             uint32_t* __restrict__ idx, float* __restrict__ val,
+                                                             int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk,
+                                                             int64_t K) {
+    __shared__ uint32_t lds[kWaves];
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const uint32_t* st = state + tr.pair * kTopkStateWords;
+    const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+    uint32_t* out_idx = idx + tr.pair * K;
+    float* out_val = val + tr.pair * K;
+    uint32_t row_base = tile_offsets[tr.pair * tiles_per_chunk + tr.tile];
+    for (int r = 0; r < kTileRows; ++r) {                      // rows are consecutive index ranges
+        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+        const bool valid = off < L;
+        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (valid) v = load_stream(buf + tr.base + off);
+        bool keep[4];
+        uint32_t mine = 0;
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            keep[c] = valid && kept(key_of(v[c]), static_cast<uint32_t>(off + c), T, idxT);
+            mine += keep[c] ? 1u : 0u;
+        }
+        uint32_t total;
+        uint32_t rank = row_base + block_exclusive_scan_u32(mine, lds, total);   // all threads take part
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (keep[c]) {
+                if (rank < K) {                                // holds by construction; guards the list bounds
+                    out_idx[rank] = static_cast<uint32_t>(off + c);
+                    out_val[rank] = v[c];
+                }
+                buf[tr.base + off + c] = 0.0f;
+                ++rank;
+            }
+        }
+        row_base += total;
+    }
+}
+
+// ------------------------------------------------------------------------
+// Gather + model update (Algorithm 1 lines 10-11) from the server's list.
+// ------------------------------------------------------------------------
+__global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __restrict__ sidx,
+                                                              const float* __restrict__ sval,
+                                                              const float* __restrict__ v, float* __restrict__ x,
+                                                              float* __restrict__ m, int64_t d, int64_t L, int32_t C,
+                                                              int32_t tiles_per_chunk, int32_t K, float lr, float eps) {
+    __shared__ float dense[kTopkTile];
+    __shared__ int range[2];
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // pair = slice * C + chunk
+    const int64_t slice = tr.pair / C;
+    const int64_t chunk = tr.pair - slice * C;
+    const int64_t tile_lo = tr.tile * kTopkTile;
+    const int64_t tile_hi = min(tile_lo + kTopkTile, L);
+    for (int j = threadIdx.x; j < kTopkTile; j += kThreads) dense[j] = 0.0f;
+    const int64_t list = chunk * K;
+    if (threadIdx.x == 0) {
+        range[0] = lower_bound_u32(sidx + list, K, static_cast<uint32_t>(tile_lo));
+        range[1] = lower_bound_u32(sidx + list, K, static_cast<uint32_t>(tile_hi));
+    }
+    __syncthreads();
+    for (int t = range[0] + threadIdx.x; t < range[1]; t += kThreads) {
+        const uint32_t j = sidx[list + t] - static_cast<uint32_t>(tile_lo);
+        if (j < static_cast<uint32_t>(kTopkTile)) dense[j] = sval[list + t];             // always true for sorted lists
+    }
+    __syncthreads();
+    const bool model_step = (slice == 0);
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int local = threadIdx.x * 4 + r * kRowStride;
+        const int64_t off = tile_lo + local;
+        if (off >= L) continue;
+        const f32x4 mom = {dense[local], dense[local + 1], dense[local + 2], dense[local + 3]};
+        store_stream(m + tr.base + off, mom);
+        if (model_step) {
+            const int64_t p = chunk * L + off;
+            const f32x4 vv = load_stream(v + p), vx = load_stream(x + p);
+            f32x4 xn;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const float root = sqrtf(vv[c]);
+                const float denom = root + eps;
+                const float ratio = mom[c] / denom;
+                const float step = lr * ratio;
+                xn[c] = vx[c] - step;
+            }
+            store_stream(x + p, xn);
+        }
+    }
+}
+
+__global__ __launch_bounds__(kThreads) void topk_zero_kernel(uint32_t* __restrict__ p, int64_t count) {
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) p[i] = 0u;
+}
+
+#define APMS_RETURN_IF_ERROR()                 \
+    do {                                       \
+        const hipError_t e_ = hipGetLastError(); \
+        if (e_ != hipSuccess) return e_;       \
+    } while (0)
+
+// The selection + emission over `slices` x C pairs of `buf` ([slices][d]) whose level-0 histogram is filled.
+hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float* buf, uint32_t* idx, float* val,
+                           const TopkScratch& s, hipStream_t stream) {
+    const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
+    const uint32_t K32 = static_cast<uint32_t>(K);
+    for (int level = 0; level < 3; ++level) {
+        if (level > 0) {
+            hipLaunchKernelGGL(topk_hist_kernel<false>, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
+                               geo.C, tpc, level);
+            APMS_RETURN_IF_ERROR();
+        }
+        hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
+        APMS_RETURN_IF_ERROR();
+    }
+    for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
+        hipLaunchKernelGGL(topk_hist_kernel<true>, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
+                           geo.C, tpc, level);
+        APMS_RETURN_IF_ERROR();
+        hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
+        APMS_RETURN_IF_ERROR();
+    }
+    hipLaunchKernelGGL(topk_count_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_counts, geo.d, geo.L, geo.C,
+                       tpc);
+    APMS_RETURN_IF_ERROR();
+    hipLaunchKernelGGL(topk_scan_kernel, per_pair, block, 0, stream, s.tile_counts, tpc);
+    APMS_RETURN_IF_ERROR();
+    hipLaunchKernelGGL(topk_emit_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_counts, idx, val, geo.d, geo.L,
+                       geo.C, tpc, K);
+    return hipGetLastError();
+}
+
+hipError_t zero_histograms(int64_t pairs, const TopkScratch& s, hipStream_t stream) {
+    const int64_t count = pairs * kTopkBins;
+    const int64_t blocks = (count + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(topk_zero_kernel, dim3(static_cast<uint32_t>(blocks < 4096 ? blocks : 4096)), dim3(kThreads), 0,
+                       stream, s.hist, count);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, const float* g, float* werr,
+                                uint32_t* idx, float* val, float beta, float one_minus_beta,
+                                const TopkScratch& scratch, hipStream_t stream) {
+    const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
+    if (pairs <= 0) return hipSuccess;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    hipError_t e = zero_histograms(pairs, scratch, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), 0, stream, m, g,
+                       werr, scratch.hist, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
+    APMS_RETURN_IF_ERROR();
+    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch, stream);
+}
+
+hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint32_t* idx, const float* val,
+                                     float* serr, uint32_t* sidx, float* sval, float inv_n,
+                                     const TopkScratch& scratch, hipStream_t stream) {
+    if (geo.C <= 0) return hipSuccess;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    hipError_t e = zero_histograms(geo.C, scratch, stream);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(topk_server_u_kernel, dim3(static_cast<uint32_t>(static_cast<int64_t>(geo.C) * tpc)),
+                       dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, geo.d, geo.L, geo.C, geo.n,
+                       static_cast<int32_t>(K), tpc, inv_n);
+    APMS_RETURN_IF_ERROR();
+    return select_and_emit(geo, 1, K, serr, sidx, sval, scratch, stream);
+}
+
+hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
+                             const float* v, float* x, float* m, float lr, float eps, hipStream_t stream) {
+    const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
+    if (pairs <= 0) return hipSuccess;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    hipLaunchKernelGGL(topk_apply_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), 0, stream, sidx, sval,
+                       v, x, m, geo.d, geo.L, geo.C, tpc, static_cast<int32_t>(K), lr, eps);
+    return hipGetLastError();
+}
+
+}  // namespace apms

@@ -81,6 +81,17 @@ class DeviceRun:
         self.server_reduce(stream)
         self.apply(lr, eps, stream)
 
+    def step_topk(self, g, K, beta, lr, eps, stream=None):
+        """One compressed step with the top-k compressor (Section 5.1): K kept elements per chunk."""
+        if getattr(self, "idx", None) is None or self.idx.shape[-1] != K:
+            i = dict(dtype=torch.int32, device=self.device)
+            f = dict(dtype=torch.float32, device=self.device)
+            self.idx, self.val = torch.zeros(self.n, self.C, K, **i), torch.zeros(self.n, self.C, K, **f)
+            self.sidx, self.sval = torch.zeros(self.C, K, **i), torch.zeros(self.C, K, **f)
+        B.apms_topk_compress(self.ctx, self.m, g, self.werr, self.idx, self.val, K, beta, stream)
+        B.apms_topk_server_reduce(self.ctx, self.idx, self.val, K, self.serr, self.sidx, self.sval, stream)
+        B.apms_topk_apply(self.ctx, self.sidx, self.sval, K, self.v, self.x, self.m, lr, eps, stream)
+
     def step_gradient(self, g, beta, lr, eps, stream=None):
         """One step of the APGSqueeze variant (Section 5.3): the gradient is what gets compressed."""
         B.apms_compress_gradient(self.ctx, g, self._grad_format(g), self.werr, self.packed, self.scales, stream)

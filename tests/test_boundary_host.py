@@ -165,6 +165,23 @@ def test_gradient_variant_entry_points(ctx):
     assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m + 8, 1e-4, 0.9, 1e-8) == B.APMS_EALIGN
 
 
+def test_topk_entry_points(ctx):
+    a = [fake(i) for i in range(6)]
+    m, g, e, idx, val, x = a
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx, val, 40, 0.9) == B.APMS_ENODEV
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx, val, 0, 0.9) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx, val, 4097, 0.9) == B.APMS_EINVAL      # K > chunk
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx, val, 40, 1.0) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, None, val, 40, 0.9) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx, idx + 16, 40, 0.9) == B.APMS_EALIAS
+    assert status_of(B.apms_topk_compress, ctx, m, g, e, idx + 4, val, 40, 0.9) == B.APMS_EALIGN
+    assert status_of(B.apms_topk_server_reduce, ctx, idx, val, 40, e, m, g) == B.APMS_ENODEV
+    assert status_of(B.apms_topk_server_reduce, ctx, idx, val, -1, e, m, g) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, m, 1e-4, 1e-8) == B.APMS_ENODEV
+    assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, x, 1e-4, 1e-8) == B.APMS_EALIAS
+    assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, m, float("nan"), 1e-8) == B.APMS_EINVAL
+
+
 def test_empty_problem_is_ok_without_a_device():
     c = B.apms_create(0, 4, 64, B.APMS_DEVICE_NONE)
     try:
