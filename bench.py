@@ -90,8 +90,10 @@ def main():
                          "deferred, but m[n][d] is never written (departs from the benchmark's state model)")
     ap.add_argument("--compress-tiles", type=int, default=0)
     ap.add_argument("--server-tiles", type=int, default=0)
-    ap.add_argument("--algo", choices=["momentum", "gradient"], default="momentum",
-                    help="momentum: APMSqueeze (the benchmark); gradient: the APGSqueeze variant of Section 5.3")
+    ap.add_argument("--algo", choices=["momentum", "gradient", "topk"], default="momentum",
+                    help="momentum: APMSqueeze with the 1-bit compressor (the benchmark); gradient: the APGSqueeze "
+                         "variant of Section 5.3; topk: APMSqueeze with the top-k compressor of Section 5.1 (eager)")
+    ap.add_argument("--topk-percent", type=float, default=1.0, help="kept fraction of every chunk, in percent")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient input (f32 is the benchmark's configuration)")
     ap.add_argument("--occupancy-pad", default="", help="e.g. compress=65536,apply=0 (apms_set_occupancy_pad)")
@@ -139,6 +141,14 @@ def main():
     for item in filter(None, args.occupancy_pad.split(",")):
         name, val = item.split("=")
         B.apms_set_occupancy_pad(run.ctx, kernel_ids[name], int(val))
+    topk_K = max(1, int(L * args.topk_percent / 100.0))
+    if args.algo == "topk":
+        if deferral or args.grad_dtype != "f32":
+            sys.exit("bench.py: --algo topk is eager and fp32 only (use --mode eager)")
+        i32 = dict(dtype=torch.int32, device=dev)
+        f32 = dict(dtype=torch.float32, device=dev)
+        run.idx, run.val = torch.zeros(n, wl.C, topk_K, **i32), torch.zeros(n, wl.C, topk_K, **f32)
+        run.sidx, run.sval = torch.zeros(wl.C, topk_K, **i32), torch.zeros(wl.C, topk_K, **f32)
     plan = B.apms_get_plan(run.ctx)
     g32 = torch.empty(n, d, dtype=torch.float32, device=dev)
     gdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.grad_dtype]
@@ -158,14 +168,21 @@ def main():
             events[0].record(stream)
         if args.algo == "gradient":
             B.apms_compress_gradient(run.ctx, g, run._grad_format(g), run.werr, run.packed, run.scales)
+        elif args.algo == "topk":
+            B.apms_topk_compress(run.ctx, run.m, g, run.werr, run.idx, run.val, topk_K, wl.beta)
         else:
             run.compress(g, wl.beta)
         if events is not None:
             events[1].record(stream)
-        run.server_reduce()
+        if args.algo == "topk":
+            B.apms_topk_server_reduce(run.ctx, run.idx, run.val, topk_K, run.serr, run.sidx, run.sval)
+        else:
+            run.server_reduce()
         if events is not None:
             events[2].record(stream)
-        if args.algo == "gradient":
+        if args.algo == "topk":
+            B.apms_topk_apply(run.ctx, run.sidx, run.sval, topk_K, run.v, run.x, run.m, wl.lr, wl.eps)
+        elif args.algo == "gradient":
             B.apms_apply_gradient(run.ctx, run.spacked, run.sscales, run.v, run.x, run.m, wl.lr, wl.beta, wl.eps)
         else:
             run.apply(wl.lr, wl.eps)
@@ -220,6 +237,13 @@ def main():
     ab["compress"] -= (4 - gbytes) * n             # 16-bit gradients: 2n fewer bytes read
     if deferral & B.APMS_IMPLICIT_MOMENTUM:
         ab["compress"] -= 4.0 * n                  # m is not written
+    if args.algo == "topk":
+        # as implemented: worker = u pass (read m, g, delta; write u) + 2 histogram passes + count + emit
+        # passes over u, plus the lists; server the same on one vector; gather = dense m to n slices + model
+        kf = topk_K / L
+        ab["compress"] = (16.0 + 16.0 + 8.0 * kf) * n
+        ab["server_reduce"] = 8.0 * kf * n + 8.0 + 16.0 + 8.0 * kf
+        ab["apply"] = 4.0 * n + 12.0 + 8.0 * kf
     if args.algo == "gradient":
         # worker: read g, delta; write delta, n/8 signs.  apply: read + write m per worker, n/8 signs, v, x, x
         ab["compress"] = (8.0 + gbytes) * n + n / 8.0
@@ -238,7 +262,7 @@ def main():
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {
             "workload": "%s: d_pad=%d n=%d chunk=%d" % (wl.name, d, n, L),
-            "algo": args.algo, "mode": args.mode, "grad_dtype": args.grad_dtype, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
+            "algo": args.algo, "topk_K_per_chunk": topk_K if args.algo == "topk" else None, "mode": args.mode, "grad_dtype": args.grad_dtype, "gradients": wl.grad + (", reused" if args.reuse_grad else ", fresh each step"),
             "worker_params_per_s": value * n,
             "bytes_per_param_step": sum(ab.values()),
             "step_GBps": step_bytes / (ms_per_step * 1e-3) / 1e9,

@@ -133,3 +133,38 @@ def test_topk_refused_while_onebit_state_is_pending():
     run.step_topk(g, K, 0.9, 1e-4, 1e-8)
     torch.cuda.synchronize()
     run.close()
+
+
+def test_topk_full_size_sampled_chunk():
+    """BERT-Base-sized buffer (d_pad = 110 002 176, n = 8, chunk = d_pad / 8), K = 0.1 % of the chunk: the GPU
+    runs the whole step, the oracle follows the last chunk (chunks are independent) on the same bits."""
+    wl = W.BERT_BASE
+    d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    K = L // 1000
+    st = W.device_state(wl, DEV)
+    run = DeviceRun(d, n, L, DEV, state=st)
+    del st
+    k = C - 1
+    sl = slice(k * L, (k + 1) * L)
+    ost = oracle.State(L, n, L, run.x[sl].cpu().numpy(), run.m[:, sl].cpu().numpy(), run.v[sl].cpu().numpy())
+    g = torch.empty(n, d, dtype=torch.float32, device=DEV)
+    W.device_grad_(wl, 0, g)
+    say("full size: GPU step, d=%d n=%d L=%d K=%d" % (d, n, L, K))
+    run.step_topk(g, K, wl.beta, wl.lr, wl.eps)
+    torch.cuda.synchronize()
+    say("full size: oracle on chunk %d (sorts %d x %d elements)" % (k, n + 1, L))
+    ost.step_topk(np.ascontiguousarray(g[:, sl].cpu().numpy()), K, wl.beta, wl.lr, wl.eps)
+    same(host(run.idx[:, k]), ost.idx[:, 0], "worker indices")
+    same(host(run.val[:, k]), ost.val[:, 0], "worker values")
+    same(host(run.sidx[k]), ost.sidx[0], "server indices")
+    same(host(run.sval[k]), ost.sval[0], "server values")
+    same(host(run.serr[sl]), ost.serr, "server_err")
+    for i in (0, n - 1):
+        same(host(run.werr[i, sl]), ost.werr[i], "worker_err[%d]" % i)
+        same(host(run.m[i, sl]), ost.m[i], "momentum[%d]" % i)
+    np.testing.assert_allclose(host(run.x[sl]), ost.x, rtol=1e-5, atol=1e-7)
+    # whole buffer: every chunk's lists are strictly ascending and inside the chunk
+    idx = run.idx.to(torch.int64)
+    assert bool((idx[..., 1:] > idx[..., :-1]).all()) and int(idx.max()) < L and int(idx.min()) >= 0
+    assert int((run.m[0] != 0).sum()) <= C * K
+    run.close()
