@@ -86,15 +86,39 @@ __device__ __forceinline__ uint32_t block_exclusive_scan_u32(uint32_t v, uint32_
     return before + inc - v;
 }
 
+// The same for one uint64 per thread (used to scan four 16-bit counters at once).
+__device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t v, uint64_t* lds /* kWaves */, uint64_t& total) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    uint64_t inc = v;
+#pragma unroll
+    for (int off = 1; off < kWaveSize; off <<= 1) {
+        const uint64_t up = static_cast<uint64_t>(__shfl_up(static_cast<unsigned long long>(inc), off));
+        if (lane >= off) inc += up;
+    }
+    if (lane == kWaveSize - 1) lds[wave] = inc;
+    __syncthreads();
+    uint64_t before = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const uint64_t t = lds[w];
+        if (w < wave) before += t;
+        sum += t;
+    }
+    __syncthreads();
+    total = sum;
+    return before + inc - v;
+}
+
 // Decomposition of blockIdx into (pair, tile) for kernels that take one kTopkTile tile per workgroup.
 struct TileRef {
     int64_t pair;        // slice * C + chunk
     int64_t tile;
     int64_t base;        // element offset of the chunk inside the [slices][d] buffer
 };
-__device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk) {
+__device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk,
+                                            int64_t blk = blockIdx.x) {
     TileRef r;
-    const int64_t blk = blockIdx.x;
     r.pair = blk / tiles_per_chunk;
     r.tile = blk - r.pair * tiles_per_chunk;
     const int64_t slice = r.pair / C;
@@ -279,31 +303,17 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
     }
 }
 
-// One pass over the buffer: histogram of the next radix digit of the elements inside the current prefix.
+// Histogram of the next radix digit of the elements of one tile that lie inside the current prefix.
 template <bool kIdx>
-__global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
-                                                             const uint32_t* __restrict__ state, int64_t d, int64_t L,
-                                                             int32_t C, int32_t tiles_per_chunk, int level) {
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
-    const uint32_t* st = state + tr.pair * kTopkStateWords;
-    if (kIdx && st[kStTieNeeded] == 0u) return;
-    const Level lv = kIdx ? idx_level(level) : key_level(level);
-    const uint32_t prefix = level == 0 ? 0u : (kIdx ? st[kStIdxPrefix] : st[kStPrefix]);
-    const uint32_t T = st[kStKeyT];
-    const int64_t tile_lo = tr.tile * kTopkTile;
-    if (kIdx && level > 0) {
-        // only tiles that intersect the index range of the current prefix can contribute
-        const int64_t span = int64_t{1} << idx_level(level - 1).shift;
-        if (tile_lo + kTopkTile <= static_cast<int64_t>(prefix) || tile_lo >= static_cast<int64_t>(prefix) + span) return;
-    }
-    uint32_t* h = hist + tr.pair * kTopkBins;
+__device__ __forceinline__ void hist_tile(const float* __restrict__ buf, uint32_t* __restrict__ h, int64_t base,
+                                          int64_t tile_lo, int64_t L, Level lv, uint32_t prefix, uint32_t T) {
     const uint32_t digit_mask = (1u << lv.bits) - 1u;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int64_t off = tile_lo + threadIdx.x * 4 + r * kRowStride;
-        const bool valid = off < L;                            // uniform per wave-row only by accident: no branch
+        const bool valid = off < L;                            // no branch: every lane takes part in the ballots
         f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (valid) v = load_stream(buf + tr.base + off);
+        if (valid) v = load_stream(buf + base + off);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const uint32_t key = key_of(v[c]);
@@ -319,6 +329,42 @@ __global__ __launch_bounds__(kThreads) void topk_hist_kernel(const float* __rest
             }
             hist_add_aggregated(h, active, bin);
         }
+    }
+}
+
+// Key levels 1 and 2: one pass over the buffer, one tile per workgroup.
+__global__ __launch_bounds__(kThreads) void topk_key_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
+                                                                 const uint32_t* __restrict__ state, int64_t d, int64_t L,
+                                                                 int32_t C, int32_t tiles_per_chunk, int level) {
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const uint32_t* st = state + tr.pair * kTopkStateWords;
+    hist_tile<false>(buf, hist + tr.pair * kTopkBins, tr.base, tr.tile * kTopkTile, L, key_level(level), st[kStPrefix], 0u);
+}
+
+// Index (tie) levels usually have nothing to do, so they run on a small grid: every workgroup walks the
+// pairs, skips those without a tie to break with one state read, and strides over the tiles of the others,
+// skipping tiles outside the index range of the current prefix.
+__global__ __launch_bounds__(kThreads) void topk_tie_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
+                                                                 const uint32_t* __restrict__ state, int64_t d, int64_t L,
+                                                                 int32_t C, int64_t pairs, int32_t tiles_per_chunk,
+                                                                 int level) {
+    const Level lv = idx_level(level);
+    for (int64_t pair = 0; pair < pairs; ++pair) {
+        const uint32_t* st = state + pair * kTopkStateWords;
+        if (st[kStTieNeeded] == 0u) continue;
+        const uint32_t prefix = level == 0 ? 0u : st[kStIdxPrefix];
+        const uint32_t T = st[kStKeyT];
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        // tiles that intersect the index range [prefix, prefix + span) of the current prefix
+        int64_t first = 0, last = tiles_per_chunk;
+        if (level > 0) {
+            const int64_t span = int64_t{1} << idx_level(level - 1).shift;
+            first = static_cast<int64_t>(prefix) / kTopkTile;
+            last = min(static_cast<int64_t>(tiles_per_chunk), (static_cast<int64_t>(prefix) + span + kTopkTile - 1) / kTopkTile);
+        }
+        for (int64_t tile = first + blockIdx.x; tile < last; tile += gridDim.x)
+            hist_tile<true>(buf, hist + pair * kTopkBins, base, tile * kTopkTile, L, lv, prefix, T);
     }
 }
 
@@ -363,45 +409,61 @@ __global__ __launch_bounds__(kThreads) void topk_scan_kernel(uint32_t* __restric
 }
 
 // Writes the kept elements of a tile to the pair's (idx, val) list at the tile's offset, in index order,
-// and zeroes them in the buffer: what stays there is u - C[u].
+// and zeroes them in the buffer: what stays there is u - C[u].  Index order inside a tile is row by row
+// (plain layout), thread by thread inside a row: one workgroup scan of the four per-row counts, packed as
+// four 16-bit fields of a uint64, gives every thread its rank in each row.
 __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ buf, const uint32_t* __restrict__ state,
                                                              const uint32_t* __restrict__ tile_offsets,
                                                              uint32_t* __restrict__ idx, float* __restrict__ val,
                                                              int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk,
                                                              int64_t K) {
-    __shared__ uint32_t lds[kWaves];
+    static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
+    __shared__ uint64_t lds[kWaves];
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
     const uint32_t* st = state + tr.pair * kTopkStateWords;
     const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
     uint32_t* out_idx = idx + tr.pair * K;
     float* out_val = val + tr.pair * K;
-    uint32_t row_base = tile_offsets[tr.pair * tiles_per_chunk + tr.tile];
-    for (int r = 0; r < kTileRows; ++r) {                      // rows are consecutive index ranges
+    const uint32_t tile_base = tile_offsets[tr.pair * tiles_per_chunk + tr.tile];
+    f32x4 v[kTileRows];
+    uint32_t keep_mask = 0;                                    // bit 4*r + c: element c of row r is kept
+    uint64_t packed = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
         const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
-        const bool valid = off < L;
-        f32x4 v = {0.0f, 0.0f, 0.0f, 0.0f};
-        if (valid) v = load_stream(buf + tr.base + off);
-        bool keep[4];
-        uint32_t mine = 0;
+        v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (off < L) {
+            v[r] = load_stream(buf + tr.base + off);
+            uint32_t count = 0;
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            keep[c] = valid && kept(key_of(v[c]), static_cast<uint32_t>(off + c), T, idxT);
-            mine += keep[c] ? 1u : 0u;
+            for (int c = 0; c < 4; ++c) {
+                if (kept(key_of(v[r][c]), static_cast<uint32_t>(off + c), T, idxT)) {
+                    keep_mask |= 1u << (4 * r + c);
+                    ++count;
+                }
+            }
+            packed |= static_cast<uint64_t>(count) << (16 * r);
         }
-        uint32_t total;
-        uint32_t rank = row_base + block_exclusive_scan_u32(mine, lds, total);   // all threads take part
+    }
+    uint64_t totals;
+    const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);
+    uint32_t row_base = tile_base;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+        uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            if (keep[c]) {
+            if (keep_mask & (1u << (4 * r + c))) {
                 if (rank < K) {                                // holds by construction; guards the list bounds
                     out_idx[rank] = static_cast<uint32_t>(off + c);
-                    out_val[rank] = v[c];
+                    out_val[rank] = v[r][c];
                 }
                 buf[tr.base + off + c] = 0.0f;
                 ++rank;
             }
         }
-        row_base += total;
+        row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
     }
 }
 
@@ -475,9 +537,10 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
     const uint32_t K32 = static_cast<uint32_t>(K);
+    const dim3 tie_grid(static_cast<uint32_t>(tpc < 4096 ? tpc : 4096));
     for (int level = 0; level < 3; ++level) {
         if (level > 0) {
-            hipLaunchKernelGGL(topk_hist_kernel<false>, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
+            hipLaunchKernelGGL(topk_key_hist_kernel, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
                                geo.C, tpc, level);
             APMS_RETURN_IF_ERROR();
         }
@@ -485,8 +548,8 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
         APMS_RETURN_IF_ERROR();
     }
     for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
-        hipLaunchKernelGGL(topk_hist_kernel<true>, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
-                           geo.C, tpc, level);
+        hipLaunchKernelGGL(topk_tie_hist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
+                           geo.C, pairs, tpc, level);
         APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
         APMS_RETURN_IF_ERROR();
