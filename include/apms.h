@@ -97,8 +97,9 @@ typedef struct apms_plan {
 /*
  * Create a context for vectors of d elements, n workers and chunks of
  * chunk_elems elements on HIP device `device` (or APMS_DEVICE_NONE).  The
- * context owns a few MB of device scratch (binary64 norm partials, pending
- * scales).  Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
+ * context owns its device scratch (binary64 norm partials, pending scales, the
+ * top-k selection's histograms and tile counts: a few MB to a few tens of MB,
+ * see apms_plan.scratch_bytes).  Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
  */
 int apms_create(apms_ctx **out, int64_t d, int32_t n, int64_t chunk_elems, int device);
 

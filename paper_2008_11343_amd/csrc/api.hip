@@ -159,7 +159,7 @@ const char* apms_strerror(int status) {
         case APMS_EHIP: return "a HIP call failed (see apms_last_hip_error)";
         case APMS_ENODEV: return "validation-only context: no device to run on";
         case APMS_EALIAS: return "array arguments overlap";
-        case APMS_ESTATE: return "another error buffer is pending in deferred form; finalize it first";
+        case APMS_ESTATE: return "the call would lose or read state that is pending in deferred form; call apms_finalize first";
         default: return "unknown apms status";
     }
 }
@@ -305,23 +305,6 @@ int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, v
         c->pending_spacked = nullptr;
     }
     return APMS_OK;
-}
-
-int apms_apply_gradient(apms_ctx* c, const uint32_t* spacked, const float* sscales, const float* v, float* x,
-                        float* m, float lr, float beta, float eps, void* stream) {
-    if (!c) return APMS_EINVAL;
-    const int64_t vec = c->d * 4;
-    const Range r[] = {{spacked, vec / 32}, {sscales, c->C * 4}, {v, vec}, {x, vec}, {m, vec * c->n}};
-    if (int rc = check_arrays(r, 5)) return rc;
-    if (!(lr == lr) || !(eps == eps) || !unit_interval(beta)) return APMS_EINVAL;
-    if (c->pending_m && c->pending_m == m) return APMS_ESTATE;   // m is read here and is not final yet
-    int status;
-    if (!ready_to_launch(c, &status)) return status;
-    DeviceScope scope(c->device);
-    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = apms::launch_apply_gradient(geometry(c), spacked, sscales, v, x, m, lr, beta, 1.0f - beta, eps,
-                                               c->lds_pad[APMS_KERNEL_APPLY], static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
 }  // extern "C"
@@ -511,6 +494,23 @@ int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const
     c->pending_m = defer ? m : nullptr;
     c->pending_spacked = defer ? spacked : nullptr;
     return APMS_OK;
+}
+
+int apms_apply_gradient(apms_ctx* c, const uint32_t* spacked, const float* sscales, const float* v, float* x,
+                        float* m, float lr, float beta, float eps, void* stream) {
+    if (!c) return APMS_EINVAL;
+    const int64_t vec = c->d * 4;
+    const Range r[] = {{spacked, vec / 32}, {sscales, c->C * 4}, {v, vec}, {x, vec}, {m, vec * c->n}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (!(lr == lr) || !(eps == eps) || !unit_interval(beta)) return APMS_EINVAL;
+    if (c->pending_m && c->pending_m == m) return APMS_ESTATE;   // m is read here and is not final yet
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    hipError_t e = apms::launch_apply_gradient(geometry(c), spacked, sscales, v, x, m, lr, beta, 1.0f - beta, eps,
+                                               c->lds_pad[APMS_KERNEL_APPLY], static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
 // ---- top-k compressor (Section 5.1, second bullet): eager only -------------------------------------

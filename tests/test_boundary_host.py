@@ -264,3 +264,12 @@ def test_workload_recipes():
     st = W.host_state(W.scaled(W.TINY, 5000, chunk=4096))
     assert st["x"].shape == (8192,) and (st["x"][5000:] == 0).all() and (st["v"][5000:] == 1).all()
     assert (st["m"][:, 5000:] == 0).all() and not st["werr"].any() and not st["serr"].any()
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """The benchmark is a one-GPU program: --gpus N with N > 1 exits with a message that says so."""
+    import subprocess
+    import sys
+    out = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert out.returncode != 0 and "ONE GPU" in out.stderr and out.stdout.strip() == ""
