@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, each scaled by what the counter reads for a plain copy of known size); the summary
 # with the commands is profiles/bench_bert-large-flat_hbm_traffic.txt.  Reported only for the workload
 # and error mode it was measured on.
-MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 88.445e9, ("bert-large-flat", "deferred-errors"): 87.763e9}
+MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 88.513e9, ("bert-large-flat", "deferred-errors"): 87.762e9}
 
 METRIC = "compressed-momentum step params/sec & HBM GB/s (% of peak), BERT-Large d, 1 GPU"
 
@@ -281,7 +281,11 @@ def main():
             "device": torch.cuda.get_device_name(0),
         },
         "roofline": {
-            "kernel": "compress_kernel<%s> (apms_compress)" % ("true" if deferral & B.APMS_DEFER_GATHER else "false"),
+            "kernel": ("apms_topk_compress (all passes of the worker selection)" if args.algo == "topk" else
+                       "compress_kernel<momentum: %s, gradient: %s> (apms_compress%s)" % (
+                           "none" if args.algo == "gradient" else
+                           "pending gather" if deferral & B.APMS_DEFER_GATHER else "read m",
+                           args.grad_dtype, "_gradient" if args.algo == "gradient" else "")),
             "bound": "hbm", "achieved": achieved,
             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": MEASURED_COMPRESS_TRAFFIC.get((wl.name, args.mode)) if (args.grad_dtype == "f32" and args.algo == "momentum") else None,
