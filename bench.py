@@ -137,7 +137,7 @@ def main():
     if args.compress_tiles or args.server_tiles:
         B.apms_set_tiles_per_block(run.ctx, args.compress_tiles, args.server_tiles)
     kernel_ids = {"compress": B.APMS_KERNEL_COMPRESS, "server": B.APMS_KERNEL_SERVER,
-                  "apply": B.APMS_KERNEL_APPLY, "finalize": B.APMS_KERNEL_FINALIZE}
+                  "apply": B.APMS_KERNEL_APPLY, "finalize": B.APMS_KERNEL_FINALIZE, "warmup": B.APMS_KERNEL_WARMUP}
     for item in filter(None, args.occupancy_pad.split(",")):
         name, val = item.split("=")
         B.apms_set_occupancy_pad(run.ctx, kernel_ids[name], int(val))
@@ -250,6 +250,7 @@ def main():
         ab["apply"] = 8.125 * n + 12.0
     spec_bytes = sum(call_bytes(n).values())       # the workload's own accounting (eager gather)
     mean = lambda xs: sum(xs) / len(xs)
+    median = lambda xs: sorted(xs)[len(xs) // 2] if len(xs) % 2 else 0.5 * sum(sorted(xs)[len(xs) // 2 - 1:len(xs) // 2 + 1])
     step_bytes = d * sum(ab.values())
     compress_ms = mean(t_c)
     achieved = d * ab["compress"] / (compress_ms * 1e-3) / 1e9
@@ -271,6 +272,7 @@ def main():
             "step_GBps_eager_accounting": d * spec_bytes / (ms_per_step * 1e-3) / 1e9,
             "ms": {"compress": compress_ms, "server_reduce": mean(t_s), "apply": mean(t_a),
                    "final_finalize_total": t_fin},
+            "ms_per_step_median": median([a + b + c for a, b, c in zip(t_c, t_s, t_a)]),
             "GBps": {"compress": achieved,
                      "server_reduce": d * ab["server_reduce"] / (mean(t_s) * 1e-3) / 1e9,
                      "apply": d * ab["apply"] / (mean(t_a) * 1e-3) / 1e9},

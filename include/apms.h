@@ -91,7 +91,8 @@ typedef struct apms_plan {
     int32_t apply_tile_elems;
     int64_t apply_grid;                 /* n * C * ceil(chunk_elems / apply_tile_elems) */
     int64_t scratch_bytes;              /* device memory owned by the context */
-    int32_t occupancy_pad[4];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_* */
+    int32_t occupancy_pad[8];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_*;
+                                           entries past APMS_KERNEL_COUNT are 0 */
 } apms_plan;
 
 /*
@@ -133,6 +134,8 @@ int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t serv
 #define APMS_KERNEL_SERVER 1
 #define APMS_KERNEL_APPLY 2
 #define APMS_KERNEL_FINALIZE 3
+#define APMS_KERNEL_WARMUP 4
+#define APMS_KERNEL_COUNT 5
 int apms_set_occupancy_pad(apms_ctx *ctx, int kernel, int32_t lds_bytes);
 
 /*

@@ -23,7 +23,8 @@ APMS_GRAD_BF16 = 2
 APMS_DEFER_ERRORS = 1
 APMS_DEFER_GATHER = 2
 APMS_IMPLICIT_MOMENTUM = 4
-APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE = 0, 1, 2, 3
+APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE, APMS_KERNEL_WARMUP = 0, 1, 2, 3, 4
+APMS_KERNEL_COUNT = 5
 
 EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
@@ -43,12 +44,12 @@ class apms_plan(ctypes.Structure):
         ("server_tile_elems", ctypes.c_int32), ("server_tiles_per_block", ctypes.c_int32),
         ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
         ("apply_tile_elems", ctypes.c_int32), ("apply_grid", ctypes.c_int64),
-        ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 4),
+        ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 8),
     ]
 
     def as_dict(self):
         out = {name: getattr(self, name) for name, _ in self._fields_}
-        out["occupancy_pad"] = list(self.occupancy_pad)
+        out["occupancy_pad"] = list(self.occupancy_pad)[:APMS_KERNEL_COUNT]
         return out
 
 

@@ -22,7 +22,7 @@ struct apms_ctx {
     int32_t w_tiles_per_chunk = 0, w_tiles_per_block = 0, w_blocks_per_chunk = 0;    // apms_compress
     int32_t s_tiles_per_chunk = 0, s_tiles_per_block = 0, s_blocks_per_chunk = 0;    // apms_server_reduce
     int32_t a_tiles_per_chunk = 0;                                                   // apms_apply
-    int32_t lds_pad[4] = {0, 0, 0, 0};          // per APMS_KERNEL_*: unused dynamic LDS that caps occupancy
+    int32_t lds_pad[APMS_KERNEL_COUNT] = {};    // per APMS_KERNEL_*: unused dynamic LDS that caps occupancy
     // device scratch (owned)
     double* w_partials = nullptr;     // [n*C][w_tiles_per_chunk] (sized for 1 tile per block)
     double* s_partials = nullptr;     // [C][s_tiles_per_chunk]
@@ -47,10 +47,10 @@ namespace {
 constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
-// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize).  Measured on MI355X:
-// the worker kernel streams fastest with 2 workgroups (8 waves) per CU, the small-tile kernels with as
-// many as fit.
-constexpr int32_t kDefaultLdsPad[4] = {64 * 1024, 0, 0, 0};
+// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize, warm-up).  Measured on MI355X:
+// the worker kernel and the warm-up kernel (n + 3 read streams) stream fastest with 2 workgroups (8 waves)
+// per CU, the small-tile kernels with as many as fit.
+constexpr int32_t kDefaultLdsPad[APMS_KERNEL_COUNT] = {64 * 1024, 0, 0, 0, 64 * 1024};
 
 struct Range {
     const void* p;
@@ -188,7 +188,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     c->w_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kCompressTile));
     c->s_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kServerTile));
     c->a_tiles_per_chunk = static_cast<int32_t>(apms::tiles_per_chunk(geo, apms::kApplyTile));
-    for (int k = 0; k < 4; ++k) c->lds_pad[k] = kDefaultLdsPad[k];
+    for (int k = 0; k < APMS_KERNEL_COUNT; ++k) c->lds_pad[k] = kDefaultLdsPad[k];
     c->w_tiles_per_block = kDefaultCompressTiles;
     c->s_tiles_per_block = kDefaultServerTiles;
     plan_blocks(c);
@@ -251,7 +251,7 @@ int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
     plan->apply_tile_elems = apms::kApplyTile;
     plan->apply_grid = c->C * c->a_tiles_per_chunk * c->n;
     plan->scratch_bytes = c->scratch_bytes;
-    for (int k = 0; k < 4; ++k) plan->occupancy_pad[k] = c->lds_pad[k];
+    for (int k = 0; k < 8; ++k) plan->occupancy_pad[k] = k < APMS_KERNEL_COUNT ? c->lds_pad[k] : 0;
     return APMS_OK;
 }
 
@@ -264,7 +264,7 @@ int apms_set_tiles_per_block(apms_ctx* c, int32_t compress_tiles, int32_t server
 }
 
 int apms_set_occupancy_pad(apms_ctx* c, int kernel, int32_t lds_bytes) {
-    if (!c || kernel < 0 || kernel > 3 || lds_bytes < 0 || lds_bytes > apms::kMaxLdsPad) return APMS_EINVAL;
+    if (!c || kernel < 0 || kernel >= APMS_KERNEL_COUNT || lds_bytes < 0 || lds_bytes > apms::kMaxLdsPad) return APMS_EINVAL;
     c->lds_pad[kernel] = lds_bytes;
     return APMS_OK;
 }
@@ -339,7 +339,8 @@ int warmup_impl(apms_ctx* c, float* x, float* m, float* v, const void* g, int gr
     const float bc2 = static_cast<float>(1.0 - std::pow(static_cast<double>(beta2), static_cast<double>(t)));
     const float inv_n = 1.0f / static_cast<float>(c->n);
     hipError_t e = apms::launch_warmup(c->d, c->n, x, m, v, g, grad_format, lr, beta1, 1.0f - beta1, beta2,
-                                       1.0f - beta2, bc1, bc2, eps, inv_n, static_cast<hipStream_t>(stream));
+                                       1.0f - beta2, bc1, bc2, eps, inv_n, c->lds_pad[APMS_KERNEL_WARMUP],
+                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 

@@ -91,7 +91,7 @@ hipError_t launch_apply_gradient(const Geometry& geo, const uint32_t* spacked, c
 // Adam warm-up step on the averaged gradient (g in grad_format).
 hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const void* g, int grad_format, float lr,
                          float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
-                         float bc2, float eps, float inv_n, hipStream_t stream);
+                         float bc2, float eps, float inv_n, int32_t lds_pad, hipStream_t stream);
 
 // m[i] <- m[0] for i >= 1; werr, serr <- 0.
 hipError_t launch_freeze(int64_t d, int32_t n, float* m, float* werr, float* serr, hipStream_t stream);

@@ -561,7 +561,10 @@ hipError_t enable_large_lds_pads() {
                              reinterpret_cast<const void*>(apply_kernel<false, true>),
                              reinterpret_cast<const void*>(apply_kernel<true, false>),
                              reinterpret_cast<const void*>(apply_gradient_kernel),
-                             reinterpret_cast<const void*>(finalize_kernel)};
+                             reinterpret_cast<const void*>(finalize_kernel),
+                             reinterpret_cast<const void*>(warmup_kernel<kGradF32>),
+                             reinterpret_cast<const void*>(warmup_kernel<kGradF16>),
+                             reinterpret_cast<const void*>(warmup_kernel<kGradBF16>)};
     for (const void* k : kernels) {
         e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
         if (e != hipSuccess) return e;
@@ -660,20 +663,20 @@ hipError_t launch_apply_gradient(const Geometry& geo, const uint32_t* spacked, c
 
 hipError_t launch_warmup(int64_t d, int32_t n, float* x, float* m, float* v, const void* g, int grad_format, float lr,
                          float beta1, float one_minus_beta1, float beta2, float one_minus_beta2, float bc1,
-                         float bc2, float eps, float inv_n, hipStream_t stream) {
+                         float bc2, float eps, float inv_n, int32_t lds_pad, hipStream_t stream) {
     if (d <= 0) return hipSuccess;
     const dim3 grid(static_cast<uint32_t>(((d >> 2) + kThreads - 1) / kThreads)), block(kThreads);
     switch (grad_format) {
         case kGradF32:
-            hipLaunchKernelGGL(warmup_kernel<kGradF32>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+            hipLaunchKernelGGL(warmup_kernel<kGradF32>, grid, block, lds_pad, stream, x, m, v, g, d, n, lr, beta1,
                                one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
             break;
         case kGradF16:
-            hipLaunchKernelGGL(warmup_kernel<kGradF16>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+            hipLaunchKernelGGL(warmup_kernel<kGradF16>, grid, block, lds_pad, stream, x, m, v, g, d, n, lr, beta1,
                                one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
             break;
         case kGradBF16:
-            hipLaunchKernelGGL(warmup_kernel<kGradBF16>, grid, block, 0, stream, x, m, v, g, d, n, lr, beta1,
+            hipLaunchKernelGGL(warmup_kernel<kGradBF16>, grid, block, lds_pad, stream, x, m, v, g, d, n, lr, beta1,
                                one_minus_beta1, beta2, one_minus_beta2, bc1, bc2, eps, inv_n);
             break;
         default: return hipErrorInvalidValue;

@@ -129,7 +129,8 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_set_deferral, ctx, B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM) == B.APMS_OK
     assert status_of(B.apms_set_deferral, ctx, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER) == B.APMS_OK
     assert status_of(B.apms_set_tiles_per_block, ctx, -1, 0) == B.APMS_EINVAL
-    assert status_of(B.apms_set_occupancy_pad, ctx, 4, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_COUNT, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_WARMUP, 32768) == B.APMS_OK
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 200 * 1024) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 4096) == B.APMS_OK
     assert B.apms_get_plan(ctx)["occupancy_pad"][B.APMS_KERNEL_APPLY] == 4096
