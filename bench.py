@@ -81,7 +81,7 @@ def cpu_baseline(wl, run, g, sample_elems, steps):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="bert-large-flat")
     ap.add_argument("--mode", choices=["deferred", "deferred-errors", "eager", "implicit"], default="deferred",

@@ -68,6 +68,13 @@ __device__ __forceinline__ float signed_scale(bool positive, float s) {
     return positive ? s : -s;
 }
 
+// |s| with the sign bit taken from the top bit of t (set = negative): two VALU operations per decoded
+// element (shift + bit-field insert) where compare + select + mask take three.  s is a chunk scale, a
+// square root, hence never negative, so this equals signed_scale(!(t >> 31), s).
+__device__ __forceinline__ float scale_signed_by_msb(uint32_t t, float s) {
+    return __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, s) & 0x7fffffffu) | (t & 0x80000000u));
+}
+
 // Sign nibble of four elements: bit c = (u[c] >= 0), so -0.0 and +0.0 give 1.
 __device__ __forceinline__ uint32_t sign_nibble(f32x4 u) {
     return (u.x >= 0.0f ? 1u : 0u) | (u.y >= 0.0f ? 2u : 0u) |

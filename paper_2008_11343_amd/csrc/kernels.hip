@@ -231,19 +231,26 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
         if (ok[r]) ve[r] = load_stream(serr + chunk_base + off0 + 32 * r);
         sum[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-#pragma unroll 4
+    // eight workers' sign words in flight per lane; a full tile takes its group's ROWS = 4 consecutive
+    // words as one 128-bit load (w0 is a multiple of 4: chunks and tiles are multiples of 4096 elements)
+#pragma unroll 8
     for (int32_t i = 0; i < n; ++i) {
         const float s = scales[static_cast<int64_t>(i) * C + chunk];
         const uint32_t* wp = packed + i * words_per_worker + w0;
         uint32_t w[ROWS];
+        if constexpr (kFull && ROWS == 4) {
+            const u32x4 wq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wp));
+            w[0] = wq.x, w[1] = wq.y, w[2] = wq.z, w[3] = wq.w;
+        } else {
 #pragma unroll
-        for (int r = 0; r < ROWS; ++r) w[r] = ok[r] ? wp[r] : 0u;
+            for (int r = 0; r < ROWS; ++r) w[r] = ok[r] ? wp[r] : 0u;
+        }
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            const uint32_t nib = w[r] >> shift;
+            const uint32_t clear = ~(w[r] >> shift);      // bit c set = element c is negative
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                sum[r][c] = sum[r][c] + signed_scale((nib >> c) & 1u, s);
+                sum[r][c] = sum[r][c] + scale_signed_by_msb(clear << (31 - c), s);
         }
     }
     uint32_t words[ROWS];
