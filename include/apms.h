@@ -93,14 +93,15 @@ typedef struct apms_plan {
     int64_t scratch_bytes;              /* device memory owned by the context */
     int32_t occupancy_pad[8];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_*;
                                            entries past APMS_KERNEL_COUNT are 0 */
+    int64_t topk_scratch_bytes;         /* further device memory the apms_topk_* calls have allocated */
 } apms_plan;
 
 /*
  * Create a context for vectors of d elements, n workers and chunks of
  * chunk_elems elements on HIP device `device` (or APMS_DEVICE_NONE).  The
- * context owns its device scratch (binary64 norm partials, pending scales, the
- * top-k selection's histograms and tile counts: a few MB to a few tens of MB,
- * see apms_plan.scratch_bytes).  Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
+ * context owns its device scratch (binary64 norm partials, pending scales: a few MB,
+ * see apms_plan.scratch_bytes; the top-k calls add theirs on first use, see below).
+ * Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
  */
 int apms_create(apms_ctx **out, int64_t d, int32_t n, int64_t chunk_elems, int device);
 
@@ -289,6 +290,11 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
  * K (index, value) pairs, indices local to the chunk and ascending; the selection is exact.
  * These calls are eager (no deferral) and return ESTATE while the 1-bit path has a buffer pending;
  * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31.
+ * The first of them on a context allocates the selection's scratch: histograms, per-tile counts and, per
+ * 4096-element tile, 64 to 512 slots of 8 bytes for the elements near or above the threshold (256 slots,
+ * n*d/2 bytes in all, when K is 1 % of chunk_elems).  That synchronises the device; ENOMEM if it fails.
+ * Later calls allocate nothing unless K has grown enough to ask for more slots per tile, in which case the
+ * slots are allocated again.  apms_plan.topk_scratch_bytes is what is allocated at the moment.
  *
  * apms_topk_compress:       u = (fl(beta*m_i) + fl(fl(1-beta)*g_i)) + delta_i ;  (idx, val) <- C[u] ;
  *                           delta_i <- u - C[u]  (zero where kept, u elsewhere)

@@ -44,7 +44,7 @@ class apms_plan(ctypes.Structure):
         ("server_tile_elems", ctypes.c_int32), ("server_tiles_per_block", ctypes.c_int32),
         ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
         ("apply_tile_elems", ctypes.c_int32), ("apply_grid", ctypes.c_int64),
-        ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 8),
+        ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 8), ("topk_scratch_bytes", ctypes.c_int64),
     ]
 
     def as_dict(self):

@@ -29,7 +29,9 @@ struct apms_ctx {
     float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
     float* s_pending = nullptr;       // [C]   same for the server error buffer
     float* g_pending = nullptr;       // [C]   server scales of a gather that has not been carried out yet
-    apms::TopkScratch topk = {nullptr, nullptr, nullptr};   // selection scratch of the top-k compressor
+    apms::TopkScratch topk = {};                // selection scratch of the top-k compressor, allocated by the
+                                                // first apms_topk_* call
+    int64_t topk_bytes = 0;                     // its size so far
     int64_t scratch_bytes = 0;
     // deferral bookkeeping (host side, follows call order = stream order)
     const void* pending_werr = nullptr;       // error buffers that hold u instead of delta
@@ -97,7 +99,7 @@ apms::Geometry geometry(const apms_ctx* c) {
 
 int hip_fail(apms_ctx* c, hipError_t e) {
     c->last_hip = static_cast<int>(e);
-    return APMS_EHIP;
+    return e == hipErrorOutOfMemory ? APMS_ENOMEM : APMS_EHIP;
 }
 
 // Makes the context's device current for the duration of a call.
@@ -117,16 +119,62 @@ struct DeviceScope {
     }
 };
 
+void free_topk_scratch(apms_ctx* c) {
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
+    for (void* a : arrays)
+        if (a) (void)hipFree(a);
+    c->topk = {};
+    c->topk_bytes = 0;
+}
+
+// Allocates the top-k scratch (see TopkScratch) on first use, and the slots again when K asks for more of
+// them per tile than there are.  The device must be current.  Every array is fully written by the kernels
+// before they read it.
+hipError_t ensure_topk_scratch(apms_ctx* c, int64_t K) {
+    const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
+    const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
+    const int64_t fixed = pairs * (apms::kTopkBins + apms::kTopkStateWords) * 4 + 2 * tiles * 4;
+    hipError_t e = hipSuccess;
+    if (!c->topk.hist) {
+        e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
+        if (e != hipSuccess) {
+            free_topk_scratch(c);
+            return e;
+        }
+        c->topk_bytes = fixed;
+    }
+    const int32_t want = apms::topk_slots_for(K, c->L);
+    if (!c->topk.slots || c->topk.slots_per_tile < want) {
+        if (c->topk.slots) {
+            e = hipDeviceSynchronize();                        // kernels of earlier calls may still read them
+            if (e == hipSuccess) e = hipFree(c->topk.slots);
+            c->topk.slots = nullptr;
+            c->topk.slots_per_tile = 0;
+            c->topk_bytes = fixed;
+            if (e != hipSuccess) return e;
+        }
+        const int64_t bytes = tiles * want * static_cast<int64_t>(sizeof(uint2));
+        e = hipMalloc(reinterpret_cast<void**>(&c->topk.slots), bytes);
+        if (e != hipSuccess) {
+            c->topk.slots = nullptr;
+            return e;
+        }
+        c->topk.slots_per_tile = want;
+        c->topk_bytes = fixed + bytes;
+    }
+    return hipSuccess;
+}
+
 void free_scratch(apms_ctx* c) {
     if (c->w_partials) (void)hipFree(c->w_partials);
     if (c->s_partials) (void)hipFree(c->s_partials);
     if (c->w_pending) (void)hipFree(c->w_pending);
     if (c->s_pending) (void)hipFree(c->s_pending);
     if (c->g_pending) (void)hipFree(c->g_pending);
-    if (c->topk.hist) (void)hipFree(c->topk.hist);
-    if (c->topk.state) (void)hipFree(c->topk.state);
-    if (c->topk.tile_counts) (void)hipFree(c->topk.tile_counts);
-    c->topk = {nullptr, nullptr, nullptr};
+    free_topk_scratch(c);
     c->w_partials = c->s_partials = nullptr;
     c->w_pending = c->s_pending = c->g_pending = nullptr;
 }
@@ -197,9 +245,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     const int64_t sp = C * c->s_tiles_per_chunk * static_cast<int64_t>(sizeof(double));
     const int64_t wq = pairs * static_cast<int64_t>(sizeof(float));
     const int64_t sq = C * static_cast<int64_t>(sizeof(float));
-    const int64_t topk_tiles = apms::tiles_per_chunk(geo, apms::kTopkTile);
-    const int64_t th = pairs * apms::kTopkBins * 4, ts = pairs * apms::kTopkStateWords * 4, tc = pairs * topk_tiles * 4;
-    c->scratch_bytes = wp + sp + wq + 2 * sq + th + ts + tc;
+    c->scratch_bytes = wp + sp + wq + 2 * sq;
     if (device != APMS_DEVICE_NONE && d > 0) {
         DeviceScope scope(device);
         hipError_t e = scope.err;
@@ -209,9 +255,6 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_pending), sq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->g_pending), sq);
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), th);
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), ts);
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tc);
         if (e != hipSuccess) {
             free_scratch(c);
             delete c;
@@ -251,6 +294,7 @@ int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
     plan->apply_tile_elems = apms::kApplyTile;
     plan->apply_grid = c->C * c->a_tiles_per_chunk * c->n;
     plan->scratch_bytes = c->scratch_bytes;
+    plan->topk_scratch_bytes = c->topk_bytes;
     for (int k = 0; k < 8; ++k) plan->occupancy_pad[k] = k < APMS_KERNEL_COUNT ? c->lds_pad[k] : 0;
     return APMS_OK;
 }
@@ -536,8 +580,10 @@ int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worke
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
-                                              static_cast<hipStream_t>(stream));
+    hipError_t e = ensure_topk_scratch(c, K);
+    if (e == hipSuccess)
+        e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
+                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
@@ -554,9 +600,11 @@ int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, 
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
-                                                   1.0f / static_cast<float>(c->n), c->topk,
-                                                   static_cast<hipStream_t>(stream));
+    hipError_t e = ensure_topk_scratch(c, K);
+    if (e == hipSuccess)
+        e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
+                                            1.0f / static_cast<float>(c->n), c->topk,
+                                            static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
@@ -574,8 +622,10 @@ int apms_topk_apply(apms_ctx* c, const uint32_t* sidx, const float* sval, int64_
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps,
-                                           static_cast<hipStream_t>(stream));
+    hipError_t e = ensure_topk_scratch(c, K);
+    if (e == hipSuccess)
+        e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps, c->topk,
+                                    static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 

@@ -5,6 +5,12 @@
 // Selection is exact and deterministic: a 3-level radix select on the 31 magnitude bits finds the K-th
 // largest key T of a chunk; if more elements equal T than may be kept, a second 3-level radix select on the
 // element index finds the last tie to keep.  Kept elements are then emitted in index order.
+//
+// Passes over the dense buffer: one that forms u and the level-0 histogram, and one that copies every
+// element at or above the level-0 bin of T (under 2 % of a tile when K is 1 % of a chunk) to the tile's
+// slots.  Key levels 1 and 2, the per-tile counts and the emission work on the slots alone.  A chunk with a
+// tile that has more such elements than slots (constant or heavily tied data, or a K far beyond what the
+// slots were sized for) takes full passes over the buffer instead: slower, same result.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -15,15 +21,35 @@
 namespace apms {
 
 constexpr int kTopkBins = 2048;        // histogram bins per (slice, chunk) pair: 11 bits per radix level
-constexpr int kTopkStateWords = 8;     // per-pair selection state, see topk.hip
-constexpr int kTopkTile = 4096;        // elements per tile of the count / emit / server / gather kernels
+constexpr int kTopkStateWords = 16;    // per-pair selection state, see topk.hip
+constexpr int kTopkTile = 4096;        // elements per tile of the split / emit / server / gather kernels
+constexpr int kTopkMinSlots = 64;      // slots per tile: a power of two in this range, see topk_slots_for
+constexpr int kTopkMaxSlots = 512;
 
-// Device scratch of the selection, owned by the context: hist [pairs][kTopkBins] u32,
-// state [pairs][kTopkStateWords] u32, tile_counts [pairs][ceil(L / kTopkTile)] u32.
+// Slots per tile for keeping K of L elements per chunk: room for three times the tile's expected share of
+// the kept elements (those above the threshold's level-0 bin plus the bin's own, typically under twice the
+// share) and a margin for small shares.
+inline int32_t topk_slots_for(int64_t K, int64_t L) {
+    const int64_t want = 3 * ((K * kTopkTile + L - 1) / L) + 64;
+    int32_t slots = kTopkMinSlots;
+    while (slots < want && slots < kTopkMaxSlots) slots *= 2;
+    return slots;
+}
+
+// Device scratch of the selection, owned by the context; pairs = n * C, tiles = ceil(L / kTopkTile):
+//   hist        [pairs][kTopkBins] u32
+//   state       [pairs][kTopkStateWords] u32
+//   tile_counts [pairs][tiles] u32       kept elements per tile, then their exclusive scan; the server and
+//                                        gather kernels first use it for the tile offsets of their input lists
+//   tile_split  [pairs][tiles] u32       elements of the tile at or above the level-0 bin of the threshold
+//   slots       [pairs][tiles][slots_per_tile] uint2   those elements: (tile-local index, value bits)
 struct TopkScratch {
     uint32_t* hist;
     uint32_t* state;
     uint32_t* tile_counts;
+    uint32_t* tile_split;
+    uint2* slots;
+    int32_t slots_per_tile;
 };
 
 // Worker: u = beta*m + (1-beta)*g + delta for all (worker, chunk) pairs, written into werr, then the K
@@ -42,6 +68,7 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
 // Gather + model update: every slice of m becomes the decoded server list (zero elsewhere);
 // x <- x - lr * m / (sqrt(v) + eps).
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
-                             const float* v, float* x, float* m, float lr, float eps, hipStream_t stream);
+                             const float* v, float* x, float* m, float lr, float eps, const TopkScratch& scratch,
+                             hipStream_t stream);
 
 }  // namespace apms

@@ -9,6 +9,12 @@
 // such element to keep.  Histograms use integer atomics (order-independent), the emission order comes from
 // per-tile counts and a scan, so the result does not depend on scheduling.
 //
+// Only the level-0 histogram needs every element.  Once the level-0 bin of T is known, one pass splits each
+// tile into elements above that bin (kept whatever T turns out to be), below it (dropped) and inside it
+// (candidates); the candidates, typically well under 1 % of a tile, go to the tile's kTopkSlots slots and
+// key levels 1 and 2 and the per-tile kept counts are computed from the slots.  If some tile of a chunk has
+// more candidates than slots, the chunk is flagged and takes full passes over the buffer instead.
+//
 // Built with -ffp-contract=off: the elementwise arithmetic is that of the 1-bit path.
 
 #include "apms_device.h"
@@ -28,7 +34,10 @@ enum : int {
     kStIdxRemaining = 5,  // how many ties are still to be taken from inside the current index prefix
     kStKeyT = 6,          // T: the K-th largest key
     kStIdxT = 7,          // ties are kept up to and including this chunk-local index
+    kStOverflow = 8,      // 1 if a tile of this pair had more candidates than slots: full passes instead
 };
+
+constexpr uint32_t kTopMask = 0x7FF00000u;      // the level-0 digit of a key
 
 struct Level {
     int shift;
@@ -185,29 +194,40 @@ __device__ __forceinline__ int lower_bound_u32(const uint32_t* __restrict__ a, i
     return lo;
 }
 
+// offsets[list][tile] = how many entries of the sorted index list `list` lie below the tile's first element:
+// where the tile's stretch of the list starts (it ends where the next tile's starts, or at K).
+__global__ __launch_bounds__(kThreads) void topk_tile_offsets_kernel(const uint32_t* __restrict__ idx,
+                                                                     uint32_t* __restrict__ offsets, int64_t lists,
+                                                                     int32_t tiles_per_chunk, int32_t K) {
+    const int64_t t = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (t >= lists * tiles_per_chunk) return;
+    const int64_t list = t / tiles_per_chunk;
+    const int64_t tile = t - list * tiles_per_chunk;
+    offsets[t] = static_cast<uint32_t>(lower_bound_u32(idx + list * K, K, static_cast<uint32_t>(tile * kTopkTile)));
+}
+
 __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t* __restrict__ idx,
                                                                  const float* __restrict__ val,
                                                                  float* __restrict__ serr, uint32_t* __restrict__ hist,
+                                                                 const uint32_t* __restrict__ offsets,
                                                                  int64_t d, int64_t L, int32_t C, int32_t n,
                                                                  int32_t K, int32_t tiles_per_chunk, float inv_n) {
     __shared__ uint32_t lds_hist[kTopkBins];
     __shared__ float acc[kTopkTile];
-    __shared__ int range[2];
     for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
     for (int j = threadIdx.x; j < kTopkTile; j += kThreads) acc[j] = 0.0f;
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // slices = 1: pair = chunk
     const int64_t tile_lo = tr.tile * kTopkTile;
-    const int64_t tile_hi = min(tile_lo + kTopkTile, L);
     __syncthreads();
     for (int32_t i = 0; i < n; ++i) {                         // worker order
-        const int64_t list = (static_cast<int64_t>(i) * C + tr.pair) * K;
-        if (threadIdx.x == 0) {
-            range[0] = lower_bound_u32(idx + list, K, static_cast<uint32_t>(tile_lo));
-            range[1] = lower_bound_u32(idx + list, K, static_cast<uint32_t>(tile_hi));
-        }
-        __syncthreads();
+        const int64_t which = static_cast<int64_t>(i) * C + tr.pair;
+        const int64_t list = which * K;
+        // this tile's stretch of worker i's sorted list, from the table topk_tile_offsets_kernel filled
+        const uint32_t* off = offsets + which * tiles_per_chunk + tr.tile;
+        const int first = static_cast<int>(off[0]);
+        const int last = (tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : K;
         // indices are unique inside one worker's list: no two threads touch the same accumulator
-        for (int t = range[0] + threadIdx.x; t < range[1]; t += kThreads) {
+        for (int t = first + threadIdx.x; t < last; t += kThreads) {
             const uint32_t j = idx[list + t] - static_cast<uint32_t>(tile_lo);
             if (j < static_cast<uint32_t>(kTopkTile)) acc[j] = acc[j] + val[list + t];   // always true for sorted lists
         }
@@ -247,6 +267,7 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
     const int64_t pair = blockIdx.x;
     uint32_t* h = hist + pair * kTopkBins;
     uint32_t* st = state + pair * kTopkStateWords;
+    if (!kIdx && level == 0 && threadIdx.x == 0) st[kStOverflow] = 0u;   // set again by the split pass if need be
     const bool tie_needed = kIdx ? (st[kStTieNeeded] != 0u) : true;
     if (kIdx && !tie_needed) {                                 // every element equal to T is kept
         if (level == 2 && threadIdx.x == 0) st[kStIdxT] = 0xFFFFFFFFu;
@@ -332,26 +353,161 @@ __device__ __forceinline__ void hist_tile(const float* __restrict__ buf, uint32_
     }
 }
 
-// Key levels 1 and 2: one pass over the buffer, one tile per workgroup.
-__global__ __launch_bounds__(kThreads) void topk_key_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
-                                                                 const uint32_t* __restrict__ state, int64_t d, int64_t L,
-                                                                 int32_t C, int32_t tiles_per_chunk, int level) {
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
-    const uint32_t* st = state + tr.pair * kTopkStateWords;
-    hist_tile<false>(buf, hist + tr.pair * kTopkBins, tr.base, tr.tile * kTopkTile, L, key_level(level), st[kStPrefix], 0u);
+// The kernels for the rare cases (ties to break, pairs that overflowed their slots) run on a small grid in
+// which every workgroup visits the flagged pairs and strides over their tiles.  The flags are read kThreads
+// pairs at a time, one per thread, so a launch with nothing to do costs one state read per thread.  A pair
+// is flagged if both state words named are non-zero (name one word twice to test it alone).
+// `body(pair)` may contain workgroup barriers: all threads see the same flags.
+template <class Body>
+__device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ state, int64_t pairs, int flag_word,
+                                                  int second_flag_word, Body body) {
+    __shared__ uint32_t flags[kThreads];
+    for (int64_t p0 = 0; p0 < pairs; p0 += kThreads) {
+        const int64_t p = p0 + threadIdx.x;
+        const uint32_t mine = (p < pairs && state[p * kTopkStateWords + flag_word] != 0u &&
+                               state[p * kTopkStateWords + second_flag_word] != 0u) ? 1u : 0u;
+        if (!__syncthreads_or(mine != 0u)) continue;           // same answer in every thread
+        flags[threadIdx.x] = mine;
+        __syncthreads();
+        for (int q = 0; q < kThreads; ++q)
+            if (flags[q] != 0u) body(p0 + q);
+        __syncthreads();                                       // before the next round overwrites the flags
+    }
 }
 
-// Index (tie) levels usually have nothing to do, so they run on a small grid: every workgroup walks the
-// pairs, skips those without a tie to break with one state read, and strides over the tiles of the others,
-// skipping tiles outside the index range of the current prefix.
+// After the level-0 pick: split every tile of the buffer by the level-0 digit b0 of T.  Elements above b0
+// (kept whatever T turns out to be) and inside b0 (candidates) are copied to the tile's slots as
+// (tile-local index, value bits), in index order; everything below b0 is dropped for certain.  With K at
+// 1 % of a chunk that is under 2 % of the elements.  A tile with more such elements than slots stores the
+// first `slots_per_tile` of them and flags its pair, which then takes full passes over the buffer.
+// Index order inside a tile is row by row (plain layout), thread by thread inside a row: one workgroup scan
+// of the four per-row counts, packed as four 16-bit fields of a uint64, gives every thread its rank.
+__global__ __launch_bounds__(kThreads) void topk_split_kernel(const float* __restrict__ buf, uint32_t* __restrict__ state,
+                                                              uint32_t* __restrict__ tile_split,
+                                                              uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                              int64_t d, int64_t L, int32_t C,
+                                                              int32_t tiles_per_chunk) {
+    static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
+    __shared__ uint64_t lds[kWaves];
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    uint32_t* st = state + tr.pair * kTopkStateWords;
+    const uint32_t b0 = st[kStPrefix] & kTopMask;
+    f32x4 v[kTileRows];
+    uint32_t take_mask = 0;                                    // bit 4*r + c: element c of row r goes to a slot
+    uint64_t packed = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+        v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (off < L) {
+            v[r] = load_stream(buf + tr.base + off);
+            uint32_t count = 0;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                if ((key_of(v[r][c]) & kTopMask) >= b0) {
+                    take_mask |= 1u << (4 * r + c);
+                    ++count;
+                }
+            }
+            packed |= static_cast<uint64_t>(count) << (16 * r);
+        }
+    }
+    uint64_t totals;
+    const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);
+    const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
+    uint2* my_slots = slots + tile_id * slots_per_tile;
+    uint32_t row_base = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (take_mask & (1u << (4 * r + c))) {
+                const uint32_t local = static_cast<uint32_t>(threadIdx.x * 4 + r * kRowStride + c);
+                // by value: a bit cast applied to the vector element expression itself reads element 0
+                const float value = v[r][c];
+                if (rank < static_cast<uint32_t>(slots_per_tile))
+                    my_slots[rank] = make_uint2(local, __builtin_bit_cast(uint32_t, value));
+                ++rank;
+            }
+        }
+        row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
+    }
+    if (threadIdx.x == 0) {
+        tile_split[tile_id] = row_base;                        // all four rows' totals
+        if (row_base > static_cast<uint32_t>(slots_per_tile)) st[kStOverflow] = 1u;
+    }
+}
+
+// Key levels 1 and 2 (kIdx = false) and the index levels of the tie selection (kIdx = true: only pairs with
+// a tie to break) from the slots.  One workgroup takes kCandTilesPerBlock consecutive tiles of one pair, a
+// wave per tile at a time, and accumulates the level's digit histogram in LDS.
+constexpr int kCandTilesPerBlock = 256;
+template <bool kIdx>
+__global__ __launch_bounds__(kThreads) void topk_cand_hist_kernel(const uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                                  const uint32_t* __restrict__ tile_split,
+                                                                  uint32_t* __restrict__ hist,
+                                                                  const uint32_t* __restrict__ state,
+                                                                  int32_t tiles_per_chunk, int32_t blocks_per_pair,
+                                                                  int level) {
+    __shared__ uint32_t lds_hist[kTopkBins];
+    const int64_t pair = blockIdx.x / blocks_per_pair;
+    const int32_t b = static_cast<int32_t>(blockIdx.x - pair * blocks_per_pair);
+    const uint32_t* st = state + pair * kTopkStateWords;
+    if (st[kStOverflow] != 0u) return;                         // whole workgroup: the full passes take this pair
+    if (kIdx && st[kStTieNeeded] == 0u) return;
+    for (int q = threadIdx.x; q < kTopkBins; q += kThreads) lds_hist[q] = 0u;
+    __syncthreads();
+    const Level lv = kIdx ? idx_level(level) : key_level(level);
+    const uint32_t digit_mask = (1u << lv.bits) - 1u;
+    const uint32_t prefix = kIdx ? (level == 0 ? 0u : st[kStIdxPrefix]) : st[kStPrefix];
+    const uint32_t T = st[kStKeyT];                            // final only when kIdx
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int wave = threadIdx.x >> 6;
+    const int32_t t0 = b * kCandTilesPerBlock;
+    const int32_t t1 = min(t0 + kCandTilesPerBlock, tiles_per_chunk);
+    for (int32_t tile = t0 + wave; tile < t1; tile += kWaves) {
+        const int64_t tile_id = pair * tiles_per_chunk + tile;
+        const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
+        for (uint32_t e = lane; e < count; e += kWaveSize) {
+            const uint2 entry = slots[tile_id * slots_per_tile + e];
+            const uint32_t key = entry.y & 0x7FFFFFFFu;
+            if (kIdx) {
+                const uint32_t j = static_cast<uint32_t>(tile) * kTopkTile + entry.x;
+                if (key == T && (j & lv.match_mask) == prefix) atomicAdd(&lds_hist[(j >> lv.shift) & digit_mask], 1u);
+            } else {
+                if ((key & lv.match_mask) == prefix) atomicAdd(&lds_hist[(key >> lv.shift) & digit_mask], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    flush_histogram(lds_hist, hist + pair * kTopkBins);
+}
+
+// Key levels 1 and 2 for pairs that overflowed their slots: full passes over the buffer.
+__global__ __launch_bounds__(kThreads) void topk_key_hist_walk_kernel(const float* __restrict__ buf,
+                                                                      uint32_t* __restrict__ hist,
+                                                                      const uint32_t* __restrict__ state, int64_t d,
+                                                                      int64_t L, int32_t C, int64_t pairs,
+                                                                      int32_t tiles_per_chunk, int level) {
+    for_flagged_pairs(state, pairs, kStOverflow, kStOverflow, [&](int64_t pair) {
+        const uint32_t* st = state + pair * kTopkStateWords;
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        for (int64_t tile = blockIdx.x; tile < tiles_per_chunk; tile += gridDim.x)
+            hist_tile<false>(buf, hist + pair * kTopkBins, base, tile * kTopkTile, L, key_level(level), st[kStPrefix], 0u);
+    });
+}
+
+// Index (tie) levels for pairs that overflowed their slots, from the buffer.  Tiles outside the index range
+// of the current prefix are skipped.
 __global__ __launch_bounds__(kThreads) void topk_tie_hist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
                                                                  const uint32_t* __restrict__ state, int64_t d, int64_t L,
                                                                  int32_t C, int64_t pairs, int32_t tiles_per_chunk,
                                                                  int level) {
     const Level lv = idx_level(level);
-    for (int64_t pair = 0; pair < pairs; ++pair) {
+    for_flagged_pairs(state, pairs, kStTieNeeded, kStOverflow, [&](int64_t pair) {
         const uint32_t* st = state + pair * kTopkStateWords;
-        if (st[kStTieNeeded] == 0u) continue;
         const uint32_t prefix = level == 0 ? 0u : st[kStIdxPrefix];
         const uint32_t T = st[kStKeyT];
         const int64_t slice = pair / C;
@@ -365,32 +521,65 @@ __global__ __launch_bounds__(kThreads) void topk_tie_hist_kernel(const float* __
         }
         for (int64_t tile = first + blockIdx.x; tile < last; tile += gridDim.x)
             hist_tile<true>(buf, hist + pair * kTopkBins, base, tile * kTopkTile, L, lv, prefix, T);
-    }
+    });
 }
 
 // ------------------------------------------------------------------------
 // Emission in index order: per-tile counts, scan, write.
 // ------------------------------------------------------------------------
-__global__ __launch_bounds__(kThreads) void topk_count_kernel(const float* __restrict__ buf,
-                                                              const uint32_t* __restrict__ state,
-                                                              uint32_t* __restrict__ tile_counts, int64_t d, int64_t L,
-                                                              int32_t C, int32_t tiles_per_chunk) {
-    __shared__ uint32_t lds[kWaves];
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
-    const uint32_t* st = state + tr.pair * kTopkStateWords;
+// Kept elements per tile, from the tile's slots (entries above the level-0 bin of T pass the test by
+// themselves).  A wave per tile.
+__global__ __launch_bounds__(kThreads) void topk_slot_count_kernel(const uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                                   const uint32_t* __restrict__ tile_split,
+                                                                   const uint32_t* __restrict__ state,
+                                                                   uint32_t* __restrict__ tile_counts,
+                                                                   int32_t tiles_per_chunk, int64_t tiles_total) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int64_t tile_id = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    if (tile_id >= tiles_total) return;
+    const int64_t pair = tile_id / tiles_per_chunk;
+    const uint32_t tile = static_cast<uint32_t>(tile_id - pair * tiles_per_chunk);
+    const uint32_t* st = state + pair * kTopkStateWords;
+    if (st[kStOverflow] != 0u) return;                         // whole wave: topk_count_walk_kernel takes this pair
     const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+    const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
     uint32_t mine = 0;
-#pragma unroll
-    for (int r = 0; r < kTileRows; ++r) {
-        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
-        if (off >= L) continue;
-        const f32x4 v = load_stream(buf + tr.base + off);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) mine += kept(key_of(v[c]), static_cast<uint32_t>(off + c), T, idxT) ? 1u : 0u;
+    for (uint32_t e = lane; e < count; e += kWaveSize) {
+        const uint2 entry = slots[tile_id * slots_per_tile + e];
+        mine += kept(entry.y & 0x7FFFFFFFu, tile * kTopkTile + entry.x, T, idxT) ? 1u : 0u;
     }
-    uint32_t total;
-    (void)block_exclusive_scan_u32(mine, lds, total);
-    if (threadIdx.x == 0) tile_counts[tr.pair * tiles_per_chunk + tr.tile] = total;
+#pragma unroll
+    for (int off = kWaveSize / 2; off > 0; off >>= 1) mine += static_cast<uint32_t>(__shfl_xor(static_cast<int>(mine), off));
+    if (lane == 0) tile_counts[tile_id] = mine;
+}
+
+// The same from the buffer, for pairs that overflowed their slots.
+__global__ __launch_bounds__(kThreads) void topk_count_walk_kernel(const float* __restrict__ buf,
+                                                                   const uint32_t* __restrict__ state,
+                                                                   uint32_t* __restrict__ tile_counts, int64_t d,
+                                                                   int64_t L, int32_t C, int64_t pairs,
+                                                                   int32_t tiles_per_chunk) {
+    __shared__ uint32_t lds[kWaves];
+    for_flagged_pairs(state, pairs, kStOverflow, kStOverflow, [&](int64_t pair) {
+        const uint32_t* st = state + pair * kTopkStateWords;
+        const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        for (int64_t tile = blockIdx.x; tile < tiles_per_chunk; tile += gridDim.x) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int r = 0; r < kTileRows; ++r) {
+                const int64_t off = tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+                if (off >= L) continue;
+                const f32x4 v = load_stream(buf + base + off);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) mine += kept(key_of(v[c]), static_cast<uint32_t>(off + c), T, idxT) ? 1u : 0u;
+            }
+            uint32_t total;
+            (void)block_exclusive_scan_u32(mine, lds, total);     // contains __syncthreads: uniform trip counts
+            if (threadIdx.x == 0) tile_counts[pair * tiles_per_chunk + tile] = total;
+        }
+    });
 }
 
 // One workgroup per pair: tile_counts -> exclusive offsets, in place.
@@ -409,62 +598,111 @@ __global__ __launch_bounds__(kThreads) void topk_scan_kernel(uint32_t* __restric
 }
 
 // Writes the kept elements of a tile to the pair's (idx, val) list at the tile's offset, in index order,
-// and zeroes them in the buffer: what stays there is u - C[u].  Index order inside a tile is row by row
-// (plain layout), thread by thread inside a row: one workgroup scan of the four per-row counts, packed as
-// four 16-bit fields of a uint64, gives every thread its rank in each row.
-__global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__ buf, const uint32_t* __restrict__ state,
-                                                             const uint32_t* __restrict__ tile_offsets,
-                                                             uint32_t* __restrict__ idx, float* __restrict__ val,
-                                                             int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk,
-                                                             int64_t K) {
+// and zeroes them in the buffer: what stays there is u - C[u].  From the slots (already in index order), a
+// wave per tile: a ballot over 64 entries at a time ranks the kept ones.
+__global__ __launch_bounds__(kThreads) void topk_slot_emit_kernel(float* __restrict__ buf, const uint2* __restrict__ slots,
+                                                                  int32_t slots_per_tile,
+                                                                  const uint32_t* __restrict__ tile_split,
+                                                                  const uint32_t* __restrict__ state,
+                                                                  const uint32_t* __restrict__ tile_offsets,
+                                                                  uint32_t* __restrict__ idx, float* __restrict__ val,
+                                                                  int64_t d, int64_t L, int32_t C,
+                                                                  int32_t tiles_per_chunk, int64_t tiles_total,
+                                                                  int64_t K) {
+    const int lane = threadIdx.x & (kWaveSize - 1);
+    const int64_t tile_id = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
+    if (tile_id >= tiles_total) return;
+    const int64_t pair = tile_id / tiles_per_chunk;
+    const uint32_t tile = static_cast<uint32_t>(tile_id - pair * tiles_per_chunk);
+    const uint32_t* st = state + pair * kTopkStateWords;
+    if (st[kStOverflow] != 0u) return;                         // whole wave: topk_emit_walk_kernel takes this pair
+    const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+    const int64_t slice = pair / C;
+    float* chunk_buf = buf + slice * d + (pair - slice * C) * L;
+    uint32_t* out_idx = idx + pair * K;
+    float* out_val = val + pair * K;
+    const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
+    uint32_t done = tile_offsets[tile_id];                     // list position of this tile's next kept element
+    for (uint32_t e0 = 0; e0 < count; e0 += kWaveSize) {       // same trip count in every lane
+        const uint32_t e = e0 + lane;
+        uint2 entry = make_uint2(0u, 0u);
+        if (e < count) entry = slots[tile_id * slots_per_tile + e];
+        const uint32_t j = tile * kTopkTile + entry.x;         // chunk-local index
+        const bool keep = e < count && j < L && kept(entry.y & 0x7FFFFFFFu, j, T, idxT);
+        const uint64_t votes = __ballot(keep);
+        if (keep) {
+            const uint32_t rank = done + static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes & ((uint64_t{1} << lane) - 1))));
+            if (rank < K) {                                    // holds by construction; guards the list bounds
+                out_idx[rank] = j;
+                const uint32_t bits = entry.y;
+                out_val[rank] = __builtin_bit_cast(float, bits);
+            }
+            chunk_buf[j] = 0.0f;
+        }
+        done += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes)));
+    }
+}
+
+// The same from the buffer, for pairs that overflowed their slots.  Index order inside a tile is row by row
+// (plain layout), thread by thread inside a row, ranked as in topk_split_kernel.
+__global__ __launch_bounds__(kThreads) void topk_emit_walk_kernel(float* __restrict__ buf, const uint32_t* __restrict__ state,
+                                                                  const uint32_t* __restrict__ tile_offsets,
+                                                                  uint32_t* __restrict__ idx, float* __restrict__ val,
+                                                                  int64_t d, int64_t L, int32_t C, int64_t pairs,
+                                                                  int32_t tiles_per_chunk, int64_t K) {
     static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
     __shared__ uint64_t lds[kWaves];
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
-    const uint32_t* st = state + tr.pair * kTopkStateWords;
-    const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
-    uint32_t* out_idx = idx + tr.pair * K;
-    float* out_val = val + tr.pair * K;
-    const uint32_t tile_base = tile_offsets[tr.pair * tiles_per_chunk + tr.tile];
-    f32x4 v[kTileRows];
-    uint32_t keep_mask = 0;                                    // bit 4*r + c: element c of row r is kept
-    uint64_t packed = 0;
+    for_flagged_pairs(state, pairs, kStOverflow, kStOverflow, [&](int64_t pair) {
+        const uint32_t* st = state + pair * kTopkStateWords;
+        const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        uint32_t* out_idx = idx + pair * K;
+        float* out_val = val + pair * K;
+        for (int64_t tile = blockIdx.x; tile < tiles_per_chunk; tile += gridDim.x) {
+            const uint32_t tile_base = tile_offsets[pair * tiles_per_chunk + tile];
+            f32x4 v[kTileRows];
+            uint32_t keep_mask = 0;                            // bit 4*r + c: element c of row r is kept
+            uint64_t packed = 0;
 #pragma unroll
-    for (int r = 0; r < kTileRows; ++r) {
-        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
-        v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (off < L) {
-            v[r] = load_stream(buf + tr.base + off);
-            uint32_t count = 0;
+            for (int r = 0; r < kTileRows; ++r) {
+                const int64_t off = tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+                v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (off < L) {
+                    v[r] = load_stream(buf + base + off);
+                    uint32_t count = 0;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if (kept(key_of(v[r][c]), static_cast<uint32_t>(off + c), T, idxT)) {
-                    keep_mask |= 1u << (4 * r + c);
-                    ++count;
+                    for (int c = 0; c < 4; ++c) {
+                        if (kept(key_of(v[r][c]), static_cast<uint32_t>(off + c), T, idxT)) {
+                            keep_mask |= 1u << (4 * r + c);
+                            ++count;
+                        }
+                    }
+                    packed |= static_cast<uint64_t>(count) << (16 * r);
                 }
             }
-            packed |= static_cast<uint64_t>(count) << (16 * r);
-        }
-    }
-    uint64_t totals;
-    const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);
-    uint32_t row_base = tile_base;
+            uint64_t totals;
+            const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);   // barriers: uniform trip counts
+            uint32_t row_base = tile_base;
 #pragma unroll
-    for (int r = 0; r < kTileRows; ++r) {
-        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
-        uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
+            for (int r = 0; r < kTileRows; ++r) {
+                const int64_t off = tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+                uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
 #pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (keep_mask & (1u << (4 * r + c))) {
-                if (rank < K) {                                // holds by construction; guards the list bounds
-                    out_idx[rank] = static_cast<uint32_t>(off + c);
-                    out_val[rank] = v[r][c];
+                for (int c = 0; c < 4; ++c) {
+                    if (keep_mask & (1u << (4 * r + c))) {
+                        if (rank < K) {                        // holds by construction; guards the list bounds
+                            out_idx[rank] = static_cast<uint32_t>(off + c);
+                            out_val[rank] = v[r][c];
+                        }
+                        buf[base + off + c] = 0.0f;
+                        ++rank;
+                    }
                 }
-                buf[tr.base + off + c] = 0.0f;
-                ++rank;
+                row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
             }
         }
-        row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
-    }
+    });
 }
 
 // ------------------------------------------------------------------------
@@ -473,23 +711,22 @@ __global__ __launch_bounds__(kThreads) void topk_emit_kernel(float* __restrict__
 __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __restrict__ sidx,
                                                               const float* __restrict__ sval,
                                                               const float* __restrict__ v, float* __restrict__ x,
-                                                              float* __restrict__ m, int64_t d, int64_t L, int32_t C,
-                                                              int32_t tiles_per_chunk, int32_t K, float lr, float eps) {
+                                                              float* __restrict__ m,
+                                                              const uint32_t* __restrict__ offsets, int64_t d,
+                                                              int64_t L, int32_t C, int32_t tiles_per_chunk,
+                                                              int32_t K, float lr, float eps) {
     __shared__ float dense[kTopkTile];
-    __shared__ int range[2];
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // pair = slice * C + chunk
     const int64_t slice = tr.pair / C;
     const int64_t chunk = tr.pair - slice * C;
     const int64_t tile_lo = tr.tile * kTopkTile;
-    const int64_t tile_hi = min(tile_lo + kTopkTile, L);
     for (int j = threadIdx.x; j < kTopkTile; j += kThreads) dense[j] = 0.0f;
     const int64_t list = chunk * K;
-    if (threadIdx.x == 0) {
-        range[0] = lower_bound_u32(sidx + list, K, static_cast<uint32_t>(tile_lo));
-        range[1] = lower_bound_u32(sidx + list, K, static_cast<uint32_t>(tile_hi));
-    }
+    const uint32_t* off = offsets + chunk * tiles_per_chunk + tr.tile;
+    const int first = static_cast<int>(off[0]);
+    const int last = (tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : K;
     __syncthreads();
-    for (int t = range[0] + threadIdx.x; t < range[1]; t += kThreads) {
+    for (int t = first + threadIdx.x; t < last; t += kThreads) {
         const uint32_t j = sidx[list + t] - static_cast<uint32_t>(tile_lo);
         if (j < static_cast<uint32_t>(kTopkTile)) dense[j] = sval[list + t];             // always true for sorted lists
     }
@@ -537,30 +774,60 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
     const uint32_t K32 = static_cast<uint32_t>(K);
-    const dim3 tie_grid(static_cast<uint32_t>(tpc < 4096 ? tpc : 4096));
+    const dim3 tie_grid(static_cast<uint32_t>(tpc < 4096 ? tpc : 4096));   // the pair-walking kernels
+    const int32_t cand_blocks = (tpc + kCandTilesPerBlock - 1) / kCandTilesPerBlock;
+    const dim3 cand_grid(static_cast<uint32_t>(pairs * cand_blocks));
+    const int64_t tiles_total = pairs * tpc;
     for (int level = 0; level < 3; ++level) {
+        if (level == 1) {
+            hipLaunchKernelGGL(topk_split_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_split, s.slots,
+                               s.slots_per_tile, geo.d, geo.L, geo.C, tpc);
+            APMS_RETURN_IF_ERROR();
+        }
         if (level > 0) {
-            hipLaunchKernelGGL(topk_key_hist_kernel, per_tile, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
-                               geo.C, tpc, level);
+            hipLaunchKernelGGL(topk_cand_hist_kernel<false>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
+                               s.tile_split, s.hist, s.state, tpc, cand_blocks, level);
+            APMS_RETURN_IF_ERROR();
+            hipLaunchKernelGGL(topk_key_hist_walk_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d,
+                               geo.L, geo.C, pairs, tpc, level);
             APMS_RETURN_IF_ERROR();
         }
         hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
         APMS_RETURN_IF_ERROR();
     }
     for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
+        hipLaunchKernelGGL(topk_cand_hist_kernel<true>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
+                           s.tile_split, s.hist, s.state, tpc, cand_blocks, level);
+        APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_tie_hist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
                            geo.C, pairs, tpc, level);
         APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
         APMS_RETURN_IF_ERROR();
     }
-    hipLaunchKernelGGL(topk_count_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_counts, geo.d, geo.L, geo.C,
-                       tpc);
+    const dim3 per_wave_tile(static_cast<uint32_t>((tiles_total + kWaves - 1) / kWaves));
+    hipLaunchKernelGGL(topk_slot_count_kernel, per_wave_tile, block, 0, stream, s.slots, s.slots_per_tile, s.tile_split,
+                       s.state, s.tile_counts, tpc, tiles_total);
+    APMS_RETURN_IF_ERROR();
+    hipLaunchKernelGGL(topk_count_walk_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_counts, geo.d, geo.L,
+                       geo.C, pairs, tpc);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_scan_kernel, per_pair, block, 0, stream, s.tile_counts, tpc);
     APMS_RETURN_IF_ERROR();
-    hipLaunchKernelGGL(topk_emit_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_counts, idx, val, geo.d, geo.L,
-                       geo.C, tpc, K);
+    hipLaunchKernelGGL(topk_slot_emit_kernel, per_wave_tile, block, 0, stream, buf, s.slots, s.slots_per_tile,
+                       s.tile_split, s.state, s.tile_counts, idx, val, geo.d, geo.L, geo.C, tpc, tiles_total, K);
+    APMS_RETURN_IF_ERROR();
+    hipLaunchKernelGGL(topk_emit_walk_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_counts, idx, val, geo.d,
+                       geo.L, geo.C, pairs, tpc, K);
+    return hipGetLastError();
+}
+
+// Fills s.tile_counts[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries.
+hipError_t tile_offsets(int64_t lists, int32_t tpc, int64_t K, const uint32_t* idx, const TopkScratch& s,
+                        hipStream_t stream) {
+    const int64_t blocks = (lists * tpc + kThreads - 1) / kThreads;
+    hipLaunchKernelGGL(topk_tile_offsets_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, idx,
+                       s.tile_counts, lists, tpc, static_cast<int32_t>(K));
     return hipGetLastError();
 }
 
@@ -595,20 +862,25 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     hipError_t e = zero_histograms(geo.C, scratch, stream);
     if (e != hipSuccess) return e;
+    e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, K, idx, scratch, stream);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(topk_server_u_kernel, dim3(static_cast<uint32_t>(static_cast<int64_t>(geo.C) * tpc)),
-                       dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, geo.d, geo.L, geo.C, geo.n,
-                       static_cast<int32_t>(K), tpc, inv_n);
+                       dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.tile_counts, geo.d, geo.L,
+                       geo.C, geo.n, static_cast<int32_t>(K), tpc, inv_n);
     APMS_RETURN_IF_ERROR();
     return select_and_emit(geo, 1, K, serr, sidx, sval, scratch, stream);
 }
 
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
-                             const float* v, float* x, float* m, float lr, float eps, hipStream_t stream) {
+                             const float* v, float* x, float* m, float lr, float eps, const TopkScratch& scratch,
+                             hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
     if (pairs <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    const hipError_t e = tile_offsets(geo.C, tpc, K, sidx, scratch, stream);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(topk_apply_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), 0, stream, sidx, sval,
-                       v, x, m, geo.d, geo.L, geo.C, tpc, static_cast<int32_t>(K), lr, eps);
+                       v, x, m, scratch.tile_counts, geo.d, geo.L, geo.C, tpc, static_cast<int32_t>(K), lr, eps);
     return hipGetLastError();
 }
 

@@ -61,6 +61,8 @@ CASES = [
     (3, 4096 * 5 + 96, 3, 207),       # ragged last tile
     (4, 65536, 2, 655),               # 1 %
     (16, 4096 * 3 + 1024, 2, 13),
+    (2, 65536, 2, 6554),              # 10 %: many candidates per tile, still inside the slots
+    (2, 65536 + 4096 + 64, 2, 34848), # half of everything: the threshold sits where the key bins are fullest
 ]
 
 
@@ -98,6 +100,60 @@ def test_topk_ties(K):
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.5, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.5, 1e-3, 1e-8)
         compare(run, ost, "ties step %d" % step)
+    run.close()
+
+
+@pytest.mark.parametrize("level", ["threshold", "above", "below"])
+def test_topk_one_constant_tile_among_random_ones(level):
+    """One tile of one (worker, chunk) pair holds 4096 equal magnitudes at, above or below the chunk's
+    threshold while everything else is random: that pair's tile has more candidates than slots when the
+    constant shares the threshold's level-0 bin, so the pair takes the full passes and its neighbours the
+    candidate slots, inside one call."""
+    n, L, C, K = 3, 4096 * 6 + 512, 2, 250
+    d = L * C
+    rng = np.random.default_rng(7)
+    z = np.zeros
+    werr = rng.normal(0, 3e-3, (n, d)).astype(F)
+    # |u| of the random part has a standard deviation of about 3.2e-3; the 1 % quantile is near 8e-3
+    const = {"threshold": 8.0e-3, "above": 0.5, "below": 1e-5}[level]
+    lo = L + 4096 * 2                                         # worker 1, chunk 1, tile 2
+    werr[1, lo:lo + 4096] = const * np.where(np.arange(4096) % 3 == 0, -1.0, 1.0).astype(F)
+    st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=werr, serr=z(d, F))
+    run, ost = make(d, n, L, st)
+    for step in range(2):
+        say("constant tile (%s) step %d" % (level, step))
+        g = rng.normal(0, 1e-2, (n, d)).astype(F)
+        if step == 0:
+            g[1, lo:lo + 4096] = 0.0
+        run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
+        ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
+        compare(run, ost, "constant tile (%s) step %d" % (level, step))
+    run.close()
+
+
+def test_topk_few_ties_at_the_threshold():
+    """Random data in which the K-th largest magnitude of every (worker, chunk) pair occurs seven times, in
+    different tiles and with both signs: the index rule decides among them, and the tiles are far from
+    overflowing their slots."""
+    n, L, C, K = 2, 4096 * 4 + 160, 2, 100
+    d = L * C
+    rng = np.random.default_rng(11)
+    z = np.zeros
+    werr = rng.normal(0, 3e-3, (n, d)).astype(F)
+    for i in range(n):
+        for k in range(C):
+            chunk = werr[i, k * L:(k + 1) * L]
+            order = np.argsort(-np.abs(chunk), kind="stable")
+            t = np.abs(chunk[order[K - 1]])
+            small = order[K + 50:]                            # positions holding smaller magnitudes
+            picks = rng.choice(small, 6, replace=False)
+            chunk[picks] = t * np.where(np.arange(6) % 2 == 0, 1.0, -1.0).astype(F)
+    st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=werr, serr=z(d, F))
+    run, ost = make(d, n, L, st)
+    g = z((n, d), F)                                          # u = werr exactly
+    run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
+    ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
+    compare(run, ost, "few ties")
     run.close()
 
 
