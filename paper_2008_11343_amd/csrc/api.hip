@@ -120,7 +120,7 @@ struct DeviceScope {
 };
 
 void free_topk_scratch(apms_ctx* c) {
-    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
     for (void* a : arrays)
         if (a) (void)hipFree(a);
     c->topk = {};
@@ -133,11 +133,12 @@ void free_topk_scratch(apms_ctx* c) {
 hipError_t ensure_topk_scratch(apms_ctx* c, int64_t K) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
-    const int64_t fixed = pairs * (apms::kTopkBins + apms::kTopkStateWords) * 4 + 2 * tiles * 4;
+    const int64_t fixed = pairs * (apms::kTopkBins + apms::kTopkStateWords + 1) * 4 + 2 * tiles * 4;
     hipError_t e = hipSuccess;
     if (!c->topk.hist) {
         e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), pairs * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
         if (e != hipSuccess) {
@@ -162,6 +163,9 @@ hipError_t ensure_topk_scratch(apms_ctx* c, int64_t K) {
             c->topk.slots = nullptr;
             return e;
         }
+        // no guess to go by: the slots' size decides how low a guess may be without overflowing them
+        e = hipMemset(c->topk.guess, 0xFF, pairs * 4);
+        if (e != hipSuccess) return e;
         c->topk.slots_per_tile = want;
         c->topk_bytes = fixed + bytes;
     }

@@ -34,8 +34,11 @@ enum : int {
     kStIdxRemaining = 5,  // how many ties are still to be taken from inside the current index prefix
     kStKeyT = 6,          // T: the K-th largest key
     kStIdxT = 7,          // ties are kept up to and including this chunk-local index
-    kStOverflow = 8,      // 1 if a tile of this pair had more candidates than slots: full passes instead
+    kStOverflow = 8,      // 1 if a tile of this pair had more entries than slots: full passes instead
+    kStResplit = 9,       // 1 if the pair's slots have to be filled again, from the threshold bin now known
 };
+
+constexpr uint32_t kNoGuess = 0xFFFFFFFFu;      // guess[pair]: no earlier call to go by
 
 constexpr uint32_t kTopMask = 0x7FF00000u;      // the level-0 digit of a key
 
@@ -147,37 +150,96 @@ __device__ __forceinline__ void flush_histogram(const uint32_t* lds_hist, uint32
     }
 }
 
+// Copies the marked elements of a tile (bit 4*r + c of take_mask: element c of row r of this thread; packed:
+// the four per-row counts as 16-bit fields) to the tile's slots as (tile-local index, value bits), in index
+// order, as far as there are slots; returns how many elements were marked in the whole tile.  Index order
+// inside a tile is row by row (plain layout), thread by thread inside a row: one workgroup scan of the packed
+// counts gives every thread its rank in each row.  Contains workgroup barriers.
+__device__ __forceinline__ uint32_t write_tile_slots(const f32x4 (&v)[kTileRows], uint32_t take_mask, uint64_t packed,
+                                                     uint64_t* lds /* kWaves */, uint2* __restrict__ my_slots,
+                                                     int32_t slots_per_tile) {
+    static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
+    uint64_t totals;
+    const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);
+    uint32_t row_base = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            if (take_mask & (1u << (4 * r + c))) {
+                const uint32_t local = static_cast<uint32_t>(threadIdx.x * 4 + r * kRowStride + c);
+                // by value: a bit cast applied to the vector element expression itself reads element 0
+                const float value = v[r][c];
+                if (rank < static_cast<uint32_t>(slots_per_tile))
+                    my_slots[rank] = make_uint2(local, __builtin_bit_cast(uint32_t, value));
+                ++rank;
+            }
+        }
+        row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
+    }
+    return row_base;
+}
+
 // ------------------------------------------------------------------------
 // Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
 // ------------------------------------------------------------------------
+// The threshold hardly moves from one step to the next, so the pass also fills the slots on a guess: the
+// level-0 bin of the previous call's threshold, less one (guess[pair]; kNoGuess before the first call).
+// The guess is good if it is not above the bin the selection then finds - the slots hold a superset of what
+// is needed, and the extra entries fail every later test; otherwise, or if a tile overflowed on the guess,
+// the pair is marked and topk_split_kernel fills its slots again.
 __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __restrict__ m,
                                                                  const float* __restrict__ g,
                                                                  float* __restrict__ e, uint32_t* __restrict__ hist,
+                                                                 uint32_t* __restrict__ state,
+                                                                 const uint32_t* __restrict__ guess,
+                                                                 uint32_t* __restrict__ tile_split,
+                                                                 uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                  int64_t d, int64_t L, int32_t C,
                                                                  int32_t tiles_per_chunk, float beta, float omb) {
     __shared__ uint32_t lds_hist[kTopkBins];
+    __shared__ uint64_t lds_scan[kWaves];
     for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
     __syncthreads();
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
     const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
+    const uint32_t guessed = guess[tr.pair];
+    const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
+    f32x4 u[kTileRows];
+    uint32_t take_mask = 0;
+    uint64_t packed = 0;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int64_t off = off0 + r * kRowStride;
+        u[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (off >= L) continue;
         const int64_t p = tr.base + off;
         const f32x4 vm = load_stream(m + p), vg = load_stream(g + p), ve = load_stream(e + p);
-        f32x4 u;
+        uint32_t count = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float bm = beta * vm[c];
             const float bg = omb * vg[c];
             const float mi = bm + bg;
-            u[c] = mi + ve[c];
-            atomicAdd(&lds_hist[key_of(u[c]) >> 20], 1u);
+            u[r][c] = mi + ve[c];
+            const uint32_t key = key_of(u[r][c]);
+            atomicAdd(&lds_hist[key >> 20], 1u);
+            if ((key & kTopMask) >= floor_bits) {
+                take_mask |= 1u << (4 * r + c);
+                ++count;
+            }
         }
-        store_stream(e + p, u);
+        packed |= static_cast<uint64_t>(count) << (16 * r);
+        store_stream(e + p, u[r]);
     }
-    __syncthreads();
+    const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
+    const uint32_t marked = write_tile_slots(u, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
+                                             slots_per_tile);        // its barriers also cover lds_hist
+    if (threadIdx.x == 0) {
+        tile_split[tile_id] = marked;
+        if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
+    }
     flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
 }
 
@@ -260,14 +322,15 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
 // One workgroup per pair.  Scans the level's histogram (from the top bin down for keys, from bin 0 up for
 // indices) to the bin where the running count reaches `remaining`, records it in the state and clears the
 // histogram for the next level.
+// At key level 0 with a guess table: checks the guess the slots were filled on against the bin found (see
+// topk_worker_u_kernel) and leaves the next call's guess.
 template <bool kIdx>
 __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
-                                                             int level, uint32_t K) {
+                                                             int level, uint32_t K, uint32_t* __restrict__ guess) {
     __shared__ uint32_t lds[kWaves];
     const int64_t pair = blockIdx.x;
     uint32_t* h = hist + pair * kTopkBins;
     uint32_t* st = state + pair * kTopkStateWords;
-    if (!kIdx && level == 0 && threadIdx.x == 0) st[kStOverflow] = 0u;   // set again by the split pass if need be
     const bool tie_needed = kIdx ? (st[kStTieNeeded] != 0u) : true;
     if (kIdx && !tie_needed) {                                 // every element equal to T is kept
         if (level == 2 && threadIdx.x == 0) st[kStIdxT] = 0xFFFFFFFFu;
@@ -310,6 +373,10 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
                 } else {
                     st[kStPrefix] = new_prefix;
                     st[kStRemaining] = left;
+                    if (level == 0 && guess) {
+                        if (guess[pair] == kNoGuess || guess[pair] > bin) st[kStResplit] = 1u;
+                        guess[pair] = bin > 0u ? bin - 1u : 0u;
+                    }
                     if (level == 2) {
                         st[kStKeyT] = new_prefix;
                         st[kStCountEq] = cnt[q];
@@ -375,68 +442,53 @@ __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ s
     }
 }
 
-// After the level-0 pick: split every tile of the buffer by the level-0 digit b0 of T.  Elements above b0
-// (kept whatever T turns out to be) and inside b0 (candidates) are copied to the tile's slots as
-// (tile-local index, value bits), in index order; everything below b0 is dropped for certain.  With K at
-// 1 % of a chunk that is under 2 % of the elements.  A tile with more such elements than slots stores the
-// first `slots_per_tile` of them and flags its pair, which then takes full passes over the buffer.
-// Index order inside a tile is row by row (plain layout), thread by thread inside a row: one workgroup scan
-// of the four per-row counts, packed as four 16-bit fields of a uint64, gives every thread its rank.
+// After the level-0 pick, for the pairs marked kStResplit (every pair of a call that had no guess to go by):
+// fill the slots of every tile from the buffer, by the level-0 digit b0 of T.  Elements above b0 (kept
+// whatever T turns out to be) and inside b0 (candidates) are copied, everything below b0 is dropped for
+// certain.  With K at 1 % of a chunk that is under 2 % of the elements.  A tile with more such elements than
+// slots stores the first `slots_per_tile` of them and flags its pair kStOverflow, which then takes full
+// passes over the buffer.
 __global__ __launch_bounds__(kThreads) void topk_split_kernel(const float* __restrict__ buf, uint32_t* __restrict__ state,
                                                               uint32_t* __restrict__ tile_split,
                                                               uint2* __restrict__ slots, int32_t slots_per_tile,
-                                                              int64_t d, int64_t L, int32_t C,
+                                                              int64_t d, int64_t L, int32_t C, int64_t pairs,
                                                               int32_t tiles_per_chunk) {
-    static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
     __shared__ uint64_t lds[kWaves];
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
-    uint32_t* st = state + tr.pair * kTopkStateWords;
-    const uint32_t b0 = st[kStPrefix] & kTopMask;
-    f32x4 v[kTileRows];
-    uint32_t take_mask = 0;                                    // bit 4*r + c: element c of row r goes to a slot
-    uint64_t packed = 0;
+    for_flagged_pairs(state, pairs, kStResplit, kStResplit, [&](int64_t pair) {
+        uint32_t* st = state + pair * kTopkStateWords;
+        const uint32_t b0 = st[kStPrefix] & kTopMask;
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        for (int64_t tile = blockIdx.x; tile < tiles_per_chunk; tile += gridDim.x) {
+            f32x4 v[kTileRows];
+            uint32_t take_mask = 0;                            // bit 4*r + c: element c of row r goes to a slot
+            uint64_t packed = 0;
 #pragma unroll
-    for (int r = 0; r < kTileRows; ++r) {
-        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
-        v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
-        if (off < L) {
-            v[r] = load_stream(buf + tr.base + off);
-            uint32_t count = 0;
+            for (int r = 0; r < kTileRows; ++r) {
+                const int64_t off = tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+                v[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+                if (off < L) {
+                    v[r] = load_stream(buf + base + off);
+                    uint32_t count = 0;
 #pragma unroll
-            for (int c = 0; c < 4; ++c) {
-                if ((key_of(v[r][c]) & kTopMask) >= b0) {
-                    take_mask |= 1u << (4 * r + c);
-                    ++count;
+                    for (int c = 0; c < 4; ++c) {
+                        if ((key_of(v[r][c]) & kTopMask) >= b0) {
+                            take_mask |= 1u << (4 * r + c);
+                            ++count;
+                        }
+                    }
+                    packed |= static_cast<uint64_t>(count) << (16 * r);
                 }
             }
-            packed |= static_cast<uint64_t>(count) << (16 * r);
-        }
-    }
-    uint64_t totals;
-    const uint64_t before = block_exclusive_scan_u64(packed, lds, totals);
-    const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
-    uint2* my_slots = slots + tile_id * slots_per_tile;
-    uint32_t row_base = 0;
-#pragma unroll
-    for (int r = 0; r < kTileRows; ++r) {
-        uint32_t rank = row_base + static_cast<uint32_t>((before >> (16 * r)) & 0xFFFFu);
-#pragma unroll
-        for (int c = 0; c < 4; ++c) {
-            if (take_mask & (1u << (4 * r + c))) {
-                const uint32_t local = static_cast<uint32_t>(threadIdx.x * 4 + r * kRowStride + c);
-                // by value: a bit cast applied to the vector element expression itself reads element 0
-                const float value = v[r][c];
-                if (rank < static_cast<uint32_t>(slots_per_tile))
-                    my_slots[rank] = make_uint2(local, __builtin_bit_cast(uint32_t, value));
-                ++rank;
+            const int64_t tile_id = pair * tiles_per_chunk + tile;
+            const uint32_t marked = write_tile_slots(v, take_mask, packed, lds, slots + tile_id * slots_per_tile,
+                                                     slots_per_tile);     // barriers: uniform trip counts
+            if (threadIdx.x == 0) {
+                tile_split[tile_id] = marked;
+                if (marked > static_cast<uint32_t>(slots_per_tile)) st[kStOverflow] = 1u;
             }
         }
-        row_base += static_cast<uint32_t>((totals >> (16 * r)) & 0xFFFFu);
-    }
-    if (threadIdx.x == 0) {
-        tile_split[tile_id] = row_base;                        // all four rows' totals
-        if (row_base > static_cast<uint32_t>(slots_per_tile)) st[kStOverflow] = 1u;
-    }
+    });
 }
 
 // Key levels 1 and 2 (kIdx = false) and the index levels of the tie selection (kIdx = true: only pairs with
@@ -756,9 +808,17 @@ __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __
     }
 }
 
-__global__ __launch_bounds__(kThreads) void topk_zero_kernel(uint32_t* __restrict__ p, int64_t count) {
+// Start of a call: clear the histograms and the per-pair flags.  resplit = 1 marks every pair for
+// topk_split_kernel (calls whose first pass does not fill the slots).
+__global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restrict__ hist, int64_t count,
+                                                              uint32_t* __restrict__ state, int64_t pairs,
+                                                              uint32_t resplit) {
     const int64_t stride = static_cast<int64_t>(gridDim.x) * kThreads;
-    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) p[i] = 0u;
+    for (int64_t i = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; i < count; i += stride) hist[i] = 0u;
+    for (int64_t p = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; p < pairs; p += stride) {
+        state[p * kTopkStateWords + kStOverflow] = 0u;
+        state[p * kTopkStateWords + kStResplit] = resplit;
+    }
 }
 
 #define APMS_RETURN_IF_ERROR()                 \
@@ -768,8 +828,10 @@ __global__ __launch_bounds__(kThreads) void topk_zero_kernel(uint32_t* __restric
     } while (0)
 
 // The selection + emission over `slices` x C pairs of `buf` ([slices][d]) whose level-0 histogram is filled.
+// `guess`: the per-pair table the first pass filled the slots on (see topk_worker_u_kernel), or nullptr if it
+// did not fill them (every pair is then marked kStResplit).
 hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float* buf, uint32_t* idx, float* val,
-                           const TopkScratch& s, hipStream_t stream) {
+                           uint32_t* guess, const TopkScratch& s, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
@@ -780,8 +842,8 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     const int64_t tiles_total = pairs * tpc;
     for (int level = 0; level < 3; ++level) {
         if (level == 1) {
-            hipLaunchKernelGGL(topk_split_kernel, per_tile, block, 0, stream, buf, s.state, s.tile_split, s.slots,
-                               s.slots_per_tile, geo.d, geo.L, geo.C, tpc);
+            hipLaunchKernelGGL(topk_split_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_split, s.slots,
+                               s.slots_per_tile, geo.d, geo.L, geo.C, pairs, tpc);
             APMS_RETURN_IF_ERROR();
         }
         if (level > 0) {
@@ -792,7 +854,8 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                                geo.L, geo.C, pairs, tpc, level);
             APMS_RETURN_IF_ERROR();
         }
-        hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
+        hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
+                           level == 0 ? guess : static_cast<uint32_t*>(nullptr));
         APMS_RETURN_IF_ERROR();
     }
     for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
@@ -802,7 +865,8 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
         hipLaunchKernelGGL(topk_tie_hist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
                            geo.C, pairs, tpc, level);
         APMS_RETURN_IF_ERROR();
-        hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32);
+        hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
+                           static_cast<uint32_t*>(nullptr));
         APMS_RETURN_IF_ERROR();
     }
     const dim3 per_wave_tile(static_cast<uint32_t>((tiles_total + kWaves - 1) / kWaves));
@@ -831,11 +895,11 @@ hipError_t tile_offsets(int64_t lists, int32_t tpc, int64_t K, const uint32_t* i
     return hipGetLastError();
 }
 
-hipError_t zero_histograms(int64_t pairs, const TopkScratch& s, hipStream_t stream) {
+hipError_t begin_call(int64_t pairs, bool resplit, const TopkScratch& s, hipStream_t stream) {
     const int64_t count = pairs * kTopkBins;
     const int64_t blocks = (count + kThreads - 1) / kThreads;
-    hipLaunchKernelGGL(topk_zero_kernel, dim3(static_cast<uint32_t>(blocks < 4096 ? blocks : 4096)), dim3(kThreads), 0,
-                       stream, s.hist, count);
+    hipLaunchKernelGGL(topk_begin_kernel, dim3(static_cast<uint32_t>(blocks < 4096 ? blocks : 4096)), dim3(kThreads), 0,
+                       stream, s.hist, count, s.state, pairs, resplit ? 1u : 0u);
     return hipGetLastError();
 }
 
@@ -847,12 +911,13 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, 
     const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
     if (pairs <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
-    hipError_t e = zero_histograms(pairs, scratch, stream);
+    hipError_t e = begin_call(pairs, /*resplit=*/false, scratch, stream);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), 0, stream, m, g,
-                       werr, scratch.hist, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
+                       werr, scratch.hist, scratch.state, scratch.guess, scratch.tile_split, scratch.slots,
+                       scratch.slots_per_tile, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch, stream);
+    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, scratch, stream);
 }
 
 hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint32_t* idx, const float* val,
@@ -860,7 +925,7 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
                                      const TopkScratch& scratch, hipStream_t stream) {
     if (geo.C <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
-    hipError_t e = zero_histograms(geo.C, scratch, stream);
+    hipError_t e = begin_call(geo.C, /*resplit=*/true, scratch, stream);
     if (e != hipSuccess) return e;
     e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, K, idx, scratch, stream);
     if (e != hipSuccess) return e;
@@ -868,7 +933,7 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
                        dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.tile_counts, geo.d, geo.L,
                        geo.C, geo.n, static_cast<int32_t>(K), tpc, inv_n);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, 1, K, serr, sidx, sval, scratch, stream);
+    return select_and_emit(geo, 1, K, serr, sidx, sval, nullptr, scratch, stream);
 }
 
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,

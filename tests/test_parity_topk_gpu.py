@@ -82,6 +82,25 @@ def test_topk_trajectory(n, L, C, K):
     run.close()
 
 
+def test_topk_changing_K_between_steps():
+    """The worker pass fills its slots on the previous call's threshold bin: a K that grows (threshold falls
+    below the guess: the slots are filled again), shrinks (guess low: superset) or outgrows the slots
+    (they are allocated again, guesses forgotten) must not change a bit."""
+    n, L, C = 4, 65536, 2
+    d = L * C
+    wl = W.Workload("topk-K", 2, d=d, n=n, chunk=L, steps=6)
+    st = W.host_state(wl)
+    st["werr"] = np.random.default_rng(5).normal(0, 3e-3, (n, d)).astype(F)
+    run, ost = make(d, n, L, st)
+    for step, K in enumerate([2000, 655, 2000, 66, 4000, 4000]):
+        say("changing K: step %d K=%d" % (step, K))
+        g = W.host_grad(wl, step)
+        run.step_topk(torch.from_numpy(g).to(DEV), K, wl.beta, wl.lr, wl.eps)
+        ost.step_topk(g, K, wl.beta, wl.lr, wl.eps)
+        compare(run, ost, "changing K step %d" % step)
+    run.close()
+
+
 @pytest.mark.parametrize("K", [1, 100, 1500, 3000, 8000])
 def test_topk_ties(K):
     """Values from a five-element set, so almost everything ties: the kept set is decided by the index rule,
