@@ -28,7 +28,8 @@
  *     accumulated in binary64 (exact squares, tree order fixed by the launch
  *     plan) and each scale is rounded to binary32 once.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Work is queued asynchronously; no call synchronises the host.  A context
+ *     Work is queued asynchronously; no call synchronises the host, except an
+ *     apms_topk_* call that has to allocate scratch (see there).  A context
  *     serves one stream at a time.  Results are deterministic for a given
  *     context geometry (no floating-point atomics).
  *   - Return value: APMS_OK or a negative apms_status.  Arguments are validated
