@@ -97,6 +97,9 @@ def main():
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient input (f32 is the benchmark's configuration)")
     ap.add_argument("--occupancy-pad", default="", help="e.g. compress=65536,apply=0 (apms_set_occupancy_pad)")
+    ap.add_argument("--chunk-elems", type=int, default=0,
+                    help="chunk length (the unit that has its own scale and server) instead of the workload's own, "
+                         "which is d_pad / n as in the paper; a labelled variant, e.g. 65536")
     ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -117,6 +120,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
     wl = {w.name: w for w in W.CONFIGS}[args.workload]
+    if args.chunk_elems:
+        import dataclasses
+        wl = dataclasses.replace(wl, chunk=args.chunk_elems, name="%s-chunk%d" % (wl.name, args.chunk_elems))
     dev = "cuda:0"
     d, n, L = wl.d_pad, wl.n, wl.L
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
