@@ -209,7 +209,9 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ 
 // order, add the server error, re-compress.
 // ------------------------------------------------------------------------
 
-template <bool kFull>
+// kWide: the tile is full and its sign words are 16-byte aligned (chunk lengths that are multiples of 128),
+// so a group's ROWS = 4 consecutive words are taken as one 128-bit load.
+template <bool kFull, bool kWide>
 __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
                                             const float* __restrict__ scales, float* __restrict__ serr,
                                             uint32_t* __restrict__ spacked, int64_t d, int64_t L, int32_t C,
@@ -231,16 +233,17 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
         if (ok[r]) ve[r] = load_stream(serr + chunk_base + off0 + 32 * r);
         sum[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
-    // eight workers' sign words in flight per lane; a full tile takes its group's ROWS = 4 consecutive
-    // words as one 128-bit load (w0 is a multiple of 4: chunks and tiles are multiples of 4096 elements)
+    static_assert(!kWide || (kFull && ROWS == 4), "the wide load covers four full rows");
+    // eight workers' sign words in flight per lane
 #pragma unroll 8
     for (int32_t i = 0; i < n; ++i) {
         const float s = scales[static_cast<int64_t>(i) * C + chunk];
         const uint32_t* wp = packed + i * words_per_worker + w0;
         uint32_t w[ROWS];
-        if constexpr (kFull && ROWS == 4) {
+        if constexpr (kWide) {
             const u32x4 wq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wp));
-            w[0] = wq.x, w[1] = wq.y, w[2] = wq.z, w[3] = wq.w;
+#pragma unroll
+            for (int r = 0; r < ROWS; ++r) w[r] = wq[r & 3];
         } else {
 #pragma unroll
             for (int r = 0; r < ROWS; ++r) w[r] = ok[r] ? wp[r] : 0u;
@@ -291,12 +294,17 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
     double acc[4] = {0.0, 0.0, 0.0, 0.0};
     for (int32_t t = t0; t < t1; ++t) {
         const int64_t tile_off = static_cast<int64_t>(t) * kServerTile;
-        if (tile_off + kServerTile <= L)
-            server_tile<true>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
-                              inv_n, prev_scale, acc);
-        else
-            server_tile<false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
-                               inv_n, prev_scale, acc);
+        if (tile_off + kServerTile <= L) {
+            if (((chunk * L) & 127) == 0)                      // tile offsets are multiples of 128 anyway
+                server_tile<true, kServerRows == 4>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off,
+                                                    lane_off, lane, wave, inv_n, prev_scale, acc);
+            else
+                server_tile<true, false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane,
+                                         wave, inv_n, prev_scale, acc);
+        } else {
+            server_tile<false, false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
+                                      inv_n, prev_scale, acc);
+        }
     }
     const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
     const double total = block_sum_f64(mine, lds);
