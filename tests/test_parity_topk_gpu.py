@@ -150,6 +150,73 @@ def test_topk_one_constant_tile_among_random_ones(level):
     run.close()
 
 
+def test_topk_many_pairs():
+    """More (worker, chunk) pairs than one round of the flag scan of the full-pass kernels covers (256):
+    random data in most pairs, a constant tile (which overflows its slots) in some beyond the first round."""
+    n, L, C, K = 8, 4096 + 64, 40, 30
+    d = L * C
+    rng = np.random.default_rng(13)
+    z = np.zeros
+    werr = rng.normal(0, 3e-3, (n, d)).astype(F)
+    for i, k in [(0, 3), (6, 20), (7, 39), (7, 0)]:           # pairs 3, 260, 319, 280
+        werr[i, k * L:k * L + 4096] = 0.25 * np.where(np.arange(4096) % 2 == 0, 1.0, -1.0).astype(F)
+    st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=werr, serr=z(d, F))
+    run, ost = make(d, n, L, st)
+    for step in range(2):
+        say("many pairs step %d" % step)
+        g = rng.normal(0, 1e-2, (n, d)).astype(F)
+        run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
+        ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
+        compare(run, ost, "many pairs step %d" % step)
+    run.close()
+
+
+def test_topk_more_tiles_than_the_full_pass_grid():
+    """One chunk of 4200 tiles: the full-pass kernels (4096 workgroups) stride over the tiles.  Random data
+    with one tile of equal large magnitudes, so the chunk overflows its slots and every full-pass kernel
+    runs.  The oracle's sort is too slow at this length for a GPU test, so the expectation is the
+    definition written with numpy: with m = g = 0 the compensated vector is the error buffer itself; kept
+    are the elements above the K-th largest magnitude plus the lowest-indexed ones equal to it."""
+    n, C, K = 1, 1, 20000
+    L = 4096 * 4200 + 32
+    d = L * C
+    rng = np.random.default_rng(17)
+    u = rng.normal(0, 3e-3, d).astype(F)
+    u[4096 * 4150:4096 * 4151] = 0.5 * np.where(np.arange(4096) % 5 == 0, -1.0, 1.0).astype(F)
+    T = np.partition(np.abs(u), d - K)[d - K]                  # K-th largest magnitude ...
+    u[[7, 4096 * 1000 + 5, 4096 * 4199 + 31, d - 1]] = [T, -T, T, -T]   # ... now shared by five elements
+    mag = np.abs(u)
+    assert np.partition(mag, d - K)[d - K] == T
+    above = np.flatnonzero(mag > T)
+    ties = np.flatnonzero(mag == T)[:K - above.size]
+    want = np.sort(np.concatenate([above, ties])).astype(np.uint32)
+    assert want.size == K and ties.size < np.count_nonzero(mag == T)   # the index rule has work to do
+    dev = lambda a: torch.from_numpy(a).to(DEV)
+    z = lambda *shape: torch.zeros(*shape, dtype=torch.float32, device=DEV)
+    werr, m, g, serr = dev(u.reshape(n, d).copy()), z(n, d), z(n, d), z(d)
+    idx, val = torch.zeros(n, C, K, dtype=torch.int32, device=DEV), z(n, C, K)
+    sidx, sval = torch.zeros(C, K, dtype=torch.int32, device=DEV), z(C, K)
+    ctx = B.apms_create(d, n, L, 0)
+    try:
+        for call in range(2):                                 # the second call starts from the first one's guess
+            say("4200 tiles, call %d" % call)
+            werr.copy_(dev(u.reshape(n, d)))
+            B.apms_topk_compress(ctx, m, g, werr, idx, val, K, 0.9)
+            same(host(idx).reshape(-1), want, "indices (call %d)" % call)
+            same(host(val).reshape(-1), u[want], "values (call %d)" % call)
+            rest = u.copy()
+            rest[want] = 0.0
+            same(host(werr).reshape(-1), rest, "worker_err (call %d)" % call)
+        # one worker, zero server error: the server's vector is the worker's message, kept whole
+        B.apms_topk_server_reduce(ctx, idx, val, K, serr, sidx, sval)
+        same(host(sidx).reshape(-1), want, "server indices")
+        same(host(sval).reshape(-1), u[want], "server values")
+        assert not host(serr).any()
+    finally:
+        torch.cuda.synchronize()
+        B.apms_destroy(ctx)
+
+
 def test_topk_few_ties_at_the_threshold():
     """Random data in which the K-th largest magnitude of every (worker, chunk) pair occurs seven times, in
     different tiles and with both signs: the index rule decides among them, and the tiles are far from
