@@ -100,6 +100,10 @@ def main():
     ap.add_argument("--chunk-elems", type=int, default=0,
                     help="chunk length (the unit that has its own scale and server) instead of the workload's own, "
                          "which is d_pad / n as in the paper; a labelled variant, e.g. 65536")
+    ap.add_argument("--placement", choices=["tuned", "packed"], default="tuned",
+                    help="tuned: the worker error and the gradient are the pair of several successively "
+                         "allocated buffers that the worker kernel runs fastest on (the chip's HBM regions; "
+                         "fp32 gradients, buffers of 4 GB and more); packed: as first allocated")
     ap.add_argument("--reuse-grad", action="store_true", help="do not redraw gradients between steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -131,15 +135,17 @@ def main():
                 "eager": 0,
                 "implicit": B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM}[args.mode]
     warm = None
+    gdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.grad_dtype]
+    # the run owns every buffer, the gradient input included, so that it can place them in HBM
+    run = DeviceRun(d, n, L, dev, deferred=deferral, place=args.placement == "tuned" and args.algo != "topk",
+                    grad_dtype=gdt)
+    if run.placement:
+        log("placement: pair %d of %s ms" % (run.placement["chosen_pair"], run.placement["worker_kernel_ms_by_pair"]))
     if wl.warmup_steps:
         # full pipeline: Adam warm-up on the averaged gradients (Algorithm 1 line 2), then freeze v
-        st = W.device_state(wl, dev, warm_start=True)
-        run = DeviceRun(d, n, L, dev, deferred=deferral)
-        run.x.copy_(st["x"])
-        run.v.zero_()
-        del st
+        W.device_state_(wl, dict(x=run.x, m=run.m[0], v=run.v), warm_start=True)
     else:
-        run = DeviceRun(d, n, L, dev, deferred=deferral, state=W.device_state(wl, dev))
+        W.device_state_(wl, dict(x=run.x, m=run.m, v=run.v, werr=run.werr, serr=run.serr))
     if args.compress_tiles or args.server_tiles:
         B.apms_set_tiles_per_block(run.ctx, args.compress_tiles, args.server_tiles)
     kernel_ids = {"compress": B.APMS_KERNEL_COMPRESS, "server": B.APMS_KERNEL_SERVER,
@@ -156,9 +162,8 @@ def main():
         run.idx, run.val = torch.zeros(n, wl.C, topk_K, **i32), torch.zeros(n, wl.C, topk_K, **f32)
         run.sidx, run.sval = torch.zeros(wl.C, topk_K, **i32), torch.zeros(wl.C, topk_K, **f32)
     plan = B.apms_get_plan(run.ctx)
-    g32 = torch.empty(n, d, dtype=torch.float32, device=dev)
-    gdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.grad_dtype]
-    g = g32 if gdt == torch.float32 else torch.empty(n, d, dtype=gdt, device=dev)
+    g = run.g
+    g32 = g if gdt == torch.float32 else torch.empty(n, d, dtype=torch.float32, device=dev)   # generation buffer
     gbytes = g.element_size()
     stream = torch.cuda.current_stream()
 
@@ -287,6 +292,7 @@ def main():
                                           "server_grid", "apply_grid", "occupancy_pad")},
             "wall_s_including_input_generation": wall,
             "adam_warmup": warm,
+            "placement": run.placement,
             "device": torch.cuda.get_device_name(0),
         },
         "roofline": {

@@ -192,18 +192,38 @@ def _gen(device, seed_int):
 def device_state(wl: Workload, device="cuda", seed: int = BASE_SEED, warm_start: bool = False) -> dict:
     """Initial state as torch tensors on `device` (same layout as host_state, different random bits)."""
     import torch
-    d, dp, n = wl.d, wl.d_pad, wl.n
+    dp, n = wl.d_pad, wl.n
     kw = dict(dtype=torch.float32, device=device)
-    x = torch.zeros(dp, **kw)
+    if warm_start:
+        st = dict(x=torch.empty(dp, **kw), m=torch.empty(dp, **kw), v=torch.empty(dp, **kw))
+    else:
+        st = dict(x=torch.empty(dp, **kw), m=torch.empty(n, dp, **kw), v=torch.empty(dp, **kw),
+                  werr=torch.empty(n, dp, **kw), serr=torch.empty(dp, **kw))
+    return device_state_(wl, st, seed=seed, warm_start=warm_start)
+
+
+def device_state_(wl: Workload, st: dict, seed: int = BASE_SEED, warm_start: bool = False) -> dict:
+    """Fill the tensors of `st` (x, m, v and, unless warm_start, werr, serr; already on the GPU, shapes as
+    device_state returns them) with the initial state, in place."""
+    import torch
+    d, dp, n = wl.d, wl.d_pad, wl.n
+    x, m, v = st["x"], st["m"], st["v"]
+    device = x.device
+    x.zero_()
     x[:d].normal_(0.0, 0.02, generator=_gen(device, _device_seed(wl, "x", seed=seed)))
     if warm_start:
-        return dict(x=x, m=torch.zeros(dp, **kw), v=torch.zeros(dp, **kw))
-    m = torch.zeros(n, dp, **kw)
+        m.zero_()
+        v.zero_()
+        return st
+    assert m.shape == (n, dp)
+    m.zero_()
     for i in range(n):
         m[i, :d].normal_(0.0, 1e-3, generator=_gen(device, _device_seed(wl, "m", i, seed=seed)))
-    v = torch.ones(dp, **kw)
+    v.fill_(1.0)
     v[:d].normal_(-12.0, 1.0, generator=_gen(device, _device_seed(wl, "v", seed=seed))).exp_()
-    return dict(x=x, m=m, v=v, werr=torch.zeros(n, dp, **kw), serr=torch.zeros(dp, **kw))
+    st["werr"].zero_()
+    st["serr"].zero_()
+    return st
 
 
 def device_grad_(wl: Workload, step: int, out, seed: int = BASE_SEED):

@@ -70,16 +70,18 @@ def whole_buffer_properties(run, tag):
 def test_sampled_chunks_at_full_size(wl, steps):
     d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
     say("%s: d_pad=%d n=%d chunk=%d, %d steps" % (wl.name, d, n, L, steps))
-    st = W.device_state(wl, DEV)
-    run = DeviceRun(d, n, L, DEV, deferred=True, state=st)
-    del st
+    # the headline workload also goes through the timed choice of where its big buffers lie
+    run = DeviceRun(d, n, L, DEV, deferred=True, place=wl is W.BERT_LARGE, grad_dtype=torch.float32)
+    W.device_state_(wl, dict(x=run.x, m=run.m, v=run.v, werr=run.werr, serr=run.serr))
+    if wl is W.BERT_LARGE:
+        say("placement: %s" % (run.placement,))
     rng = np.random.default_rng(W.BASE_SEED + wl.index)
     picks = sorted({0, C - 1, int(rng.integers(1, C - 1))})
     osts = {}
     for k in picks:
         sl = slice(k * L, (k + 1) * L)
         osts[k] = oracle.State(L, n, L, run.x[sl].cpu().numpy(), run.m[:, sl].cpu().numpy(), run.v[sl].cpu().numpy())
-    g = torch.empty(n, d, dtype=torch.float32, device=DEV)
+    g = run.g
     for step in range(steps):
         W.device_grad_(wl, step, g)
         run.step(g, wl.beta, wl.lr, wl.eps)
