@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, vendor figure
 # WRITE_SIZE runs, each scaled by what the counter reads for a plain copy of known size); the summary
 # with the commands is profiles/bench_bert-large-flat_hbm_traffic.txt.  Reported only for the workload
 # and error mode it was measured on.
-MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 88.513e9, ("bert-large-flat", "deferred-errors"): 87.762e9}
+MEASURED_COMPRESS_TRAFFIC = {("bert-large-flat", "deferred"): 88.458e9, ("bert-large-flat", "deferred-errors"): 87.763e9}
 
 METRIC = "compressed-momentum step params/sec & HBM GB/s (% of peak), BERT-Large d, 1 GPU"
 
