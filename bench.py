@@ -137,7 +137,7 @@ def main():
     warm = None
     gdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[args.grad_dtype]
     # the run owns every buffer, the gradient input included, so that it can place them in HBM
-    run = DeviceRun(d, n, L, dev, deferred=deferral, place=args.placement == "tuned" and args.algo != "topk",
+    run = DeviceRun(d, n, L, dev, deferred=deferral, place=args.placement == "tuned",
                     grad_dtype=gdt)
     if run.placement:
         log("placement: pair %d of %s ms" % (run.placement["chosen_pair"], run.placement["worker_kernel_ms_by_pair"]))
