@@ -140,7 +140,9 @@ def main():
     run = DeviceRun(d, n, L, dev, deferred=deferral, place=args.placement == "tuned",
                     grad_dtype=gdt)
     if run.placement:
-        log("placement: pair %d of %s ms" % (run.placement["chosen_pair"], run.placement["worker_kernel_ms_by_pair"]))
+        log("placement: pair %d of %s ms; worker-kernel occupancy pad %d of %s ms" % (
+            run.placement["chosen_pair"], run.placement["worker_kernel_ms_by_pair"],
+            run.placement["occupancy_pad_compress"], run.placement["worker_kernel_ms_by_occupancy_pad"]))
     if wl.warmup_steps:
         # full pipeline: Adam warm-up on the averaged gradients (Algorithm 1 line 2), then freeze v
         W.device_state_(wl, dict(x=run.x, m=run.m[0], v=run.v), warm_start=True)

@@ -82,38 +82,51 @@ class DeviceRun:
             return None
         cands = [self.werr, self.g] + [torch.empty(n, d, **f) for _ in range(extra)]
         probe = B.apms_create(d, n, self.L, dev.index or 0)
-        times = []
+
+        def worker_ms(werr, g):
+            best = None
+            for step in range(3):                             # the 1st call of a phase launches another kernel
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                B.apms_compress(probe, self.m, g, werr, self.packed, self.scales, 0.9)
+                b.record()
+                B.apms_server_reduce(probe, self.packed, self.scales, self.serr, self.spacked, self.sscales)
+                B.apms_apply(probe, self.spacked, self.sscales, self.v, self.x, self.m, 1e-4, 1e-8)
+                b.synchronize()
+                if step:
+                    ms = a.elapsed_time(b)
+                    best = ms if best is None else min(best, ms)
+            B.apms_finalize(probe, werr, self.serr, self.m)
+            return best
+
         try:
             if self.deferral:
                 B.apms_set_deferral(probe, self.deferral)          # time what this run's calls will launch
             self.v.fill_(1.0)
             for t in [self.m, self.x, self.serr] + cands:
                 t.zero_()
-            for k in range(len(cands) - 1):
-                best = None
-                for step in range(3):                         # the 1st call of a phase launches another kernel
-                    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                    a.record()
-                    B.apms_compress(probe, self.m, cands[k + 1], cands[k], self.packed, self.scales, 0.9)
-                    b.record()
-                    B.apms_server_reduce(probe, self.packed, self.scales, self.serr, self.spacked, self.sscales)
-                    B.apms_apply(probe, self.spacked, self.sscales, self.v, self.x, self.m, 1e-4, 1e-8)
-                    b.synchronize()
-                    if step:
-                        ms = a.elapsed_time(b)
-                        best = ms if best is None else min(best, ms)
-                B.apms_finalize(probe, cands[k], self.serr, self.m)
-                times.append(best)
+            times = [worker_ms(cands[k], cands[k + 1]) for k in range(len(cands) - 1)]
+            k = min(range(len(times)), key=times.__getitem__)
+            self.werr, self.g = cands[k], cands[k + 1]
+            del cands
+            torch.cuda.empty_cache()
+            # the occupancy cap of the worker kernel pays where its two write streams share a region and
+            # costs a little where they do not: keep whichever is faster here
+            default_pad = B.apms_get_plan(probe)["occupancy_pad"][B.APMS_KERNEL_COMPRESS]
+            pads = {}
+            for pad in sorted({0, default_pad}):
+                B.apms_set_occupancy_pad(probe, B.APMS_KERNEL_COMPRESS, pad)
+                pads[pad] = worker_ms(self.werr, self.g)
+            pad = min(pads, key=pads.get)
+            B.apms_set_occupancy_pad(self.ctx, B.APMS_KERNEL_COMPRESS, pad)
             torch.cuda.synchronize()
         finally:
             B.apms_destroy(probe)
-        k = min(range(len(times)), key=times.__getitem__)
-        self.werr, self.g = cands[k], cands[k + 1]
-        del cands
-        torch.cuda.empty_cache()
         return {"policy": "worker error and gradient = the adjacent pair of %d successively allocated buffers that "
                           "the worker kernel runs fastest on (HBM regions)" % (len(times) + 1),
-                "chosen_pair": k, "worker_kernel_ms_by_pair": [round(t, 3) for t in times]}
+                "chosen_pair": k, "worker_kernel_ms_by_pair": [round(t, 3) for t in times],
+                "worker_kernel_ms_by_occupancy_pad": {str(p): round(t, 3) for p, t in pads.items()},
+                "occupancy_pad_compress": pad}
 
     def close(self):
         if self.ctx is not None:
