@@ -9,11 +9,12 @@
 // such element to keep.  Histograms use integer atomics (order-independent), the emission order comes from
 // per-tile counts and a scan, so the result does not depend on scheduling.
 //
-// Only the level-0 histogram needs every element.  Once the level-0 bin of T is known, one pass splits each
-// tile into elements above that bin (kept whatever T turns out to be), below it (dropped) and inside it
-// (candidates); the candidates, typically well under 1 % of a tile, go to the tile's kTopkSlots slots and
-// key levels 1 and 2 and the per-tile kept counts are computed from the slots.  If some tile of a chunk has
-// more candidates than slots, the chunk is flagged and takes full passes over the buffer instead.
+// Only the level-0 histogram needs every element.  What the later steps need are the elements at or above
+// the level-0 bin of T (kept whatever T turns out to be if above, candidates if inside: under 2 % of a tile
+// when K is 1 % of a chunk).  They are copied to per-tile slots - by the worker's first pass itself, on the
+// previous call's bin, else by one more pass once the bin is known - and key levels 1 and 2, the tie
+// levels, the per-tile kept counts and the emission work on the slots alone.  A chunk with a tile that has
+// more such elements than slots is flagged and takes full passes over the buffer instead.
 //
 // Built with -ffp-contract=off: the elementwise arithmetic is that of the 1-bit path.
 
