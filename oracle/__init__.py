@@ -27,7 +27,7 @@ _LIB = os.path.join(_HERE, "libapms_oracle.so")
 _lib = None
 
 # No FMA contraction, no fast-math: every fp32 operation rounds once, in order.
-CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fPIC", "-shared",
+CFLAGS = ["-O2", "-std=c99", "-ffp-contract=off", "-fno-fast-math", "-fopenmp", "-fPIC", "-shared",
           "-Wall", "-Wextra"]
 
 
@@ -60,11 +60,24 @@ def _load():
             fn.restype = ctypes.c_int
         lib.apms_oracle_widen_g16.argtypes = [ctypes.c_int, i64, ptr, ptr]
         lib.apms_oracle_widen_g16.restype = ctypes.c_int
+        lib.apms_oracle_set_threads.argtypes = [ctypes.c_int]
+        lib.apms_oracle_set_threads.restype = None
         for fn in (lib.apms_oracle_compress, lib.apms_oracle_server_reduce, lib.apms_oracle_apply,
                    lib.apms_oracle_warmup_step, lib.apms_oracle_freeze):
             fn.restype = ctypes.c_int
         _lib = lib
     return _lib
+
+
+def set_threads(threads: int) -> None:
+    """Threads the oracle may spread INDEPENDENT work over ((worker, chunk) problems, chunks, elements of a
+    loop without a carried value); 1, the default, is serial.  The results do not depend on it."""
+    _load().apms_oracle_set_threads(int(threads))
+
+
+def host_cores() -> int:
+    """Cores this process may run on."""
+    return len(os.sched_getaffinity(0))
 
 
 def _p(a, dtype, size):

@@ -1,7 +1,7 @@
 /*
  * APMSqueeze reference oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
  *
- * A plain, slow, single-threaded CPU statement of what one step of the
+ * A plain, slow CPU statement of what one step of the
  * compression stage of APMSqueeze computes (Algorithm 1, lines 3-12, in the
  * parameter-server form of the supplement, "Proof to the Updating Form",
  * steps 1-3, applied to every chunk independently), of the 1-bit
@@ -19,8 +19,12 @@
  *     (compile with -ffp-contract=off, no -ffast-math); denormals are kept;
  *   - the squared l2 norm behind a scale is the exact sum of the exact
  *     squares: each square is formed in a wider type where it is exact and
- *     the sum is carried in `long double` (64-bit significand on x86-64), so
- *     its error is far below one binary64 ulp for any chunk length used here;
+ *     the sum is carried in `long double`.  THIS ASSUMES x86-64, where long
+ *     double is the x87 80-bit format (64-bit significand): the sum's error is
+ *     then far below one binary64 ulp for any chunk length used here.  On a
+ *     host whose long double is binary64 the sum is an ordinary binary64
+ *     accumulation and "exact" weakens to a relative error of about L * 1e-16
+ *     (the file refuses to compile there, see the check below);
  *     it is rounded to binary64 once, divided by the chunk length and square
  *     rooted in binary64, then rounded once to binary32;
  *   - sign(0) = +1: the sign bit sent is (u >= 0), so -0.0 maps to +1;
@@ -29,15 +33,34 @@
  *   - the server sums the n decoded values in worker order 0..n-1 and then
  *     multiplies by fl(1/n).
  *
+ * Threads: single-threaded unless apms_oracle_set_threads() asks for more (and
+ * the file was compiled with OpenMP).  Only independent work is spread: whole
+ * (worker, chunk) problems, whole chunks, or single elements of a loop that has
+ * no carried value; every sum runs in one thread in index order, so the results
+ * are the same bits for any thread count.
+ *
  * Parity status: the trajectory VALUES have no printed worked example in the
  * paper ("parity unpinned" for those); every function here is pinned by the
  * invariants, closed forms, special cases and brute-force checks in
  * tests/test_oracle_pins.py.
  */
+#include <float.h>
 #include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+
+#if LDBL_MANT_DIG < 64
+#error "the norm accumulator needs a long double with a 64-bit significand (x86-64)"
+#endif
+
+/* Threads the loops over independent work may use (1 = serial, the default). */
+static int oracle_threads = 1;
+
+void apms_oracle_set_threads(int threads)
+{
+    oracle_threads = threads > 1 ? threads : 1;
+}
 
 #define APMS_ORACLE_ONEBIT 0   /* sign + l2 scale, Section 5.1            */
 #define APMS_ORACLE_IDENTITY 1 /* C[u] = u: the "uncompressed" variant of  */
@@ -124,38 +147,42 @@ int apms_oracle_compress(int compressor, int64_t d, int32_t n, int64_t L,
         return 0;
     const int64_t C = d / L;
     const float one_minus_beta = 1.0f - beta;
-    float *u = (float *)malloc((size_t)L * sizeof(float));
-    float *c = (float *)malloc((size_t)L * sizeof(float));
-    if (!u || !c) {
+    int failed = 0;
+    /* every (worker, chunk) pair is a problem of its own */
+#pragma omp parallel for schedule(dynamic) num_threads(oracle_threads) reduction(| : failed)
+    for (int64_t pair = 0; pair < (int64_t)n * C; ++pair) {
+        const int32_t i = (int32_t)(pair / C);
+        const int64_t k = pair % C;
+        float *u = (float *)malloc((size_t)L * sizeof(float));
+        float *c = (float *)malloc((size_t)L * sizeof(float));
+        if (!u || !c) {
+            free(u);
+            free(c);
+            failed = 1;
+            continue;
+        }
+        const int64_t base = (int64_t)i * d + k * L;
+        for (int64_t j = 0; j < L; ++j) {
+            if (!m) {
+                u[j] = g[base + j] + werr[base + j];
+                continue;
+            }
+            float bm = beta * m[base + j];
+            float bg = one_minus_beta * g[base + j];
+            float mi = bm + bg;
+            u[j] = mi + werr[base + j];
+        }
+        uint32_t *words = packed ? packed + base / 32 : NULL;
+        compress_chunk(compressor, u, L, words, &scales[(int64_t)i * C + k], c);
+        for (int64_t j = 0; j < L; ++j) {
+            werr[base + j] = u[j] - c[j];
+            if (dense)
+                dense[base + j] = c[j];
+        }
         free(u);
         free(c);
-        return -1;
     }
-    for (int32_t i = 0; i < n; ++i) {
-        for (int64_t k = 0; k < C; ++k) {
-            const int64_t base = (int64_t)i * d + k * L;
-            for (int64_t j = 0; j < L; ++j) {
-                if (!m) {
-                    u[j] = g[base + j] + werr[base + j];
-                    continue;
-                }
-                float bm = beta * m[base + j];
-                float bg = one_minus_beta * g[base + j];
-                float mi = bm + bg;
-                u[j] = mi + werr[base + j];
-            }
-            uint32_t *words = packed ? packed + base / 32 : NULL;
-            compress_chunk(compressor, u, L, words, &scales[(int64_t)i * C + k], c);
-            for (int64_t j = 0; j < L; ++j) {
-                werr[base + j] = u[j] - c[j];
-                if (dense)
-                    dense[base + j] = c[j];
-            }
-        }
-    }
-    free(u);
-    free(c);
-    return 0;
+    return failed ? -1 : 0;
 }
 
 /* ------------------------------------------------------------------------ */
@@ -184,15 +211,21 @@ int apms_oracle_server_reduce(int compressor, int64_t d, int32_t n, int64_t L,
         return 0;
     const int64_t C = d / L;
     const float inv_n = 1.0f / (float)n;
-    float *ubar = (float *)malloc((size_t)L * sizeof(float));
-    float *c = (float *)malloc((size_t)L * sizeof(float));
-    if (!ubar || !c) {
-        free(ubar);
-        free(c);
-        return -1;
-    }
+    int failed = 0;
+    /* chunks are independent; with fewer chunks than threads the threads share the elements of the
+       averaging loop instead (no value is carried from one element to the next) */
+#pragma omp parallel for schedule(dynamic) num_threads(oracle_threads) reduction(| : failed) if (C >= oracle_threads)
     for (int64_t k = 0; k < C; ++k) {
+        float *ubar = (float *)malloc((size_t)L * sizeof(float));
+        float *c = (float *)malloc((size_t)L * sizeof(float));
+        if (!ubar || !c) {
+            free(ubar);
+            free(c);
+            failed = 1;
+            continue;
+        }
         const int64_t base = k * L;
+#pragma omp parallel for num_threads(oracle_threads)
         for (int64_t j = 0; j < L; ++j) {
             float acc = 0.0f;
             for (int32_t i = 0; i < n; ++i) {
@@ -212,10 +245,10 @@ int apms_oracle_server_reduce(int compressor, int64_t d, int32_t n, int64_t L,
             if (sdense)
                 sdense[base + j] = c[j];
         }
+        free(ubar);
+        free(c);
     }
-    free(ubar);
-    free(c);
-    return 0;
+    return failed ? -1 : 0;
 }
 
 /* ------------------------------------------------------------------------ */
@@ -240,6 +273,7 @@ int apms_oracle_apply(int compressor, int64_t d, int32_t n, int64_t L,
                       const float *sdense, const float *v, float *x, float *m,
                       float lr, float eps)
 {
+#pragma omp parallel for num_threads(oracle_threads)
     for (int64_t j = 0; j < d; ++j) {
         const int64_t k = j / L;
         const int64_t base = k * L;
@@ -314,6 +348,7 @@ int apms_oracle_warmup_step(int64_t d, int32_t n, float *x, float *m, float *v,
     const float omb2 = 1.0f - beta2;
     const float bc1 = (float)(1.0 - pow((double)beta1, (double)t));
     const float bc2 = (float)(1.0 - pow((double)beta2, (double)t));
+#pragma omp parallel for num_threads(oracle_threads)
     for (int64_t j = 0; j < d; ++j) {
         float acc = 0.0f;
         for (int32_t i = 0; i < n; ++i)
@@ -402,8 +437,9 @@ int apms_oracle_widen_g16(int format, int64_t count, const uint16_t *in, float *
 /* ------------------------------------------------------------------------ */
 
 /*
- * "We take top k% elements ... sorted by its absolute magnitude": C[u] keeps
- * the K elements of largest |u| of a chunk and zeroes the rest.  The paper
+ * Top-k operator of Section 5.1, second bullet: C[u] keeps the K elements of
+ * largest |u| of a chunk (K = the stated percentage of its length) and zeroes
+ * the rest.  The paper
  * does not say what happens between equal magnitudes; this build keeps the
  * LOWER index first, which makes the result unique.  The wire form of a
  * chunk is K (index, value) pairs, indices local to the chunk, ascending.

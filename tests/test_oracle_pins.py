@@ -449,6 +449,37 @@ def test_determinism():
         np.testing.assert_array_equal(a, b_)
 
 
+@pytest.mark.parametrize("shape", [(4096, 4, 1024), (3 * 2048, 3, 2048 * 3), (8 * 160, 5, 160)],
+                         ids=["4chunks", "1chunk", "8chunks"])
+def test_thread_count_does_not_change_a_bit(shape):
+    """Only independent work is spread over threads (whole (worker, chunk) problems, whole chunks, elements of
+    loops with no carried value), so any thread count gives the bits of the serial run: warm-up, hand-over and
+    compressed steps, more chunks than threads and fewer."""
+    d, n, L = shape
+    rng = np.random.default_rng(15)
+    x, _, _ = rand_state(rng, d, n)
+    gs = [rng.normal(0, 1e-2, (n, d)).astype(F) for _ in range(5)]
+    outs = []
+    try:
+        for threads in (1, 2, 5):
+            oracle.set_threads(threads)
+            xw, mw, vw = x.copy(), np.zeros(d, F), np.zeros(d, F)
+            for t in (1, 2):
+                oracle.warmup_step(d, n, xw, mw, vw, gs[t - 1], 1e-3, 0.9, 0.999, 1e-8, t)
+            m = np.zeros((n, d), F)
+            oracle.freeze(d, n, mw, m, np.zeros((n, d), F), np.zeros(d, F))
+            st = oracle.State(d, n, L, xw, m, vw)
+            for g in gs[2:]:
+                st.step(g, 0.9, 1e-4, 1e-8)
+            outs.append((st.x.copy(), st.m.copy(), st.werr.copy(), st.serr.copy(), st.packed.copy(),
+                         st.spacked.copy(), st.scales.copy(), st.sscales.copy()))
+    finally:
+        oracle.set_threads(1)
+    for other in outs[1:]:
+        for a, b_ in zip(outs[0], other):
+            np.testing.assert_array_equal(a, b_)
+
+
 def test_empty_input():
     """d = 0 is a valid, empty problem: nothing is read or written."""
     e = np.zeros((1, 0), F)
