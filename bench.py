@@ -163,6 +163,7 @@ def main():
         f32 = dict(dtype=torch.float32, device=dev)
         run.idx, run.val = torch.zeros(n, wl.C, topk_K, **i32), torch.zeros(n, wl.C, topk_K, **f32)
         run.sidx, run.sval = torch.zeros(wl.C, topk_K, **i32), torch.zeros(wl.C, topk_K, **f32)
+        B.apms_topk_reserve(run.ctx, topk_K)
     plan = B.apms_get_plan(run.ctx)
     g = run.g
     g32 = g if gdt == torch.float32 else torch.empty(n, d, dtype=torch.float32, device=dev)   # generation buffer

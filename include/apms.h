@@ -28,12 +28,15 @@
  *     accumulated in binary64 (exact squares, tree order fixed by the launch
  *     plan) and each scale is rounded to binary32 once.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *     Work is queued asynchronously; no call synchronises the host, except an
- *     apms_topk_* call that has to allocate scratch (see there).  A context
- *     serves one stream at a time.  Results are deterministic for a given
+ *     Work is queued asynchronously; no compute call allocates, frees or
+ *     synchronises the host (the set-up calls apms_create, apms_destroy and
+ *     apms_topk_reserve do).  A context serves one stream at a time.  Results are deterministic for a given
  *     context geometry (no floating-point atomics).
  *   - Return value: APMS_OK or a negative apms_status.  Arguments are validated
- *     on the host before anything is launched; on an error nothing was queued.
+ *     on the host before anything is launched; on a validation error nothing
+ *     was queued.  After APMS_EHIP from a compute call (a launch failed part
+ *     way) the call's output buffers are undefined and the context keeps the
+ *     deferred state it had before the call.
  *     d == 0 is a valid empty problem: calls validate and return APMS_OK.
  *   - There is no CPU fallback.  A context created with APMS_DEVICE_NONE only
  *     validates: every compute call returns APMS_ENODEV once its arguments
@@ -59,7 +62,8 @@ typedef enum apms_status {
     APMS_EHIP = -5,    /* a HIP call failed; see apms_last_hip_error */
     APMS_ENODEV = -6,  /* validation-only context: arguments are fine, nothing can run */
     APMS_EALIAS = -7,  /* two array arguments overlap */
-    APMS_ESTATE = -8   /* the call would lose or read state that is pending in deferred form */
+    APMS_ESTATE = -8   /* the call would lose or read state that is pending in deferred form, or a top-k
+                          call found no scratch reserved for its K (apms_topk_reserve) */
 } apms_status;
 
 #define APMS_DEVICE_NONE (-1)
@@ -94,14 +98,14 @@ typedef struct apms_plan {
     int64_t scratch_bytes;              /* device memory owned by the context */
     int32_t occupancy_pad[8];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_*;
                                            entries past APMS_KERNEL_COUNT are 0 */
-    int64_t topk_scratch_bytes;         /* further device memory the apms_topk_* calls have allocated */
+    int64_t topk_scratch_bytes;         /* further device memory apms_topk_reserve has allocated */
 } apms_plan;
 
 /*
  * Create a context for vectors of d elements, n workers and chunks of
  * chunk_elems elements on HIP device `device` (or APMS_DEVICE_NONE).  The
  * context owns its device scratch (binary64 norm partials, pending scales: a few MB,
- * see apms_plan.scratch_bytes; the top-k calls add theirs on first use, see below).
+ * see apms_plan.scratch_bytes; apms_topk_reserve adds the top-k selection's, see below).
  * Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
  */
 int apms_create(apms_ctx **out, int64_t d, int32_t n, int64_t chunk_elems, int device);
@@ -290,12 +294,15 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
  * index is kept first (the paper is silent; this makes the result unique).  The wire form of a chunk is
  * K (index, value) pairs, indices local to the chunk and ascending; the selection is exact.
  * These calls are eager (no deferral) and return ESTATE while the 1-bit path has a buffer pending;
- * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31.
- * The first of them on a context allocates the selection's scratch: histograms, per-tile counts and, per
- * 4096-element tile, 64 to 512 slots of 8 bytes for the elements near or above the threshold (256 slots,
- * n*d/2 bytes in all, when K is 1 % of chunk_elems).  That synchronises the device; ENOMEM if it fails.
- * Later calls allocate nothing unless K has grown enough to ask for more slots per tile, in which case the
- * slots are allocated again.  apms_plan.topk_scratch_bytes is what is allocated at the moment.
+ * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31 or K > 2^31 - 1.
+ *
+ * apms_topk_reserve(ctx, K_max) is the set-up call that allocates the selection's scratch, sized for calls
+ * with K <= K_max: histograms, per-tile counts and, per 4096-element tile, 64 to 512 slots of 8 bytes for the
+ * elements near or above the threshold (256 slots, n*d/2 bytes in all, when K_max is 1 % of chunk_elems).
+ * It allocates (ENOMEM if that fails) and synchronises the device; calling it again with a K_max the scratch
+ * already covers does nothing, with a larger one it frees and allocates the slots again.
+ * apms_plan.topk_scratch_bytes is what is allocated at the moment.  The three compute calls allocate
+ * nothing and do not synchronise: they return ESTATE if the scratch was not reserved for their K.
  *
  * apms_topk_compress:       u = (fl(beta*m_i) + fl(fl(1-beta)*g_i)) + delta_i ;  (idx, val) <- C[u] ;
  *                           delta_i <- u - C[u]  (zero where kept, u elsewhere)
@@ -307,6 +314,7 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
  *                           x <- x - lr * ( m / (sqrt(v) + eps) )
  *     sidx, sval [C][K], v [d] in;  x [d] in/out;  m [n][d] out.
  */
+int apms_topk_reserve(apms_ctx *ctx, int64_t K_max);
 int apms_topk_compress(apms_ctx *ctx, const float *m, const float *g, float *worker_err, uint32_t *idx,
                        float *val, int64_t K, float beta, void *stream);
 int apms_topk_server_reduce(apms_ctx *ctx, const uint32_t *idx, const float *val, int64_t K, float *server_err,

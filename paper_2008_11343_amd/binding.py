@@ -31,7 +31,7 @@ EXPORTS = (
     "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
     "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
     "apms_compress_gradient", "apms_apply_gradient",
-    "apms_topk_compress", "apms_topk_server_reduce", "apms_topk_apply",
+    "apms_topk_reserve", "apms_topk_compress", "apms_topk_server_reduce", "apms_topk_apply",
 )
 
 
@@ -70,12 +70,20 @@ def library_path() -> str:
     return _build.LIB
 
 
+def _stale() -> bool:
+    """True if libapms.so is missing or older than any of its sources."""
+    if not os.path.exists(_build.LIB):
+        return True
+    built = os.path.getmtime(_build.LIB)
+    return any(os.path.getmtime(src) > built for src in _build.source_files() if os.path.exists(src))
+
+
 def load():
-    """Load libapms.so (building it first if it has never been built)."""
+    """Load libapms.so, building it first if it is missing or older than a source it is built from."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_build.LIB):
+    if _stale():
         _build.build()
     lib = ctypes.CDLL(_build.LIB)
     vp, i32, i64, f32, ci = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_int
@@ -94,6 +102,7 @@ def load():
         "apms_compress_g16": (ci, [vp, vp, vp, ci, vp, vp, vp, f32, vp]),
         "apms_compress_gradient": (ci, [vp, vp, ci, vp, vp, vp, vp]),
         "apms_apply_gradient": (ci, [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp]),
+        "apms_topk_reserve": (ci, [vp, i64]),
         "apms_topk_compress": (ci, [vp, vp, vp, vp, vp, vp, i64, f32, vp]),
         "apms_topk_server_reduce": (ci, [vp, vp, vp, i64, vp, vp, vp, vp]),
         "apms_topk_apply": (ci, [vp, vp, vp, i64, vp, vp, vp, f32, f32, vp]),
@@ -220,6 +229,10 @@ def apms_compress_gradient(ctx, g, grad_format, worker_err, packed, scales, stre
 def apms_apply_gradient(ctx, spacked, sscales, v, x, m, lr, beta, eps, stream=None):
     _check(ctx, load().apms_apply_gradient(ctx, _ptr(spacked), _ptr(sscales), _ptr(v), _ptr(x), _ptr(m), lr, beta,
                                            eps, _stream(stream)), "apms_apply_gradient")
+
+
+def apms_topk_reserve(ctx, K_max):
+    _check(ctx, load().apms_topk_reserve(ctx, K_max), "apms_topk_reserve")
 
 
 def apms_topk_compress(ctx, m, g, worker_err, idx, val, K, beta, stream=None):

@@ -28,6 +28,13 @@ HIPCC_FLAGS = [
 ]
 
 
+def source_files():
+    """Every file libapms.so is built from (sources, their headers, the C ABI header)."""
+    files = [os.path.join(CSRC, f) for f in sorted(os.listdir(CSRC)) if f.endswith((".hip", ".h"))]
+    files.append(os.path.join(os.path.dirname(HERE), "include", "apms.h"))
+    return files
+
+
 def hipcc() -> str:
     rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
     cand = os.path.join(rocm, "bin", "hipcc")

@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <climits>
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
@@ -29,8 +30,8 @@ struct apms_ctx {
     float* w_pending = nullptr;       // [n*C] scales of the u parked in the worker error buffer
     float* s_pending = nullptr;       // [C]   same for the server error buffer
     float* g_pending = nullptr;       // [C]   server scales of a gather that has not been carried out yet
-    apms::TopkScratch topk = {};                // selection scratch of the top-k compressor, allocated by the
-                                                // first apms_topk_* call
+    apms::TopkScratch topk = {};                // selection scratch of the top-k compressor, allocated by
+                                                // apms_topk_reserve
     int64_t topk_bytes = 0;                     // its size so far
     int64_t scratch_bytes = 0;
     // deferral bookkeeping (host side, follows call order = stream order)
@@ -127,14 +128,17 @@ void free_topk_scratch(apms_ctx* c) {
     c->topk_bytes = 0;
 }
 
-// Allocates the top-k scratch (see TopkScratch) on first use, and the slots again when K asks for more of
-// them per tile than there are.  The device must be current.  Every array is fully written by the kernels
-// before they read it.
-hipError_t ensure_topk_scratch(apms_ctx* c, int64_t K) {
+// Allocates the top-k scratch (see TopkScratch) with slots for K_max kept elements per chunk; called by
+// apms_topk_reserve only (a set-up call: it may allocate, free and synchronise).  The device must be current.
+// Every array is fully written by the kernels before they read it, except guess, which is filled here.
+hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
     const int64_t fixed = pairs * (apms::kTopkBins + apms::kTopkStateWords + 1) * 4 + 2 * tiles * 4;
-    hipError_t e = hipSuccess;
+    const int32_t want = apms::topk_slots_for(K_max, c->L);
+    if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
+    hipError_t e = hipDeviceSynchronize();                     // kernels of earlier calls may still use the scratch
+    if (e != hipSuccess) return e;
     if (!c->topk.hist) {
         e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
@@ -147,29 +151,31 @@ hipError_t ensure_topk_scratch(apms_ctx* c, int64_t K) {
         }
         c->topk_bytes = fixed;
     }
-    const int32_t want = apms::topk_slots_for(K, c->L);
-    if (!c->topk.slots || c->topk.slots_per_tile < want) {
-        if (c->topk.slots) {
-            e = hipDeviceSynchronize();                        // kernels of earlier calls may still read them
-            if (e == hipSuccess) e = hipFree(c->topk.slots);
-            c->topk.slots = nullptr;
-            c->topk.slots_per_tile = 0;
-            c->topk_bytes = fixed;
-            if (e != hipSuccess) return e;
-        }
-        const int64_t bytes = tiles * want * static_cast<int64_t>(sizeof(uint2));
-        e = hipMalloc(reinterpret_cast<void**>(&c->topk.slots), bytes);
-        if (e != hipSuccess) {
-            c->topk.slots = nullptr;
-            return e;
-        }
-        // no guess to go by: the slots' size decides how low a guess may be without overflowing them
-        e = hipMemset(c->topk.guess, 0xFF, pairs * 4);
+    if (c->topk.slots) {
+        e = hipFree(c->topk.slots);
+        c->topk.slots = nullptr;
+        c->topk.slots_per_tile = 0;
+        c->topk_bytes = fixed;
         if (e != hipSuccess) return e;
-        c->topk.slots_per_tile = want;
-        c->topk_bytes = fixed + bytes;
     }
+    const int64_t bytes = tiles * want * static_cast<int64_t>(sizeof(uint2));
+    e = hipMalloc(reinterpret_cast<void**>(&c->topk.slots), bytes);
+    if (e != hipSuccess) {
+        c->topk.slots = nullptr;
+        return e;
+    }
+    // no guess to go by: the slots' size decides how low a guess may be without overflowing them
+    e = hipMemset(c->topk.guess, 0xFF, pairs * 4);
+    if (e == hipSuccess) e = hipDeviceSynchronize();           // the fill is on the null stream: done before any caller stream goes on
+    if (e != hipSuccess) return e;
+    c->topk.slots_per_tile = want;
+    c->topk_bytes = fixed + bytes;
     return hipSuccess;
+}
+
+// A top-k compute call may run only on scratch that apms_topk_reserve sized for at least this K.
+bool topk_reserved_for(const apms_ctx* c, int64_t K) {
+    return c->topk.slots != nullptr && c->topk.slots_per_tile >= apms::topk_slots_for(K, c->L);
 }
 
 void free_scratch(apms_ctx* c) {
@@ -211,7 +217,7 @@ const char* apms_strerror(int status) {
         case APMS_EHIP: return "a HIP call failed (see apms_last_hip_error)";
         case APMS_ENODEV: return "validation-only context: no device to run on";
         case APMS_EALIAS: return "array arguments overlap";
-        case APMS_ESTATE: return "the call would lose or read state that is pending in deferred form; call apms_finalize first";
+        case APMS_ESTATE: return "the context is not in a state for this call: a buffer is pending in deferred form (call apms_finalize first), or the top-k scratch was not reserved for this K (call apms_topk_reserve)";
         default: return "unknown apms status";
     }
 }
@@ -421,22 +427,20 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
                                          grad_format, worker_err, packed, c->w_partials, prev,
                                          gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
                                          beta, 1.0f - beta, c->lds_pad[APMS_KERNEL_COMPRESS], s);
+    if (e == hipSuccess)
+        e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
+                                c->w_pending, s);
+    const bool eager = !(c->deferral & APMS_DEFER_ERRORS);
+    if (e == hipSuccess && eager)
+        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
     if (e != hipSuccess) return hip_fail(c, e);
-    // from here on m holds the gathered momentum (unless implicit), the error buffer holds u and the
-    // context its scales
+    // every launch of the call is queued: m holds the gathered momentum (unless implicit); deferred, the
+    // error buffer holds u and the context its scales
     if (gather) {
         c->pending_m = nullptr;
         c->pending_spacked = nullptr;
     }
-    c->pending_werr = worker_err;
-    e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
-                            c->w_pending, s);
-    if (e != hipSuccess) return hip_fail(c, e);
-    if (!(c->deferral & APMS_DEFER_ERRORS)) {
-        e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
-        if (e != hipSuccess) return hip_fail(c, e);
-        c->pending_werr = nullptr;
-    }
+    c->pending_werr = eager ? nullptr : worker_err;
     return APMS_OK;
 }
 
@@ -509,15 +513,12 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     hipError_t e = apms::launch_server_reduce(geo, c->s_tiles_per_block, c->s_blocks_per_chunk, packed, scales,
                                               server_err, spacked, c->s_partials, prev, inv_n,
                                               c->lds_pad[APMS_KERNEL_SERVER], s);
-    if (e != hipSuccess) return hip_fail(c, e);
-    c->pending_serr = server_err;
-    e = apms::launch_scales(c->C, c->s_blocks_per_chunk, c->L, c->s_partials, sscales, c->s_pending, s);
-    if (e != hipSuccess) return hip_fail(c, e);
-    if (!(c->deferral & APMS_DEFER_ERRORS)) {
+    if (e == hipSuccess) e = apms::launch_scales(c->C, c->s_blocks_per_chunk, c->L, c->s_partials, sscales, c->s_pending, s);
+    const bool eager = !(c->deferral & APMS_DEFER_ERRORS);
+    if (e == hipSuccess && eager)
         e = apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
-        if (e != hipSuccess) return hip_fail(c, e);
-        c->pending_serr = nullptr;
-    }
+    if (e != hipSuccess) return hip_fail(c, e);
+    c->pending_serr = eager ? nullptr : server_err;          // only once every launch of the call is queued
     return APMS_OK;
 }
 
@@ -567,7 +568,20 @@ int apms_apply_gradient(apms_ctx* c, const uint32_t* spacked, const float* sscal
 static int topk_shape_ok(const apms_ctx* c, int64_t K) {
     if (c->L > (int64_t{1} << 31)) return APMS_ESHAPE;        // chunk-local indices are 32-bit
     if (K < 1 || K > c->L) return APMS_EINVAL;
+    if (K > INT32_MAX) return APMS_ESHAPE;                    // list positions are 32-bit in the kernels
     return APMS_OK;
+}
+
+int apms_topk_reserve(apms_ctx* c, int64_t K_max) {
+    if (!c) return APMS_EINVAL;
+    if (c->d > 0)
+        if (int rc = topk_shape_ok(c, K_max)) return rc;
+    int status;
+    if (!ready_to_launch(c, &status)) return status;
+    DeviceScope scope(c->device);
+    if (scope.err != hipSuccess) return hip_fail(c, scope.err);
+    const hipError_t e = reserve_topk_scratch(c, K_max);
+    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
 int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worker_err, uint32_t* idx, float* val,
@@ -584,9 +598,8 @@ int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worke
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = ensure_topk_scratch(c, K);
-    if (e == hipSuccess)
-        e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
+    if (!topk_reserved_for(c, K)) return APMS_ESTATE;
+    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
                                        static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
@@ -604,9 +617,8 @@ int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, 
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = ensure_topk_scratch(c, K);
-    if (e == hipSuccess)
-        e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
+    if (!topk_reserved_for(c, K)) return APMS_ESTATE;
+    hipError_t e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
                                             1.0f / static_cast<float>(c->n), c->topk,
                                             static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
@@ -626,9 +638,8 @@ int apms_topk_apply(apms_ctx* c, const uint32_t* sidx, const float* sval, int64_
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
-    hipError_t e = ensure_topk_scratch(c, K);
-    if (e == hipSuccess)
-        e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps, c->topk,
+    if (!topk_reserved_for(c, K)) return APMS_ESTATE;
+    hipError_t e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps, c->topk,
                                     static_cast<hipStream_t>(stream));
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }

@@ -209,8 +209,9 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ 
 // order, add the server error, re-compress.
 // ------------------------------------------------------------------------
 
-// kWide: the tile is full and its sign words are 16-byte aligned (chunk lengths that are multiples of 128),
-// so a group's ROWS = 4 consecutive words are taken as one 128-bit load.
+// kWide: the tile is full and its sign words are 16-byte aligned in EVERY worker's stream (chunk base and
+// vector length both multiples of 128 elements), so a group's ROWS = 4 consecutive words are taken as one
+// 128-bit load.
 template <bool kFull, bool kWide>
 __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
                                             const float* __restrict__ scales, float* __restrict__ serr,
@@ -295,7 +296,8 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
     for (int32_t t = t0; t < t1; ++t) {
         const int64_t tile_off = static_cast<int64_t>(t) * kServerTile;
         if (tile_off + kServerTile <= L) {
-            if (((chunk * L) & 127) == 0)                      // tile offsets are multiples of 128 anyway
+            // tile offsets are multiples of 128 anyway; worker i's words start at i * d / 32
+            if ((((chunk * L) | d) & 127) == 0)
                 server_tile<true, kServerRows == 4>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off,
                                                     lane_off, lane, wave, inv_n, prev_scale, acc);
             else

@@ -170,6 +170,7 @@ class DeviceRun:
             f = dict(dtype=torch.float32, device=self.device)
             self.idx, self.val = torch.zeros(self.n, self.C, K, **i), torch.zeros(self.n, self.C, K, **f)
             self.sidx, self.sval = torch.zeros(self.C, K, **i), torch.zeros(self.C, K, **f)
+            B.apms_topk_reserve(self.ctx, K)        # set-up: sizes the selection's scratch (no-op if it suffices)
         B.apms_topk_compress(self.ctx, self.m, g, self.werr, self.idx, self.val, K, beta, stream)
         B.apms_topk_server_reduce(self.ctx, self.idx, self.val, K, self.serr, self.sidx, self.sval, stream)
         B.apms_topk_apply(self.ctx, self.sidx, self.sval, K, self.v, self.x, self.m, lr, eps, stream)

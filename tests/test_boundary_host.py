@@ -181,6 +181,27 @@ def test_topk_entry_points(ctx):
     assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, m, 1e-4, 1e-8) == B.APMS_ENODEV
     assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, x, 1e-4, 1e-8) == B.APMS_EALIAS
     assert status_of(B.apms_topk_apply, ctx, idx, val, 40, g, x, m, float("nan"), 1e-8) == B.APMS_EINVAL
+    # the set-up call that sizes the selection's scratch
+    assert status_of(B.apms_topk_reserve, ctx, 40) == B.APMS_ENODEV
+    assert status_of(B.apms_topk_reserve, ctx, 0) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_reserve, ctx, 4097) == B.APMS_EINVAL
+    assert status_of(B.apms_topk_reserve, None, 40) == B.APMS_EINVAL
+
+
+def test_topk_list_positions_must_fit_32_bits():
+    """K = chunk_elems = 2^31 passes the range check on K but not the kernels' 32-bit list positions."""
+    big = 1 << 31
+    c = B.apms_create(d=big, n=1, chunk_elems=big, device=B.APMS_DEVICE_NONE)
+    try:
+        far = [A + i * (1 << 40) for i in range(6)]
+        m, g, e, idx, val, x = far
+        assert status_of(B.apms_topk_reserve, c, big) == B.APMS_ESHAPE
+        assert status_of(B.apms_topk_compress, c, m, g, e, idx, val, big, 0.9) == B.APMS_ESHAPE
+        assert status_of(B.apms_topk_server_reduce, c, idx, val, big, e, m, g) == B.APMS_ESHAPE
+        assert status_of(B.apms_topk_apply, c, idx, val, big, g, x, m, 1e-4, 1e-8) == B.APMS_ESHAPE
+        assert status_of(B.apms_topk_compress, c, m, g, e, idx, val, big - 1, 0.9) == B.APMS_ENODEV
+    finally:
+        B.apms_destroy(c)
 
 
 def test_empty_problem_is_ok_without_a_device():

@@ -4,6 +4,8 @@
 whole chunks (first, last, one seeded pick) through the steps on the very bits the GPU consumes,
 and whole-buffer properties are checked on the device.
 """
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -18,8 +20,28 @@ RTOL, ATOL = 1e-5, 1e-7
 DEV = "cuda:0"
 
 
+_capsys = None
+
+
 def say(msg):
-    print("[fullsize] " + msg, flush=True)
+    """Progress line that reaches the terminal while the test runs (a long full-size case must not look hung)."""
+    if _capsys is not None:
+        with _capsys.disabled():
+            print("[fullsize] " + msg, flush=True)
+    else:
+        print("[fullsize] " + msg, flush=True)
+
+
+@pytest.fixture(autouse=True)
+def _progress_and_oracle_threads(capsys):
+    """The oracle follows whole chunks of up to 21 M elements x 16 workers for up to 100 steps: let it spread its
+    independent work over the host's cores (same bits for any thread count, pinned in test_oracle_pins.py)."""
+    global _capsys
+    _capsys = capsys
+    oracle.set_threads(min(16, oracle.host_cores()))
+    yield
+    oracle.set_threads(1)
+    _capsys = None
 
 
 def words(t):
@@ -95,5 +117,115 @@ def test_sampled_chunks_at_full_size(wl, steps):
             osts[k].step(gk, wl.beta, wl.lr, wl.eps)
             check_chunk(run, osts[k], k, L, "%s step %d chunk %d" % (wl.name, step, k), errors=last)
     say("%s: whole-buffer properties" % wl.name)
+    whole_buffer_properties(run, wl.name)
+    run.close()
+
+
+def chunk_state(run, k):
+    """Oracle state of chunk k alone, from the bits the GPU run starts with."""
+    L = run.L
+    sl = slice(k * L, (k + 1) * L)
+    return oracle.State(L, run.n, L, run.x[sl].cpu().numpy(), run.m[:, sl].cpu().numpy(), run.v[sl].cpu().numpy())
+
+
+def follow_chunks(wl, run, osts, first_step, steps, tag):
+    """`steps` compressed steps on the GPU (deferred mode) with the oracle following the chunks in `osts`
+    ({chunk index: oracle.State}) on the same gradient bits; every step compares sign words, scales and x, the
+    last one (after apms_finalize) also both errors and the momentum."""
+    L, g = run.L, run.g
+    for step in range(steps):
+        W.device_grad_(wl, first_step + step, g)
+        run.step(g, wl.beta, wl.lr, wl.eps)
+        last = step == steps - 1
+        if last:
+            run.finalize()
+        torch.cuda.synchronize()
+        for k, ost in osts.items():
+            gk = np.ascontiguousarray(g[:, k * L:(k + 1) * L].cpu().numpy())
+            ost.step(gk, wl.beta, wl.lr, wl.eps)
+            check_chunk(run, ost, k, L, "%s step %d chunk %d" % (tag, step, k), errors=last)
+        if step % 10 == 9 or last:
+            say("%s: %d of %d steps match on chunks %s" % (tag, step + 1, steps, sorted(osts)))
+
+
+def test_headline_size_many_chunks_full_step_count():
+    """The headline buffer cut into 5188 chunks of 2^16 (the chunk is the unit of scale and of server ownership;
+    Algorithm 1 line 7 uses d/n, the small benchmark case 2^16): ALL 50 steps of the configuration, the oracle on
+    six chunks including the first and the last."""
+    wl = dataclasses.replace(W.BERT_LARGE, chunk=1 << 16, name="bert-large-flat-chunk65536")
+    d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    say("%s: d_pad=%d n=%d chunk=%d (%d chunks), %d steps" % (wl.name, d, n, L, C, wl.steps))
+    run = DeviceRun(d, n, L, DEV, deferred=True, grad_dtype=torch.float32)
+    W.device_state_(wl, dict(x=run.x, m=run.m, v=run.v, werr=run.werr, serr=run.serr))
+    rng = np.random.default_rng(W.BASE_SEED + 100 + wl.index)
+    picks = sorted({0, 1, C - 1, C // 16, *(int(v) for v in rng.integers(2, C - 1, 2))})   # C // 16: a slice border
+    osts = {k: chunk_state(run, k) for k in picks}
+    follow_chunks(wl, run, osts, 0, wl.steps, wl.name)
+    whole_buffer_properties(run, wl.name)
+    run.close()
+
+
+@pytest.mark.parametrize("wl", [W.BERT_BASE, W.WORKER_SCALING], ids=lambda w: w.name)
+def test_one_chunk_full_step_count(wl):
+    """Error feedback (Section 3.1) only shows once the errors have grown to the size of the scales: one seeded
+    chunk of d_pad / n elements followed by the oracle through the configuration's whole step count."""
+    d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    k = int(np.random.default_rng(W.BASE_SEED + 200 + wl.index).integers(0, C))
+    say("%s: d_pad=%d n=%d chunk=%d, %d steps, oracle on chunk %d" % (wl.name, d, n, L, wl.steps, k))
+    run = DeviceRun(d, n, L, DEV, deferred=True, grad_dtype=torch.float32)
+    W.device_state_(wl, dict(x=run.x, m=run.m, v=run.v, werr=run.werr, serr=run.serr))
+    follow_chunks(wl, run, {k: chunk_state(run, k)}, 0, wl.steps, wl.name)
+    run.close()
+
+
+def test_full_pipeline_at_full_size():
+    """The 391-tensor BERT-Large bucket at its real size: 20 Adam warm-up steps on the averaged gradients
+    (Section 3.2; Algorithm 1 line 2), the hand-over (line 3), then the 80 compressed steps.  The warm-up is
+    elementwise, so the oracle follows element ranges: the whole last chunk (it holds the padded tail, six
+    LayerNorm tensors and the pooler) and short ranges that straddle the first LayerNorm tensor's borders and a
+    chunk border; the last chunk is then followed through every compressed step."""
+    wl = W.FULL_PIPELINE
+    d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    lr_warm = 1e-3
+    say("%s: d_pad=%d (d=%d) n=%d chunk=%d, %d warm-up + %d compressed steps" %
+        (wl.name, d, wl.d, n, L, wl.warmup_steps, wl.steps))
+    run = DeviceRun(d, n, L, DEV, deferred=True, grad_dtype=torch.float32)
+    W.device_state_(wl, dict(x=run.x, m=run.m[0], v=run.v), warm_start=True)
+    ln0, ln0_size = wl.layernorm_segments()[0]
+    k = C - 1
+    ranges = {"last chunk": (k * L, d), "LayerNorm start": (ln0 - 64, ln0 + 64),
+              "LayerNorm end": (ln0 + ln0_size - 64, ln0 + ln0_size + 64), "chunk border": (L - 96, L + 96)}
+    assert wl.d < d and k * L < wl.d, "the last chunk must hold real parameters and padding"
+    assert any(k * L <= off < wl.d for off, _ in wl.layernorm_segments())
+    host = {name: [run.x[a:b].cpu().numpy().copy(), np.zeros(b - a, np.float32), np.zeros(b - a, np.float32)]
+            for name, (a, b) in ranges.items()}
+    g = run.g
+    for t in range(1, wl.warmup_steps + 1):
+        W.device_grad_(wl, t - 1, g)
+        run.warmup_step(g, lr_warm, wl.beta, wl.beta2, wl.eps, t)
+        torch.cuda.synchronize()
+        for name, (a, b) in ranges.items():
+            x, m, v = host[name]
+            gr = np.ascontiguousarray(g[:, a:b].cpu().numpy())
+            oracle.warmup_step(b - a, n, x, m, v, gr, lr_warm, wl.beta, wl.beta2, wl.eps, t)
+        if t % 5 == 0:
+            for name, (a, b) in ranges.items():
+                x, m, v = host[name]
+                for what, dev_t, ref in (("x", run.x, x), ("m", run.m[0], m), ("v", run.v, v)):
+                    # v is a sum of squares of order 1e-6 and smaller: relative agreement is what counts
+                    np.testing.assert_allclose(dev_t[a:b].cpu().numpy(), ref, rtol=RTOL, atol=0.0 if what == "v" else ATOL,
+                                               err_msg="warm-up step %d, %s, %s" % (t, name, what))
+            say("%s: %d of %d warm-up steps match on %s" % (wl.name, t, wl.warmup_steps, sorted(ranges)))
+    run.freeze()
+    torch.cuda.synchronize()
+    a, b = ranges["last chunk"]
+    x, m, v = host["last chunk"]
+    mm, werr, serr = np.empty((n, L), np.float32), np.ones((n, L), np.float32), np.ones(L, np.float32)
+    oracle.freeze(L, n, m, mm, werr, serr)
+    for i in (0, 1, n - 1):
+        np.testing.assert_array_equal(run.m[i, a:b].cpu().numpy(), run.m[0, a:b].cpu().numpy())
+    assert float(run.werr.abs().max()) == 0.0 and float(run.serr.abs().max()) == 0.0
+    ost = oracle.State(L, n, L, x, mm, v, werr, serr)
+    follow_chunks(wl, run, {k: ost}, wl.warmup_steps, wl.steps, wl.name)
     whole_buffer_properties(run, wl.name)
     run.close()

@@ -198,6 +198,7 @@ def test_topk_more_tiles_than_the_full_pass_grid():
     sidx, sval = torch.zeros(C, K, dtype=torch.int32, device=DEV), z(C, K)
     ctx = B.apms_create(d, n, L, 0)
     try:
+        B.apms_topk_reserve(ctx, K)
         for call in range(2):                                 # the second call starts from the first one's guess
             say("4200 tiles, call %d" % call)
             werr.copy_(dev(u.reshape(n, d)))
@@ -275,6 +276,47 @@ def test_topk_refused_while_onebit_state_is_pending():
     run.step_topk(g, K, 0.9, 1e-4, 1e-8)
     torch.cuda.synchronize()
     run.close()
+
+
+def test_topk_calls_need_reserved_scratch():
+    """The compute calls allocate nothing: without apms_topk_reserve, or with a K beyond what was reserved,
+    they answer ESTATE and queue nothing; after reserving they run."""
+    n, L, C = 2, 4096 * 8, 2
+    d = L * C
+    z = lambda *shape, dt=torch.float32: torch.zeros(*shape, dtype=dt, device=DEV)
+    m, g, werr, serr, v, x = z(n, d), z(n, d), z(n, d), z(d), z(d) + 1.0, z(d)
+    g.normal_(0.0, 1e-2, generator=torch.Generator(device=DEV).manual_seed(5))
+    ctx = B.apms_create(d, n, L, 0)
+    try:
+        def lists(K):
+            return z(n, C, K, dt=torch.int32), z(n, C, K), z(C, K, dt=torch.int32), z(C, K)
+        K = 300
+        idx, val, sidx, sval = lists(K)
+        for call in (lambda: B.apms_topk_compress(ctx, m, g, werr, idx, val, K, 0.9),
+                     lambda: B.apms_topk_server_reduce(ctx, idx, val, K, serr, sidx, sval),
+                     lambda: B.apms_topk_apply(ctx, sidx, sval, K, v, x, m, 1e-4, 1e-8)):
+            with pytest.raises(B.ApmsError) as ei:
+                call()
+            assert ei.value.status == B.APMS_ESTATE
+        assert B.apms_get_plan(ctx)["topk_scratch_bytes"] == 0
+        B.apms_topk_reserve(ctx, K)
+        reserved = B.apms_get_plan(ctx)["topk_scratch_bytes"]
+        assert reserved > 0
+        B.apms_topk_compress(ctx, m, g, werr, idx, val, K, 0.9)
+        B.apms_topk_reserve(ctx, K // 2)                      # covered already: nothing changes
+        assert B.apms_get_plan(ctx)["topk_scratch_bytes"] == reserved
+        big = L // 4                                          # asks for more slots per tile than K = 300 did
+        bidx, bval, _, _ = lists(big)
+        with pytest.raises(B.ApmsError) as ei:
+            B.apms_topk_compress(ctx, m, g, werr, bidx, bval, big, 0.9)
+        assert ei.value.status == B.APMS_ESTATE
+        B.apms_topk_reserve(ctx, big)
+        assert B.apms_get_plan(ctx)["topk_scratch_bytes"] > reserved
+        B.apms_topk_compress(ctx, m, g, werr, bidx, bval, big, 0.9)
+        torch.cuda.synchronize()
+        assert int(bidx.max()) < L and bool((bidx[:, :, 1:] > bidx[:, :, :-1]).all())
+    finally:
+        B.apms_destroy(ctx)
 
 
 def test_topk_full_size_sampled_chunk():
