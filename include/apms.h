@@ -62,8 +62,9 @@ typedef enum apms_status {
     APMS_EHIP = -5,    /* a HIP call failed; see apms_last_hip_error */
     APMS_ENODEV = -6,  /* validation-only context: arguments are fine, nothing can run */
     APMS_EALIAS = -7,  /* two array arguments overlap */
-    APMS_ESTATE = -8   /* the call would lose or read state that is pending in deferred form, or a top-k
+    APMS_ESTATE = -8,  /* the call would lose or read state that is pending in deferred form, or a top-k
                           call found no scratch reserved for its K (apms_topk_reserve) */
+    APMS_ELIMIT = -9   /* the problem is larger than a fixed-size resource of the call (apms_server_reduce_static) */
 } apms_status;
 
 #define APMS_DEVICE_NONE (-1)
@@ -252,6 +253,28 @@ int apms_compress_g16(apms_ctx *ctx, float *m, const uint16_t *g, int grad_forma
  */
 int apms_server_reduce(apms_ctx *ctx, const uint32_t *packed, const float *scales,
                        float *server_err, uint32_t *spacked, float *sscales, void *stream);
+
+/*
+ * apms_server_reduce for callers that cannot allocate device memory or hold a context: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments (plus the geometry a
+ * context would carry), same kernels and same results, bit for bit, as apms_server_reduce on a newly
+ * created context in eager mode: server_err, spacked and sscales are final when the queued work ends.
+ * The binary64 norm partials go to a fixed array of APMS_STATIC_SCRATCH_BYTES that is part of the library's
+ * device image (each GPU the library runs on holds its own copy until the process ends); nothing is
+ * allocated, freed or synchronised by the call.
+ *   - Runs on the calling thread's CURRENT HIP device; every array must live on it.
+ *   - APMS_ELIMIT if the partials do not fit: ceil(chunk_elems / 16384) * (d / chunk_elems) * 8 bytes
+ *     must not exceed APMS_STATIC_SCRATCH_BYTES (d up to 2^31 elements with chunks of 16384 and more).
+ *   - The address of the array is looked up once per device, by apms_create on that device or else by the
+ *     first call of this function there: under graph capture, make sure one of the two has happened before.
+ *   - Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (different
+ *     streams, no ordering between them) race.  Calls ordered on one stream are fine.
+ * Errors: EINVAL, ESHAPE, EALIGN, EALIAS as for apms_create + apms_server_reduce; ELIMIT; EHIP.
+ */
+#define APMS_STATIC_SCRATCH_BYTES (1 << 20)
+int apms_server_reduce_static(int64_t d, int32_t n, int64_t chunk_elems, const uint32_t *packed,
+                              const float *scales, float *server_err, uint32_t *spacked, float *sscales,
+                              void *stream);
 
 /*
  * Gather + model update (Algorithm 1 lines 10-11; supplement step 3):

@@ -15,9 +15,10 @@ import torch  # first: libapms must bind to the HIP runtime torch has already lo
 from . import build as _build
 
 APMS_OK = 0
-APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS_EALIAS, APMS_ESTATE = (
-    -1, -2, -3, -4, -5, -6, -7, -8)
+APMS_EINVAL, APMS_EALIGN, APMS_ESHAPE, APMS_ENOMEM, APMS_EHIP, APMS_ENODEV, APMS_EALIAS, APMS_ESTATE, APMS_ELIMIT = (
+    -1, -2, -3, -4, -5, -6, -7, -8, -9)
 APMS_DEVICE_NONE = -1
+APMS_STATIC_SCRATCH_BYTES = 1 << 20
 APMS_GRAD_F16 = 1
 APMS_GRAD_BF16 = 2
 APMS_DEFER_ERRORS = 1
@@ -32,6 +33,7 @@ EXPORTS = (
     "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
     "apms_compress_gradient", "apms_apply_gradient",
     "apms_topk_reserve", "apms_topk_compress", "apms_topk_server_reduce", "apms_topk_apply",
+    "apms_server_reduce_static",
 )
 
 
@@ -103,6 +105,7 @@ def load():
         "apms_compress_gradient": (ci, [vp, vp, ci, vp, vp, vp, vp]),
         "apms_apply_gradient": (ci, [vp, vp, vp, vp, vp, vp, f32, f32, f32, vp]),
         "apms_topk_reserve": (ci, [vp, i64]),
+        "apms_server_reduce_static": (ci, [i64, i32, i64, vp, vp, vp, vp, vp, vp]),
         "apms_topk_compress": (ci, [vp, vp, vp, vp, vp, vp, i64, f32, vp]),
         "apms_topk_server_reduce": (ci, [vp, vp, vp, i64, vp, vp, vp, vp]),
         "apms_topk_apply": (ci, [vp, vp, vp, i64, vp, vp, vp, f32, f32, vp]),
@@ -233,6 +236,12 @@ def apms_apply_gradient(ctx, spacked, sscales, v, x, m, lr, beta, eps, stream=No
 
 def apms_topk_reserve(ctx, K_max):
     _check(ctx, load().apms_topk_reserve(ctx, K_max), "apms_topk_reserve")
+
+
+def apms_server_reduce_static(d, n, chunk_elems, packed, scales, server_err, spacked, sscales, stream=None):
+    _check(None, load().apms_server_reduce_static(d, n, chunk_elems, _ptr(packed), _ptr(scales), _ptr(server_err),
+                                                  _ptr(spacked), _ptr(sscales), _stream(stream)),
+           "apms_server_reduce_static")
 
 
 def apms_topk_compress(ctx, m, g, worker_err, idx, val, K, beta, stream=None):

@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdlib>
+#include <mutex>
 #include <new>
 
 #include "apms_launch.h"
@@ -43,7 +44,32 @@ struct apms_ctx {
     int last_hip = 0;
 };
 
+// Scratch of apms_server_reduce_static, the entry point for callers that cannot allocate: one copy per GPU
+// the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the device address static_scratch() returns.
+static __device__ __align__(256) unsigned char scratch[APMS_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, once resolved
+
+// Device address of the static scratch array on `device`, which must be the current device.  Resolved once
+// per device; allocates nothing.
+hipError_t static_scratch(int device, void** out) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return hipSuccess;
+}
 
 // Measured on MI355X: the worker kernel streams best with one tile per (short-lived) workgroup, the
 // server kernel with a few.
@@ -217,6 +243,7 @@ const char* apms_strerror(int status) {
         case APMS_EHIP: return "a HIP call failed (see apms_last_hip_error)";
         case APMS_ENODEV: return "validation-only context: no device to run on";
         case APMS_EALIAS: return "array arguments overlap";
+        case APMS_ELIMIT: return "the problem needs more than the call's fixed-size scratch holds";
         case APMS_ESTATE: return "the context is not in a state for this call: a buffer is pending in deferred form (call apms_finalize first), or the top-k scratch was not reserved for this K (call apms_topk_reserve)";
         default: return "unknown apms status";
     }
@@ -260,6 +287,8 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
         DeviceScope scope(device);
         hipError_t e = scope.err;
         if (e == hipSuccess) e = apms::enable_large_lds_pads();
+        void* unused = nullptr;
+        if (e == hipSuccess) e = static_scratch(device, &unused);   // so that apms_server_reduce_static finds it resolved
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_partials), wp);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_partials), sp);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
@@ -520,6 +549,41 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     if (e != hipSuccess) return hip_fail(c, e);
     c->pending_serr = eager ? nullptr : server_err;          // only once every launch of the call is queued
     return APMS_OK;
+}
+
+int apms_server_reduce_static(int64_t d, int32_t n, int64_t chunk_elems, const uint32_t* packed, const float* scales,
+                              float* server_err, uint32_t* spacked, float* sscales, void* stream) {
+    if (n < 1 || d < 0) return APMS_EINVAL;
+    if (chunk_elems < 32 || chunk_elems % 32 != 0 || d % chunk_elems != 0) return APMS_ESHAPE;
+    const int64_t C = d / chunk_elems;
+    apms::Geometry geo;
+    geo.d = d;
+    geo.L = chunk_elems;
+    geo.n = n;
+    geo.C = static_cast<int32_t>(C);
+    const int64_t tiles = C ? apms::tiles_per_chunk(geo, apms::kServerTile) : 0;
+    const int64_t blocks_per_chunk = (tiles + kDefaultServerTiles - 1) / kDefaultServerTiles;   // a new context's tiling
+    if (C > kMaxGrid || static_cast<int64_t>(n) * C > kMaxGrid || C * blocks_per_chunk > kMaxGrid ||
+        C * ((chunk_elems + apms::kFinalizeTile - 1) / apms::kFinalizeTile) > kMaxGrid)
+        return APMS_ESHAPE;
+    if (C * blocks_per_chunk * static_cast<int64_t>(sizeof(double)) > APMS_STATIC_SCRATCH_BYTES) return APMS_ELIMIT;
+    const int64_t vec = d * 4;
+    const Range r[] = {{packed, vec / 32 * n}, {scales, n * C * 4}, {server_err, vec}, {spacked, vec / 32}, {sscales, C * 4}};
+    if (int rc = check_arrays(r, 5)) return rc;
+    if (d == 0) return APMS_OK;
+    int device = -1;
+    if (hipGetDevice(&device) != hipSuccess) return APMS_EHIP;
+    void* base = nullptr;
+    if (static_scratch(device, &base) != hipSuccess) return APMS_EHIP;
+    double* partials = static_cast<double*>(base);           // every entry is written before it is read
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = apms::launch_server_reduce(geo, kDefaultServerTiles, static_cast<int32_t>(blocks_per_chunk), packed,
+                                              scales, server_err, spacked, partials, nullptr,
+                                              1.0f / static_cast<float>(n), kDefaultLdsPad[APMS_KERNEL_SERVER], s);
+    if (e == hipSuccess)
+        e = apms::launch_scales(C, static_cast<int32_t>(blocks_per_chunk), chunk_elems, partials, sscales, nullptr, s);
+    if (e == hipSuccess) e = apms::launch_finalize(geo, 1, server_err, sscales, kDefaultLdsPad[APMS_KERNEL_FINALIZE], s);
+    return e == hipSuccess ? APMS_OK : APMS_EHIP;
 }
 
 int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const float* v, float* x, float* m,

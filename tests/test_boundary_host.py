@@ -47,8 +47,8 @@ def test_library_exports_every_declared_symbol():
 
 
 def test_strerror_covers_all_codes():
-    texts = {B.apms_strerror(code) for code in range(0, -9, -1)}
-    assert len(texts) == 9 and "unknown apms status" not in texts
+    texts = {B.apms_strerror(code) for code in range(0, -10, -1)}
+    assert len(texts) == 10 and "unknown apms status" not in texts
     assert B.apms_strerror(-99) == "unknown apms status"
 
 
@@ -202,6 +202,24 @@ def test_topk_list_positions_must_fit_32_bits():
         assert status_of(B.apms_topk_compress, c, m, g, e, idx, val, big - 1, 0.9) == B.APMS_ENODEV
     finally:
         B.apms_destroy(c)
+
+
+def test_static_server_reduce_validates_before_touching_the_device():
+    """The context-free entry point checks geometry, its fixed scratch limit and the arrays on the host."""
+    p, sc, e, sp, ssc = (fake(i) for i in range(5))
+    call = B.apms_server_reduce_static
+    assert status_of(call, 8192, 0, 4096, p, sc, e, sp, ssc) == B.APMS_EINVAL
+    assert status_of(call, -32, 1, 32, p, sc, e, sp, ssc) == B.APMS_EINVAL
+    assert status_of(call, 8192, 2, 48, p, sc, e, sp, ssc) == B.APMS_ESHAPE
+    assert status_of(call, 8192, 2, 4096 * 3, p, sc, e, sp, ssc) == B.APMS_ESHAPE
+    assert status_of(call, 8192, 2, 4096, None, sc, e, sp, ssc) == B.APMS_EINVAL
+    assert status_of(call, 8192, 2, 4096, p + 4, sc, e, sp, ssc) == B.APMS_EALIGN
+    assert status_of(call, 8192, 2, 4096, p, sc, e, e + 64, ssc) == B.APMS_EALIAS
+    limit_blocks = B.APMS_STATIC_SCRATCH_BYTES // 8            # binary64 partials the fixed array holds
+    assert status_of(call, (limit_blocks + 1) * 32, 1, 32, p, sc, e, sp, ssc) == B.APMS_ELIMIT
+    assert status_of(call, 0, 3, 64, None, None, None, None, None) == B.APMS_OK
+    header = open(os.path.join(ROOT, "include", "apms.h")).read()
+    assert re.search(r"#define\s+APMS_STATIC_SCRATCH_BYTES\s+\(1 << 20\)", header) and B.APMS_STATIC_SCRATCH_BYTES == 1 << 20
 
 
 def test_empty_problem_is_ok_without_a_device():
