@@ -57,7 +57,8 @@ typedef enum apms_status {
     APMS_OK = 0,
     APMS_EINVAL = -1,  /* null pointer, bad scalar (n < 1, beta outside [0,1), t < 1, ...) */
     APMS_EALIGN = -2,  /* an array pointer is not 16-byte aligned */
-    APMS_ESHAPE = -3,  /* chunk_elems not a positive multiple of 32, or d not a multiple of it */
+    APMS_ESHAPE = -3,  /* chunk_elems not a positive multiple of 32, or d not a multiple of it; n > 4096;
+                          a launch grid or a top-k list position that does not fit 31 bits */
     APMS_ENOMEM = -4,  /* host or device allocation of the context's scratch failed */
     APMS_EHIP = -5,    /* a HIP call failed; see apms_last_hip_error */
     APMS_ENODEV = -6,  /* validation-only context: arguments are fine, nothing can run */
@@ -100,6 +101,12 @@ typedef struct apms_plan {
     int32_t occupancy_pad[8];           /* bytes of unused dynamic LDS per workgroup, by APMS_KERNEL_*;
                                            entries past APMS_KERNEL_COUNT are 0 */
     int64_t topk_scratch_bytes;         /* further device memory apms_topk_reserve has allocated */
+    int32_t gather_mode;                /* APMS_GATHER_*, see apms_set_gather_mode */
+    int32_t gather_choice;              /* the form in use: APMS_GATHER_SPLIT / _FUSED, or -1 while
+                                           APMS_GATHER_AUTO has not decided yet */
+    int32_t gather_uncapped;            /* 1 if APMS_GATHER_AUTO chose the fused form without the occupancy cap */
+    float gather_ms[3];                 /* APMS_GATHER_AUTO: best time it measured for [split, fused with the worker
+                                           kernel capped at two workgroups per CU, fused uncapped] (0 until decided) */
 } apms_plan;
 
 /*
@@ -107,7 +114,8 @@ typedef struct apms_plan {
  * chunk_elems elements on HIP device `device` (or APMS_DEVICE_NONE).  The
  * context owns its device scratch (binary64 norm partials, pending scales: a few MB,
  * see apms_plan.scratch_bytes; apms_topk_reserve adds the top-k selection's, see below).
- * Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE, ENOMEM, EHIP.
+ * Errors: EINVAL (out NULL, n < 1, d < 0), ESHAPE (also n > 4096, or so many chunks or tiles that a
+ * launch grid would pass 2^31 - 1), ENOMEM, EHIP.
  */
 int apms_create(apms_ctx **out, int64_t d, int32_t n, int64_t chunk_elems, int device);
 
@@ -135,7 +143,8 @@ int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t serv
  * Tuning knob: ask for lds_bytes of dynamic LDS per workgroup of one kernel without using it.  LDS is
  * what caps the number of workgroups a compute unit holds at once at no other cost, and these
  * streaming kernels reach their best HBM efficiency with few workgroups in flight per CU.
- * 0 <= lds_bytes <= 160 KB - 256.  Does not change any result.
+ * 0 <= lds_bytes <= 128 KB, or APMS_PAD_AUTO for APMS_KERNEL_COMPRESS (its default: the library
+ * picks by variant of the worker kernel).  Does not change any result.
  */
 #define APMS_KERNEL_COMPRESS 0
 #define APMS_KERNEL_SERVER 1
@@ -143,7 +152,31 @@ int apms_set_tiles_per_block(apms_ctx *ctx, int32_t compress_tiles, int32_t serv
 #define APMS_KERNEL_FINALIZE 3
 #define APMS_KERNEL_WARMUP 4
 #define APMS_KERNEL_COUNT 5
+#define APMS_PAD_AUTO (-1)
 int apms_set_occupancy_pad(apms_ctx *ctx, int kernel, int32_t lds_bytes);
+
+/*
+ * Tuning knob: how the apms_compress that finds a gather pending on m (APMS_DEFER_GATHER) writes the n
+ * momentum slices.  Same bytes moved, same results, bit for bit.
+ *   APMS_GATHER_SPLIT   a fill of its own writes m[n][d], then the worker kernel runs without touching m.
+ *                       Its speed does not depend on where the caller's buffers lie.
+ *   APMS_GATHER_FUSED   the worker kernel writes m itself, next to the error buffer: two write streams in one
+ *                       kernel.  On MI355X about 6 % faster than the split form when m lies in a different
+ *                       third of the HBM address range than worker_err and g, and about 8 % slower when they
+ *                       share one (which is where successive allocations of a new process land).
+ *   APMS_GATHER_AUTO    (default) the context finds out which is faster for the buffers it is given: its
+ *                       first gather runs split, the next six cycle through split / fused / fused without
+ *                       the worker kernel's occupancy cap and are timed with events on the caller's stream,
+ *                       and the first later call that finds those events complete (it never waits) fixes
+ *                       the fastest form for the rest of the context's life; until then, and on a stream
+ *                       under graph capture, the split form is used.
+ *                       apms_plan.gather_choice and gather_ms report the outcome.  Setting a mode again
+ *                       starts this over.
+ */
+#define APMS_GATHER_SPLIT 0
+#define APMS_GATHER_FUSED 1
+#define APMS_GATHER_AUTO 2
+int apms_set_gather_mode(apms_ctx *ctx, int mode);
 
 /*
  * Deferral: software pipelining of two writes across the step boundary.  Results are bit-identical to

@@ -26,10 +26,12 @@ APMS_DEFER_GATHER = 2
 APMS_IMPLICIT_MOMENTUM = 4
 APMS_KERNEL_COMPRESS, APMS_KERNEL_SERVER, APMS_KERNEL_APPLY, APMS_KERNEL_FINALIZE, APMS_KERNEL_WARMUP = 0, 1, 2, 3, 4
 APMS_KERNEL_COUNT = 5
+APMS_PAD_AUTO = -1
+APMS_GATHER_SPLIT, APMS_GATHER_FUSED, APMS_GATHER_AUTO = 0, 1, 2
 
 EXPORTS = (
     "apms_create", "apms_destroy", "apms_strerror", "apms_last_hip_error", "apms_get_plan",
-    "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
+    "apms_set_tiles_per_block", "apms_set_occupancy_pad", "apms_set_gather_mode", "apms_set_deferral", "apms_finalize", "apms_warmup_step",
     "apms_warmup_step_g16", "apms_freeze", "apms_compress", "apms_compress_g16", "apms_server_reduce", "apms_apply",
     "apms_compress_gradient", "apms_apply_gradient",
     "apms_topk_reserve", "apms_topk_compress", "apms_topk_server_reduce", "apms_topk_apply",
@@ -47,11 +49,14 @@ class apms_plan(ctypes.Structure):
         ("server_blocks_per_chunk", ctypes.c_int32), ("server_grid", ctypes.c_int64),
         ("apply_tile_elems", ctypes.c_int32), ("apply_grid", ctypes.c_int64),
         ("scratch_bytes", ctypes.c_int64), ("occupancy_pad", ctypes.c_int32 * 8), ("topk_scratch_bytes", ctypes.c_int64),
+        ("gather_mode", ctypes.c_int32), ("gather_choice", ctypes.c_int32), ("gather_uncapped", ctypes.c_int32),
+        ("gather_ms", ctypes.c_float * 3),
     ]
 
     def as_dict(self):
         out = {name: getattr(self, name) for name, _ in self._fields_}
         out["occupancy_pad"] = list(self.occupancy_pad)[:APMS_KERNEL_COUNT]
+        out["gather_ms"] = list(self.gather_ms)
         return out
 
 
@@ -98,6 +103,7 @@ def load():
         "apms_set_tiles_per_block": (ci, [vp, i32, i32]),
         "apms_set_occupancy_pad": (ci, [vp, ci, i32]),
         "apms_set_deferral": (ci, [vp, ci]),
+        "apms_set_gather_mode": (ci, [vp, ci]),
         "apms_finalize": (ci, [vp, vp, vp, vp, vp]),
         "apms_warmup_step": (ci, [vp, vp, vp, vp, vp, f32, f32, f32, f32, i64, vp]),
         "apms_warmup_step_g16": (ci, [vp, vp, vp, vp, vp, ci, f32, f32, f32, f32, i64, vp]),
@@ -178,6 +184,10 @@ def apms_set_tiles_per_block(ctx, compress_tiles: int = 0, server_tiles: int = 0
 
 def apms_set_occupancy_pad(ctx, kernel: int, lds_bytes: int):
     _check(ctx, load().apms_set_occupancy_pad(ctx, kernel, lds_bytes), "apms_set_occupancy_pad")
+
+
+def apms_set_gather_mode(ctx, mode: int):
+    _check(ctx, load().apms_set_gather_mode(ctx, mode), "apms_set_gather_mode")
 
 
 def apms_set_deferral(ctx, flags: int):

@@ -15,6 +15,11 @@
 #include "apms_launch.h"
 #include "apms_topk.h"
 
+// APMS_GATHER_AUTO: gathers 1..kTuneSamples of a context are timed, cycling through the kTuneForms candidate
+// forms (gather 0 pays for loading the kernels and is left out).
+constexpr int kTuneForms = 3;        // split; fused with the worker kernel's occupancy cap; fused without it
+constexpr int kTuneSamples = 2 * kTuneForms;
+
 struct apms_ctx {
     int64_t d = 0;
     int32_t n = 0;
@@ -41,6 +46,13 @@ struct apms_ctx {
     const void* pending_m = nullptr;          // momentum buffer whose gather is still to be written ...
     const uint32_t* pending_spacked = nullptr;  // ... from these sign words (caller's buffer) and g_pending
     int deferral = 0;                         // APMS_DEFER_* flags
+    int gather_mode = APMS_GATHER_AUTO;       // how a pending gather is carried out by apms_compress
+    // APMS_GATHER_AUTO: the first calls time both forms with events on the caller's stream, read back without
+    // waiting by a later call (see pick_gather_form)
+    hipEvent_t tune_ev[kTuneSamples][2] = {};
+    int tune_calls = 0;                       // gathers carried out so far while undecided
+    int tune_choice = -1;                     // index of the candidate form once decided
+    float tune_ms[kTuneForms] = {};           // best time seen per candidate form (reported by apms_get_plan)
     int last_hip = 0;
 };
 
@@ -76,10 +88,12 @@ hipError_t static_scratch(int device, void** out) {
 constexpr int32_t kDefaultCompressTiles = 1;
 constexpr int32_t kDefaultServerTiles = 4;
 constexpr int64_t kMaxGrid = 0x7fffffff;
-// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize, warm-up).  Measured on MI355X:
-// the worker kernel and the warm-up kernel (n + 3 read streams) stream fastest with 2 workgroups (8 waves)
-// per CU, the small-tile kernels with as many as fit.
-constexpr int32_t kDefaultLdsPad[APMS_KERNEL_COUNT] = {64 * 1024, 0, 0, 0, 64 * 1024};
+// Unused dynamic LDS per workgroup, by kernel (compress, server, apply, finalize, warm-up); APMS_PAD_AUTO for
+// the worker kernel means "by variant": measured on MI355X, the variant that also writes the gathered
+// momentum (two write streams) can gain from 2 workgroups per CU (see gather_form), the variants with one
+// write stream run fastest uncapped.  The warm-up kernel (n + 3 read streams) streams fastest with 2
+// workgroups (8 waves) per CU, the small-tile kernels with as many as fit.
+constexpr int32_t kDefaultLdsPad[APMS_KERNEL_COUNT] = {APMS_PAD_AUTO, 0, 0, 0, 64 * 1024};
 
 struct Range {
     const void* p;
@@ -211,8 +225,65 @@ void free_scratch(apms_ctx* c) {
     if (c->s_pending) (void)hipFree(c->s_pending);
     if (c->g_pending) (void)hipFree(c->g_pending);
     free_topk_scratch(c);
+    for (auto& pair : c->tune_ev)
+        for (hipEvent_t& ev : pair) {
+            if (ev) (void)hipEventDestroy(ev);
+            ev = nullptr;
+        }
     c->w_partials = c->s_partials = nullptr;
     c->w_pending = c->s_pending = c->g_pending = nullptr;
+}
+
+// Candidate forms of a gather-carrying apms_compress: split (0), fused with the worker kernel capped at two
+// workgroups per CU (1), fused uncapped (2).  An occupancy pad set by the caller overrides the cap, which
+// makes 1 and 2 the same.
+struct GatherForm {
+    bool fused;
+    int32_t pad;       // occupancy pad of the worker kernel in this form
+};
+GatherForm gather_form(const apms_ctx* c, int index) {
+    const int32_t set = c->lds_pad[APMS_KERNEL_COMPRESS];
+    if (index == 0) return {false, set != APMS_PAD_AUTO ? set : 0};
+    return {true, set != APMS_PAD_AUTO ? set : (index == 1 ? 64 * 1024 : 0)};
+}
+
+// Index of the form the gather of this call takes and, through *sample, the pair of events to bracket it with
+// (nullptr: do not time it).  In APMS_GATHER_AUTO the context times its gathers 1..kTuneSamples, cycling
+// through the candidate forms, and decides as soon as a later call finds all those events complete; it never
+// waits for them.  A stream under graph capture is neither timed nor queried.
+int pick_gather_form(apms_ctx* c, hipStream_t s, hipEvent_t** sample) {
+    *sample = nullptr;
+    if (c->gather_mode != APMS_GATHER_AUTO) return c->gather_mode == APMS_GATHER_FUSED ? 1 : 0;
+    if (c->tune_choice >= 0) return c->tune_choice;
+    hipStreamCaptureStatus capture = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &capture) != hipSuccess || capture != hipStreamCaptureStatusNone) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    const int call = c->tune_calls++;
+    if (call == 0) return 0;
+    if (call <= kTuneSamples) {
+        *sample = c->tune_ev[call - 1];
+        return (call - 1) % kTuneForms;
+    }
+    float best[kTuneForms] = {};
+    for (int k = 0; k < kTuneSamples; ++k) {
+        float ms = 0.0f;
+        if (hipEventQuery(c->tune_ev[k][1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, c->tune_ev[k][0], c->tune_ev[k][1]) != hipSuccess) {
+            (void)hipGetLastError();                           // not ready yet is no error of this call
+            return 0;                                          // undecided: ask again at the next gather
+        }
+        float& b = best[k % kTuneForms];
+        if (b == 0.0f || ms < b) b = ms;
+    }
+    int choice = 0;
+    for (int f = 0; f < kTuneForms; ++f) {
+        c->tune_ms[f] = best[f];
+        if (best[f] < best[choice]) choice = f;
+    }
+    c->tune_choice = choice;
+    return choice;
 }
 
 // Common tail of validation: empty problem -> OK (done), validation-only context -> ENODEV.
@@ -238,7 +309,7 @@ const char* apms_strerror(int status) {
         case APMS_OK: return "ok";
         case APMS_EINVAL: return "invalid argument (null pointer or scalar out of range)";
         case APMS_EALIGN: return "array pointer is not 16-byte aligned";
-        case APMS_ESHAPE: return "chunk_elems must be a positive multiple of 32 and divide d";
+        case APMS_ESHAPE: return "chunk_elems must be a positive multiple of 32 and divide d; at most 4096 workers; grids and top-k list positions must fit 31 bits";
         case APMS_ENOMEM: return "allocation of the context's scratch failed";
         case APMS_EHIP: return "a HIP call failed (see apms_last_hip_error)";
         case APMS_ENODEV: return "validation-only context: no device to run on";
@@ -254,6 +325,7 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
     *out = nullptr;
     if (n < 1 || d < 0 || (device < 0 && device != APMS_DEVICE_NONE)) return APMS_EINVAL;
     if (chunk_elems < 32 || chunk_elems % 32 != 0 || d % chunk_elems != 0) return APMS_ESHAPE;
+    if (n > apms::kServerMaxWorkers) return APMS_ESHAPE;     // the server kernel stages one scale per worker in LDS
     const int64_t C = d / chunk_elems;
     // every grid must fit a 1-D launch, every (worker, chunk) index an int32: bound them all by the
     // finest tiling any kernel uses
@@ -294,6 +366,8 @@ int apms_create(apms_ctx** out, int64_t d, int32_t n, int64_t chunk_elems, int d
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->w_pending), wq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->s_pending), sq);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->g_pending), sq);
+        for (int k = 0; k < kTuneSamples && e == hipSuccess; ++k)
+            for (int j = 0; j < 2 && e == hipSuccess; ++j) e = hipEventCreate(&c->tune_ev[k][j]);
         if (e != hipSuccess) {
             free_scratch(c);
             delete c;
@@ -334,6 +408,11 @@ int apms_get_plan(const apms_ctx* c, apms_plan* plan) {
     plan->apply_grid = c->C * c->a_tiles_per_chunk * c->n;
     plan->scratch_bytes = c->scratch_bytes;
     plan->topk_scratch_bytes = c->topk_bytes;
+    plan->gather_mode = c->gather_mode;
+    plan->gather_choice = c->gather_mode != APMS_GATHER_AUTO ? c->gather_mode
+                          : c->tune_choice < 0 ? -1 : (c->tune_choice == 0 ? APMS_GATHER_SPLIT : APMS_GATHER_FUSED);
+    plan->gather_uncapped = (c->gather_mode == APMS_GATHER_AUTO && c->tune_choice == 2) ? 1 : 0;
+    for (int f = 0; f < 3; ++f) plan->gather_ms[f] = c->tune_ms[f];
     for (int k = 0; k < 8; ++k) plan->occupancy_pad[k] = k < APMS_KERNEL_COUNT ? c->lds_pad[k] : 0;
     return APMS_OK;
 }
@@ -347,8 +426,18 @@ int apms_set_tiles_per_block(apms_ctx* c, int32_t compress_tiles, int32_t server
 }
 
 int apms_set_occupancy_pad(apms_ctx* c, int kernel, int32_t lds_bytes) {
-    if (!c || kernel < 0 || kernel >= APMS_KERNEL_COUNT || lds_bytes < 0 || lds_bytes > apms::kMaxLdsPad) return APMS_EINVAL;
+    if (!c || kernel < 0 || kernel >= APMS_KERNEL_COUNT || lds_bytes > apms::kMaxLdsPad) return APMS_EINVAL;
+    if (lds_bytes < 0 && !(lds_bytes == APMS_PAD_AUTO && kernel == APMS_KERNEL_COMPRESS)) return APMS_EINVAL;
     c->lds_pad[kernel] = lds_bytes;
+    return APMS_OK;
+}
+
+int apms_set_gather_mode(apms_ctx* c, int mode) {
+    if (!c || (mode != APMS_GATHER_SPLIT && mode != APMS_GATHER_FUSED && mode != APMS_GATHER_AUTO)) return APMS_EINVAL;
+    c->gather_mode = mode;
+    c->tune_calls = 0;                                         // APMS_GATHER_AUTO starts measuring afresh
+    c->tune_choice = -1;
+    for (float& ms : c->tune_ms) ms = 0.0f;
     return APMS_OK;
 }
 
@@ -452,10 +541,26 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
     const int momentum = !with_momentum ? apms::kMomNone : gather ? apms::kMomGather : apms::kMomRead;
     // implicit momentum: the pending gather is consumed without materialising m
     float* m_arg = (gather && (c->deferral & APMS_IMPLICIT_MOMENTUM)) ? nullptr : m;
-    hipError_t e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, momentum, m_arg, g,
-                                         grad_format, worker_err, packed, c->w_partials, prev,
-                                         gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
-                                         beta, 1.0f - beta, c->lds_pad[APMS_KERNEL_COMPRESS], s);
+    hipError_t e = hipSuccess;
+    hipEvent_t* sample = nullptr;
+    int32_t pad = c->lds_pad[APMS_KERNEL_COMPRESS] != APMS_PAD_AUTO ? c->lds_pad[APMS_KERNEL_COMPRESS] : 0;
+    if (gather && m_arg) {
+        const GatherForm form = gather_form(c, pick_gather_form(c, s, &sample));
+        pad = form.pad;
+        if (sample) e = hipEventRecord(sample[0], s);
+        if (e == hipSuccess && !form.fused) {
+            // the n momentum slices as one fill of its own; the worker kernel then leaves m alone
+            e = apms::launch_apply(geo, c->pending_spacked, c->g_pending, nullptr, nullptr, m, nullptr,
+                                   /*write_m=*/true, /*model_step=*/false, 0.0f, 0.0f, c->lds_pad[APMS_KERNEL_APPLY], s);
+            m_arg = nullptr;
+        }
+    }
+    if (e == hipSuccess)
+        e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, momentum, m_arg, g,
+                                  grad_format, worker_err, packed, c->w_partials, prev,
+                                  gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
+                                  beta, 1.0f - beta, pad, s);
+    if (e == hipSuccess && sample) e = hipEventRecord(sample[1], s);
     if (e == hipSuccess)
         e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
                                 c->w_pending, s);
@@ -555,6 +660,7 @@ int apms_server_reduce_static(int64_t d, int32_t n, int64_t chunk_elems, const u
                               float* server_err, uint32_t* spacked, float* sscales, void* stream) {
     if (n < 1 || d < 0) return APMS_EINVAL;
     if (chunk_elems < 32 || chunk_elems % 32 != 0 || d % chunk_elems != 0) return APMS_ESHAPE;
+    if (n > apms::kServerMaxWorkers) return APMS_ESHAPE;
     const int64_t C = d / chunk_elems;
     apms::Geometry geo;
     geo.d = d;

@@ -68,11 +68,20 @@ __device__ __forceinline__ float signed_scale(bool positive, float s) {
     return positive ? s : -s;
 }
 
-// |s| with the sign bit taken from the top bit of t (set = negative): two VALU operations per decoded
-// element (shift + bit-field insert) where compare + select + mask take three.  s is a chunk scale, a
-// square root, hence never negative, so this equals signed_scale(!(t >> 31), s).
+// |s| with the sign bit taken from the top bit of t (set = negative).  s is a chunk scale, a square root,
+// hence never negative, so this equals signed_scale(!(t >> 31), s).
 __device__ __forceinline__ float scale_signed_by_msb(uint32_t t, float s) {
     return __builtin_bit_cast(float, (__builtin_bit_cast(uint32_t, s) & 0x7fffffffu) | (t & 0x80000000u));
+}
+
+// The same as ONE VALU instruction (bit-field insert: magnitude bits from s, sign bit from t), for the server
+// kernel's inner loop, where this runs once per worker and element; written as C++ it compiles to an AND and
+// an OR.  `magnitude_bits` must hold 0x7fffffff; it and s are taken in vector registers because an
+// instruction may read only one value from the scalar side.
+__device__ __forceinline__ float scale_signed_by_msb_bfi(uint32_t magnitude_bits, float s, uint32_t t) {
+    float out;
+    asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(out) : "v"(magnitude_bits), "v"(s), "v"(t));
+    return out;
 }
 
 // Sign nibble of four elements: bit c = (u[c] >= 0), so -0.0 and +0.0 give 1.

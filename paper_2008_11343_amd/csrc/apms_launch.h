@@ -22,6 +22,9 @@ constexpr int kServerTile = tile_elems(kServerRows);
 constexpr int kApplyTile = tile_elems(kApplyRows);
 constexpr int kFinalizeTile = tile_elems(kFinalizeRows);
 
+// Most workers the server kernel takes: their scales of one chunk are staged in LDS (16 KB).
+constexpr int kServerMaxWorkers = 4096;
+
 // Element type of the gradient input (values match APMS_GRAD_* of the C ABI, 0 = binary32).
 constexpr int kGradF32 = 0;
 constexpr int kGradF16 = 1;
@@ -43,7 +46,7 @@ struct Geometry {
 // Dynamic LDS a launch asks for WITHOUT using it: LDS is the one resource that caps how many workgroups
 // a CU holds at once without costing anything else, and on MI355X these streaming kernels reach their
 // best HBM efficiency with few workgroups in flight per CU.
-constexpr int32_t kMaxLdsPad = 160 * 1024 - 256;
+constexpr int32_t kMaxLdsPad = 128 * 1024;     // leaves room for the kernels' own LDS (up to 17 KB) in the CU's 160 KB
 
 // Raise each kernel's dynamic-LDS limit so that pads above 64 KB can be launched (once per process).
 hipError_t enable_large_lds_pads();

@@ -209,12 +209,13 @@ __global__ __launch_bounds__(kThreads) void finalize_kernel(float* __restrict__ 
 // order, add the server error, re-compress.
 // ------------------------------------------------------------------------
 
+// worker_scales[i] is worker i's scale of this chunk (staged in LDS by the kernel).
 // kWide: the tile is full and its sign words are 16-byte aligned in EVERY worker's stream (chunk base and
 // vector length both multiples of 128 elements), so a group's ROWS = 4 consecutive words are taken as one
 // 128-bit load.
 template <bool kFull, bool kWide>
 __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
-                                            const float* __restrict__ scales, float* __restrict__ serr,
+                                            const float* __restrict__ worker_scales, float* __restrict__ serr,
                                             uint32_t* __restrict__ spacked, int64_t d, int64_t L, int32_t C,
                                             int32_t n, int64_t chunk, int64_t tile_off, int lane_off, int lane,
                                             int wave, float inv_n, float prev_scale, double (&acc)[4]) {
@@ -222,6 +223,10 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
     const int64_t chunk_base = chunk * L;                 // inside one [d] vector
     const int64_t off0 = tile_off + lane_off;
     const int shift = 4 * (lane & 7);
+    // element c of a row sits at bit shift + c of the row's sign word: this many places below bit 31
+    uint32_t to_msb[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) to_msb[c] = 31u - static_cast<uint32_t>(shift + c);
     // first of this group's ROWS consecutive words, inside one worker's [d/32] words
     const int64_t w0 = (chunk_base + off0) >> 5;
     const int64_t words_per_worker = d >> 5;
@@ -235,12 +240,11 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
         sum[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
     }
     static_assert(!kWide || (kFull && ROWS == 4), "the wide load covers four full rows");
-    // eight workers' sign words in flight per lane
-#pragma unroll 8
-    for (int32_t i = 0; i < n; ++i) {
-        const float s = scales[static_cast<int64_t>(i) * C + chunk];
+    uint32_t magnitude_bits = 0x7fffffffu;
+    asm("" : "+v"(magnitude_bits));                         // pinned in a vector register for the inserts below
+    // the ROWS sign words worker i holds for this lane's rows
+    auto load_words = [&](int32_t i, uint32_t (&w)[ROWS]) {
         const uint32_t* wp = packed + i * words_per_worker + w0;
-        uint32_t w[ROWS];
         if constexpr (kWide) {
             const u32x4 wq = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wp));
 #pragma unroll
@@ -249,13 +253,35 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
 #pragma unroll
             for (int r = 0; r < ROWS; ++r) w[r] = ok[r] ? wp[r] : 0u;
         }
+    };
+    // One worker's contribution to the running sums, in place.  Three VALU operations per decoded element:
+    // shift the element's sign bit to the top, insert it into the scale as ITS sign (bit set = positive gives
+    // -s), subtract: sum - (-s) = sum + s exactly.
+    auto add_worker = [&](int32_t i, const uint32_t (&w)[ROWS]) {
+        const float s = worker_scales[i];
 #pragma unroll
         for (int r = 0; r < ROWS; ++r) {
-            const uint32_t clear = ~(w[r] >> shift);      // bit c set = element c is negative
 #pragma unroll
             for (int c = 0; c < 4; ++c)
-                sum[r][c] = sum[r][c] + scale_signed_by_msb(clear << (31 - c), s);
+                sum[r][c] = sum[r][c] - scale_signed_by_msb_bfi(magnitude_bits, s, w[r] << to_msb[c]);
         }
+    };
+    // worker order 0 .. n-1; the sign words of a group of workers are requested together
+    constexpr int kGroup = 8;
+    int32_t i = 0;
+#pragma unroll 1
+    for (; i + kGroup <= n; i += kGroup) {
+        uint32_t w[kGroup][ROWS];
+#pragma unroll
+        for (int q = 0; q < kGroup; ++q) load_words(i + q, w[q]);
+#pragma unroll
+        for (int q = 0; q < kGroup; ++q) add_worker(i + q, w[q]);
+    }
+#pragma unroll 1
+    for (; i < n; ++i) {
+        uint32_t w[ROWS];
+        load_words(i, w);
+        add_worker(i, w);
     }
     uint32_t words[ROWS];
 #pragma unroll
@@ -277,16 +303,20 @@ __device__ __forceinline__ void server_tile(const uint32_t* __restrict__ packed,
     if ((lane & 7) == 0) store_group_words<ROWS, kFull>(spacked, w0, words, ok);
 }
 
-__global__ __launch_bounds__(kThreads) void server_kernel(
+__global__ __launch_bounds__(kThreads) __attribute__((amdgpu_waves_per_eu(4, 8))) void server_kernel(
     const uint32_t* __restrict__ packed, const float* __restrict__ scales, float* __restrict__ serr,
     uint32_t* __restrict__ spacked, double* __restrict__ partials, const float* __restrict__ prev_scales,
     int64_t d, int64_t L, int32_t C, int32_t n, int32_t tiles_per_chunk, int32_t tiles_per_block,
     int32_t blocks_per_chunk, float inv_n) {
     __shared__ double lds[kWaves];
+    __shared__ float lds_scales[kServerMaxWorkers];
     const int64_t blk = blockIdx.x;
     const int64_t chunk = blk / blocks_per_chunk;
     const int32_t b = static_cast<int32_t>(blk - chunk * blocks_per_chunk);
     const float prev_scale = prev_scales ? prev_scales[chunk] : 0.0f;
+    // the n scales of this chunk, one per worker (the launcher checked n <= kServerMaxWorkers)
+    for (int32_t i = threadIdx.x; i < n; i += kThreads) lds_scales[i] = scales[static_cast<int64_t>(i) * C + chunk];
+    __syncthreads();
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
     const int lane_off = packing_lane_offset<kServerRows>(wave, lane);
@@ -298,13 +328,13 @@ __global__ __launch_bounds__(kThreads) void server_kernel(
         if (tile_off + kServerTile <= L) {
             // tile offsets are multiples of 128 anyway; worker i's words start at i * d / 32
             if ((((chunk * L) | d) & 127) == 0)
-                server_tile<true, kServerRows == 4>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off,
+                server_tile<true, kServerRows == 4>(packed, lds_scales, serr, spacked, d, L, C, n, chunk, tile_off,
                                                     lane_off, lane, wave, inv_n, prev_scale, acc);
             else
-                server_tile<true, false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane,
+                server_tile<true, false>(packed, lds_scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane,
                                          wave, inv_n, prev_scale, acc);
         } else {
-            server_tile<false, false>(packed, scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
+            server_tile<false, false>(packed, lds_scales, serr, spacked, d, L, C, n, chunk, tile_off, lane_off, lane, wave,
                                       inv_n, prev_scale, acc);
         }
     }

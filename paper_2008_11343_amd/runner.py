@@ -46,18 +46,20 @@ class DeviceRun:
         for t in (self.packed, self.scales, self.spacked, self.sscales):
             t.zero_()
 
-    # MI355X: its 288 GiB of HBM behave as three regions of 96 GiB.  The fused worker kernel writes two
-    # [n][d] streams (momentum, error) and reads two (error, gradient); measured on the chip with
-    # BERT-Large-sized buffers, it runs 10-15 % faster when the momentum lies in a different region than
-    # the error and the gradient than with all three in one (where inside a region a buffer lies, and
-    # address skews, make no difference; buffers of 1 GB do not show the effect).  Where the driver puts
-    # an allocation cannot be asked or steered from here, so `place` finds a good pair by trying.
+    # MI355X: its 288 GiB of HBM behave as three regions of 96 GiB.  The fused form of the gather-carrying
+    # worker kernel writes two [n][d] streams (momentum, error) and reads two (error, gradient); measured on
+    # the chip with BERT-Large-sized buffers, it runs 10-15 % faster when the momentum lies in a different
+    # region than the error and the gradient than with all three in one (where inside a region a buffer
+    # lies, and address skews, make no difference; buffers of 1 GB do not show the effect).  The library's
+    # default (APMS_GATHER_AUTO) copes with any placement by timing its split form against the fused one;
+    # `place` goes one step further and looks for a placement on which the fused form wins.  Where the
+    # driver puts an allocation cannot be asked or steered from here, so it finds one by trying.
     PLACE_MIN_BYTES = 4 << 30          # smaller [n][d] buffers are not worth placing
 
     def _allocate(self, place, grad_dtype):
         """Allocates every buffer of the run.  With `place` (float32 gradients only) further [n][d]
-        buffers are allocated one after the other, the worker kernel is timed with each adjacent pair of
-        them as (worker error, gradient), the fastest pair is kept and the rest freed.  Returns a dict
+        buffers are allocated one after the other, the fused worker kernel is timed with each adjacent pair
+        of them as (worker error, gradient), the fastest pair is kept and the rest freed.  Returns a dict
         that describes what was done (None if nothing was placed)."""
         d, n, dev = self.d, self.n, self.device
         f = dict(dtype=torch.float32, device=dev)
@@ -73,7 +75,8 @@ class DeviceRun:
         self.spacked = torch.empty(d // 32, **i)
         self.sscales = torch.empty(self.C, **f)
         big = n * d * 4
-        if not place or big < self.PLACE_MIN_BYTES or grad_dtype != torch.float32:
+        if (not place or big < self.PLACE_MIN_BYTES or grad_dtype != torch.float32
+                or not self.deferral & B.APMS_DEFER_GATHER):
             return None
         torch.cuda.empty_cache()
         free, _ = torch.cuda.mem_get_info(dev)
@@ -85,7 +88,7 @@ class DeviceRun:
 
         def worker_ms(werr, g):
             best = None
-            for step in range(3):                             # the 1st call of a phase launches another kernel
+            for step in range(3):                             # the 1st call has no gather to carry out
                 a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                 a.record()
                 B.apms_compress(probe, self.m, g, werr, self.packed, self.scales, 0.9)
@@ -100,8 +103,8 @@ class DeviceRun:
             return best
 
         try:
-            if self.deferral:
-                B.apms_set_deferral(probe, self.deferral)          # time what this run's calls will launch
+            B.apms_set_deferral(probe, self.deferral)
+            B.apms_set_gather_mode(probe, B.APMS_GATHER_FUSED)     # the form whose speed depends on the placement
             self.v.fill_(1.0)
             for t in [self.m, self.x, self.serr] + cands:
                 t.zero_()
@@ -110,23 +113,13 @@ class DeviceRun:
             self.werr, self.g = cands[k], cands[k + 1]
             del cands
             torch.cuda.empty_cache()
-            # the occupancy cap of the worker kernel pays where its two write streams share a region and
-            # costs a little where they do not: keep whichever is faster here
-            default_pad = B.apms_get_plan(probe)["occupancy_pad"][B.APMS_KERNEL_COMPRESS]
-            pads = {}
-            for pad in sorted({0, default_pad}):
-                B.apms_set_occupancy_pad(probe, B.APMS_KERNEL_COMPRESS, pad)
-                pads[pad] = worker_ms(self.werr, self.g)
-            pad = min(pads, key=pads.get)
-            B.apms_set_occupancy_pad(self.ctx, B.APMS_KERNEL_COMPRESS, pad)
             torch.cuda.synchronize()
         finally:
             B.apms_destroy(probe)
         return {"policy": "worker error and gradient = the adjacent pair of %d successively allocated buffers that "
-                          "the worker kernel runs fastest on (HBM regions)" % (len(times) + 1),
-                "chosen_pair": k, "worker_kernel_ms_by_pair": [round(t, 3) for t in times],
-                "worker_kernel_ms_by_occupancy_pad": {str(p): round(t, 3) for p, t in pads.items()},
-                "occupancy_pad_compress": pad}
+                          "the fused worker kernel runs fastest on (HBM regions); which form of the kernel then "
+                          "runs is the library's own choice (APMS_GATHER_AUTO)" % (len(times) + 1),
+                "chosen_pair": k, "fused_worker_kernel_ms_by_pair": [round(t, 3) for t in times]}
 
     def close(self):
         if self.ctx is not None:

@@ -56,6 +56,7 @@ def test_strerror_covers_all_codes():
     (8192, 0, 4096, B.APMS_EINVAL),
     (-32, 1, 32, B.APMS_EINVAL),
     (8192, 1, 0, B.APMS_ESHAPE),
+    (8192, 4097, 4096, B.APMS_ESHAPE),     # more workers than the server kernel stages scales for
     (8192, 1, 48, B.APMS_ESHAPE),          # not a multiple of 32
     (8192, 1, 4096 * 3, B.APMS_ESHAPE),    # does not divide d
     (8192, 1, 16, B.APMS_ESHAPE),
@@ -134,6 +135,12 @@ def test_scalar_ranges(ctx):
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 200 * 1024) == B.APMS_EINVAL
     assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, 4096) == B.APMS_OK
     assert B.apms_get_plan(ctx)["occupancy_pad"][B.APMS_KERNEL_APPLY] == 4096
+    # the worker kernel's pad defaults to "by variant"; only that kernel accepts the value
+    assert B.apms_get_plan(ctx)["occupancy_pad"][B.APMS_KERNEL_COMPRESS] == B.APMS_PAD_AUTO
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_COMPRESS, 65536) == B.APMS_OK
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_COMPRESS, B.APMS_PAD_AUTO) == B.APMS_OK
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_APPLY, B.APMS_PAD_AUTO) == B.APMS_EINVAL
+    assert status_of(B.apms_set_occupancy_pad, ctx, B.APMS_KERNEL_COMPRESS, -2) == B.APMS_EINVAL
 
 
 def test_sixteen_bit_gradient_entry_points(ctx):
@@ -164,6 +171,16 @@ def test_gradient_variant_entry_points(ctx):
     assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m, 1e-4, 1.0, 1e-8) == B.APMS_EINVAL
     assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, e, 1e-4, 0.9, 1e-8) == B.APMS_EALIAS
     assert status_of(B.apms_apply_gradient, ctx, p, sc, g, e, m + 8, 1e-4, 0.9, 1e-8) == B.APMS_EALIGN
+
+
+def test_gather_mode_knob(ctx):
+    assert B.apms_get_plan(ctx)["gather_mode"] == B.APMS_GATHER_AUTO
+    for mode in (B.APMS_GATHER_SPLIT, B.APMS_GATHER_FUSED, B.APMS_GATHER_AUTO):
+        B.apms_set_gather_mode(ctx, mode)
+        assert B.apms_get_plan(ctx)["gather_mode"] == mode
+    assert status_of(B.apms_set_gather_mode, ctx, 3) == B.APMS_EINVAL
+    assert status_of(B.apms_set_gather_mode, ctx, -1) == B.APMS_EINVAL
+    assert status_of(B.apms_set_gather_mode, None, 0) == B.APMS_EINVAL
 
 
 def test_topk_entry_points(ctx):

@@ -338,6 +338,51 @@ def test_warmup_freeze_then_compressed():
     run.close()
 
 
+def test_gather_forms_agree_and_auto_decides():
+    """The pending gather can be carried out by a fill of its own (split) or inside the worker kernel (fused);
+    APMS_GATHER_AUTO times both on its first gathers and keeps the faster.  All three give the same bits in
+    every buffer, and the automatic choice is made without the library ever waiting."""
+    wl = W.scaled(W.TINY, 4096 * 24 + 4096 * 3 * 4, chunk=4096 * 3 + 0)
+    st = W.host_state(wl)
+    ost = oracle_state(wl.d_pad, wl.n, wl.L, st)
+    runs = {mode: from_host_state(wl, st, DEV, deferred=True)
+            for mode in (B.APMS_GATHER_SPLIT, B.APMS_GATHER_FUSED, B.APMS_GATHER_AUTO)}
+    for mode, r in runs.items():
+        assert B.apms_get_plan(r.ctx)["gather_mode"] == B.APMS_GATHER_AUTO      # the default
+        B.apms_set_gather_mode(r.ctx, mode)
+        plan = B.apms_get_plan(r.ctx)
+        assert plan["gather_mode"] == mode
+        assert plan["gather_choice"] == (-1 if mode == B.APMS_GATHER_AUTO else mode)
+    gd = torch.empty(wl.n, wl.d_pad, dtype=torch.float32, device=DEV)
+    steps = 11                                  # step 0 has no gather; gather 0 untimed, 1-6 timed, 7 decides, then the choice
+    for step in range(steps):
+        say("gather forms step %d" % step)
+        g = W.host_grad(wl, step)
+        gd.copy_(torch.from_numpy(g))
+        ost.step(g, wl.beta, wl.lr, wl.eps)
+        for r in runs.values():
+            r.step(gd, wl.beta, wl.lr, wl.eps)
+        torch.cuda.synchronize()
+        ref = runs[B.APMS_GATHER_SPLIT]
+        for mode, r in runs.items():
+            for name in ("packed", "scales", "spacked", "sscales", "x"):
+                assert torch.equal(getattr(r, name), getattr(ref, name)), "step %d mode %d: %s" % (step, mode, name)
+        same_words(host(ref.packed), ost.packed, "worker signs, step %d" % step)
+        same_words(host(ref.spacked), ost.spacked, "server signs, step %d" % step)
+    plan = B.apms_get_plan(runs[B.APMS_GATHER_AUTO].ctx)
+    assert plan["gather_choice"] in (B.APMS_GATHER_SPLIT, B.APMS_GATHER_FUSED), plan
+    assert all(ms > 0.0 for ms in plan["gather_ms"]), plan
+    for r in runs.values():
+        r.finalize()
+    torch.cuda.synchronize()
+    ref = runs[B.APMS_GATHER_SPLIT]
+    compare_all(ref, ost, "after %d steps" % steps, errors=True, momentum=True)
+    for mode, r in runs.items():
+        for name in ("m", "werr", "serr"):
+            assert torch.equal(getattr(r, name), getattr(ref, name)), "mode %d: %s" % (mode, name)
+        r.close()
+
+
 def test_hip_graph_replay_matches_eager():
     """The step allocates nothing, never synchronises and records no memset, so a steady-state step can be
     captured in a HIP graph: replays (with fresh gradients in the same buffer, and the program's own
