@@ -132,6 +132,60 @@ def cpu_baseline(wl, state, g, sample_elems, steps):
     }
 
 
+def region_map(args):
+    """Where the big buffers lie in HBM, and what that does to the fused worker kernel: 44 buffers of a
+    quarter-size problem (n = 16, 5.44 GB each) are allocated one after the other, and the gather-carrying
+    worker call is timed in its fused form with the momentum, the worker error and the gradient in chosen
+    ones of them.  Prints a table (stderr) and one JSON line (stdout)."""
+    import torch
+    from paper_2008_11343_amd import binding as B
+    n = 16
+    d = 340000768 // 4 // (n * 4096) * (n * 4096)
+    L = d // n
+    f = dict(dtype=torch.float32, device="cuda:0")
+    i32 = dict(dtype=torch.int32, device="cuda:0")
+    nb = 44
+    blocks = [torch.zeros(n, d, **f) for _ in range(nb)]
+    gib = lambda t: (blocks[0].data_ptr() - t.data_ptr()) / 2.0 ** 30     # the allocator hands out descending addresses
+    x = torch.empty(d, **f).normal_(0, 0.02)
+    v = torch.ones(d, **f)
+    serr = torch.zeros(d, **f)
+    packed, spacked = torch.zeros(n, d // 32, **i32), torch.zeros(d // 32, **i32)
+    scales, sscales = torch.zeros(n, n, **f), torch.zeros(n, **f)
+
+    def worker_ms(m, werr, g, form, reps=5):
+        ctx = B.apms_create(d, n, L, 0)
+        B.apms_set_deferral(ctx, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER)
+        B.apms_set_gather_mode(ctx, form)
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(reps)]
+        for r in range(reps):
+            ev[r][0].record()
+            B.apms_compress(ctx, m, g, werr, packed, scales, 0.9)
+            ev[r][1].record()
+            B.apms_server_reduce(ctx, packed, scales, serr, spacked, sscales)
+            B.apms_apply(ctx, spacked, sscales, v, x, m, 1e-4, 1e-8)
+        B.apms_finalize(ctx, werr, serr, m)
+        torch.cuda.synchronize()
+        B.apms_destroy(ctx)
+        ts = sorted(e[0].elapsed_time(e[1]) for e in ev[1:])
+        return ts[len(ts) // 2]
+
+    gcols = list(range(0, nb, 4))
+    rows = []
+    log("quarter-size problem: d=%d n=%d, %d buffers of %.2f GB; column = buffer of the gradient (offset from the first "
+        "buffer in GiB: %s)" % (d, n, nb, n * d * 4 / 1e9, " ".join("%.0f" % gib(blocks[k]) for k in gcols)))
+    for form, fname in ((B.APMS_GATHER_FUSED, "fused"), (B.APMS_GATHER_SPLIT, "split")):
+        for mi, wj in ((0, 21), (0, 40), (21, 0), (21, 40), (40, 0), (40, 21), (0, 10), (21, 30), (40, 33)):
+            if form == B.APMS_GATHER_SPLIT and (mi, wj) not in ((0, 21), (0, 10), (21, 30)):
+                continue
+            times = [None if gk in (mi, wj) else worker_ms(blocks[mi], blocks[wj], blocks[gk], form) for gk in gcols]
+            rows.append({"form": fname, "m_GiB": gib(blocks[mi]), "err_GiB": gib(blocks[wj]), "ms_by_gradient_buffer": times})
+            log("%-5s m at %5.0f GiB, error at %5.0f GiB: " % (fname, gib(blocks[mi]), gib(blocks[wj])) +
+                " ".join("  -- " if t is None else "%5.2f" % t for t in times))
+    print(json.dumps({"experiment": "region-map", "d": d, "n": n, "buffer_GB": n * d * 4 / 1e9,
+                      "gradient_buffer_GiB": [gib(blocks[k]) for k in gcols], "rows": rows}), flush=True)
+
+
 def measure(args, wl, place, want_state=False):
     """One measurement: allocate, initialise, warm up, time args.steps steps.  Returns a dict of raw results."""
     import torch
@@ -316,6 +370,9 @@ def main():
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of n*d floats (a kernel of known HBM traffic, for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--region-map", action="store_true",
+                    help="instead of the benchmark: time the fused and the split worker call with the momentum, the "
+                         "error and the gradient in different parts of HBM (the experiment behind --placement)")
     ap.add_argument("--cpu-sample", type=int, default=1 << 23)
     ap.add_argument("--cpu-steps", type=int, default=4)
     args = ap.parse_args()
@@ -329,6 +386,9 @@ def main():
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the HIP path has no CPU fallback")
+    if args.region_map:
+        region_map(args)
+        return
     wl = {w.name: w for w in W.CONFIGS}[args.workload]
     if args.chunk_elems:
         import dataclasses

@@ -174,7 +174,8 @@ void free_topk_scratch(apms_ctx* c) {
 hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
-    const int64_t fixed = pairs * (apms::kTopkBins + apms::kTopkStateWords + 1) * 4 + 2 * tiles * 4;
+    const int64_t guesses = pairs + c->C;                     // the worker call's pairs, then the server call's chunks
+    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords) + guesses) * 4 + 2 * tiles * 4;
     const int32_t want = apms::topk_slots_for(K_max, c->L);
     if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
     hipError_t e = hipDeviceSynchronize();                     // kernels of earlier calls may still use the scratch
@@ -182,7 +183,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     if (!c->topk.hist) {
         e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
-        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), pairs * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), guesses * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
         if (e != hipSuccess) {
@@ -205,7 +206,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
         return e;
     }
     // no guess to go by: the slots' size decides how low a guess may be without overflowing them
-    e = hipMemset(c->topk.guess, 0xFF, pairs * 4);
+    e = hipMemset(c->topk.guess, 0xFF, guesses * 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();           // the fill is on the null stream: done before any caller stream goes on
     if (e != hipSuccess) return e;
     c->topk.slots_per_tile = want;
@@ -234,6 +235,12 @@ void free_scratch(apms_ctx* c) {
     c->w_pending = c->s_pending = c->g_pending = nullptr;
 }
 
+// Occupancy pads of the worker kernel when the caller leaves them to the library (APMS_PAD_AUTO), from sweeps
+// on MI355X with BERT-Large-sized buffers: with a momentum stream of its own (m read, or the gathered m
+// written) two workgroups per CU stream best; with error and gradient alone, three.
+constexpr int32_t kPadWorkerReadsOrWritesMomentum = 64 * 1024;
+constexpr int32_t kPadWorkerNoMomentum = 48 * 1024;
+
 // Candidate forms of a gather-carrying apms_compress: split (0), fused with the worker kernel capped at two
 // workgroups per CU (1), fused uncapped (2).  An occupancy pad set by the caller overrides the cap, which
 // makes 1 and 2 the same.
@@ -243,8 +250,8 @@ struct GatherForm {
 };
 GatherForm gather_form(const apms_ctx* c, int index) {
     const int32_t set = c->lds_pad[APMS_KERNEL_COMPRESS];
-    if (index == 0) return {false, set != APMS_PAD_AUTO ? set : 0};
-    return {true, set != APMS_PAD_AUTO ? set : (index == 1 ? 64 * 1024 : 0)};
+    if (index == 0) return {false, set != APMS_PAD_AUTO ? set : kPadWorkerNoMomentum};
+    return {true, set != APMS_PAD_AUTO ? set : (index == 1 ? kPadWorkerReadsOrWritesMomentum : 0)};
 }
 
 // Index of the form the gather of this call takes and, through *sample, the pair of events to bracket it with
@@ -543,7 +550,9 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
     float* m_arg = (gather && (c->deferral & APMS_IMPLICIT_MOMENTUM)) ? nullptr : m;
     hipError_t e = hipSuccess;
     hipEvent_t* sample = nullptr;
-    int32_t pad = c->lds_pad[APMS_KERNEL_COMPRESS] != APMS_PAD_AUTO ? c->lds_pad[APMS_KERNEL_COMPRESS] : 0;
+    // no gather to write: by variant (reads m: three read streams; no m at all: two)
+    int32_t pad = c->lds_pad[APMS_KERNEL_COMPRESS] != APMS_PAD_AUTO ? c->lds_pad[APMS_KERNEL_COMPRESS]
+                  : (momentum == apms::kMomRead ? kPadWorkerReadsOrWritesMomentum : kPadWorkerNoMomentum);
     if (gather && m_arg) {
         const GatherForm form = gather_form(c, pick_gather_form(c, s, &sample));
         pad = form.pad;

@@ -9,7 +9,11 @@
 // such element to keep.  Histograms use integer atomics (order-independent), the emission order comes from
 // per-tile counts and a scan, so the result does not depend on scheduling.
 //
-// Only the level-0 histogram needs every element.  What the later steps need are the elements at or above
+// Only the level-0 histogram needs every element, and only if nothing is known: the first pass histograms
+// the elements at or above a guessed bin (the previous call's threshold bin, less one) and leaves the rest
+// uncounted, so that the few populated exponent bins of ordinary data do not serialise on LDS atomics; if the
+// bins it did count hold fewer than K elements the threshold lies below the guess, and one more pass over the
+// buffer builds the whole level-0 histogram for that chunk.  What the later steps need are the elements at or above
 // the level-0 bin of T (kept whatever T turns out to be if above, candidates if inside: under 2 % of a tile
 // when K is 1 % of a chunk).  They are copied to per-tile slots - by the worker's first pass itself, on the
 // previous call's bin, else by one more pass once the bin is known - and key levels 1 and 2, the tie
@@ -37,6 +41,7 @@ enum : int {
     kStIdxT = 7,          // ties are kept up to and including this chunk-local index
     kStOverflow = 8,      // 1 if a tile of this pair had more entries than slots: full passes instead
     kStResplit = 9,       // 1 if the pair's slots have to be filled again, from the threshold bin now known
+    kStRehist = 10,       // 1 if the level-0 histogram of the first pass did not reach down to the threshold bin
 };
 
 constexpr uint32_t kNoGuess = 0xFFFFFFFFu;      // guess[pair]: no earlier call to go by
@@ -141,6 +146,7 @@ __device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int
 }
 
 constexpr int kTileRows = kTopkTile / (kThreads * 4);   // 128-bit rows per thread per tile, plain layout
+constexpr int kServerStage = 2048;                       // entries of the server kernel's LDS stage (16 KB)
 constexpr int kRowStride = kThreads * 4;
 
 // Flush a workgroup's LDS histogram into the pair's global histogram (non-zero bins only).
@@ -185,11 +191,13 @@ __device__ __forceinline__ uint32_t write_tile_slots(const f32x4 (&v)[kTileRows]
 // ------------------------------------------------------------------------
 // Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
 // ------------------------------------------------------------------------
-// The threshold hardly moves from one step to the next, so the pass also fills the slots on a guess: the
-// level-0 bin of the previous call's threshold, less one (guess[pair]; kNoGuess before the first call).
-// The guess is good if it is not above the bin the selection then finds - the slots hold a superset of what
-// is needed, and the extra entries fail every later test; otherwise, or if a tile overflowed on the guess,
-// the pair is marked and topk_split_kernel fills its slots again.
+// The threshold hardly moves from one step to the next, so the pass works on a guess: the level-0 bin of the
+// previous call's threshold, less one (guess[pair]; kNoGuess before the first call).  Elements at or above
+// the guessed bin are histogrammed and copied to the slots, the others are left alone.  The guess is good if
+// it is not above the bin the selection then finds - histogram and slots hold a superset of what is needed,
+// and the extra entries fail every later test; if it is (the counted bins hold fewer than K elements), the
+// pair is marked kStRehist and takes a full histogram pass; where the guess was too high, or a tile
+// overflowed on it, the pair is marked kStResplit and topk_split_kernel fills its slots again.
 __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __restrict__ m,
                                                                  const float* __restrict__ g,
                                                                  float* __restrict__ e, uint32_t* __restrict__ hist,
@@ -225,8 +233,8 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
             const float mi = bm + bg;
             u[r][c] = mi + ve[c];
             const uint32_t key = key_of(u[r][c]);
-            atomicAdd(&lds_hist[key >> 20], 1u);
-            if ((key & kTopMask) >= floor_bits) {
+            if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
+                atomicAdd(&lds_hist[key >> 20], 1u);
                 take_mask |= 1u << (4 * r + c);
                 ++count;
             }
@@ -270,50 +278,141 @@ __global__ __launch_bounds__(kThreads) void topk_tile_offsets_kernel(const uint3
     offsets[t] = static_cast<uint32_t>(lower_bound_u32(idx + list * K, K, static_cast<uint32_t>(tile * tile_elems)));
 }
 
+// Like the worker's first pass, it counts and slots only the elements at or above a guessed level-0 bin
+// (guess[chunk], the server's own table).
 __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t* __restrict__ idx,
                                                                  const float* __restrict__ val,
                                                                  float* __restrict__ serr, uint32_t* __restrict__ hist,
+                                                                 uint32_t* __restrict__ state,
+                                                                 const uint32_t* __restrict__ guess,
                                                                  const uint32_t* __restrict__ offsets,
+                                                                 uint32_t* __restrict__ tile_split,
+                                                                 uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                  int64_t d, int64_t L, int32_t C, int32_t n,
                                                                  int32_t K, int32_t tiles_per_chunk, float inv_n) {
     __shared__ uint32_t lds_hist[kTopkBins];
+    __shared__ uint64_t lds_scan[kWaves];
     __shared__ float acc[kTopkTile];
+    __shared__ uint2 stage[kServerStage];                      // (tile-local position, value bits), worker-major
+    __shared__ uint32_t stage_first[kThreads];                 // per worker of the batch: first list entry of the tile
+    __shared__ uint32_t stage_start[kThreads + 1];             // ... and where its entries start in the stage
+    __shared__ uint32_t stage_scan[kWaves];
     for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
     for (int j = threadIdx.x; j < kTopkTile; j += kThreads) acc[j] = 0.0f;
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // slices = 1: pair = chunk
     const int64_t tile_lo = tr.tile * kTopkTile;
-    __syncthreads();
-    for (int32_t i = 0; i < n; ++i) {                         // worker order
-        const int64_t which = static_cast<int64_t>(i) * C + tr.pair;
-        const int64_t list = which * K;
-        // this tile's stretch of worker i's sorted list, from the table topk_tile_offsets_kernel filled
-        const uint32_t* off = offsets + which * tiles_per_chunk + tr.tile;
-        const int first = static_cast<int>(off[0]);
-        const int last = (tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : K;
-        // indices are unique inside one worker's list: no two threads touch the same accumulator
-        for (int t = first + threadIdx.x; t < last; t += kThreads) {
-            const uint32_t j = idx[list + t] - static_cast<uint32_t>(tile_lo);
-            if (j < static_cast<uint32_t>(kTopkTile)) acc[j] = acc[j] + val[list + t];   // always true for sorted lists
-        }
-        __syncthreads();
+    const uint32_t guessed = guess[tr.pair];
+    const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
+    // the tile of the server error, requested now: it arrives while the messages are being decoded
+    f32x4 ve[kTileRows];
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tile_lo + threadIdx.x * 4 + r * kRowStride;
+        ve[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (off < L) ve[r] = load_stream(serr + tr.base + off);
     }
+    __syncthreads();
+    // The decoded messages have to be added position by position in worker order, and walking the workers one
+    // after the other straight from memory is a chain of dependent loads (where a worker's stretch for this
+    // tile starts, then its entries) per worker.  So, kThreads workers at a time: (A) one thread per worker
+    // fetches its stretch's bounds, a workgroup scan lays the stretches out back to back; (B) all threads
+    // copy the entries of all those workers into an LDS stage at once; (C) each wave, which owns a quarter of
+    // the tile's positions, walks the stage worker by worker and adds the entries that fall into its quarter.
+    // A wave's LDS operations complete in program order, and positions are unique inside one worker's list,
+    // so the running sums see the workers in order without any barrier in (C).
+    {
+        const int lane = threadIdx.x & (kWaveSize - 1);
+        const uint32_t wave = threadIdx.x >> 6;
+        constexpr uint32_t kQuarterShift = 10;                 // kTopkTile / kWaves = 1024 positions per wave
+        static_assert((kTopkTile / kWaves) == (1 << kQuarterShift), "a wave's share of the tile");
+        for (int32_t i0 = 0; i0 < n; i0 += kThreads) {
+            const int32_t batch = min(n - i0, static_cast<int32_t>(kThreads));
+            // (A)
+            uint32_t first = 0, count = 0;
+            if (static_cast<int32_t>(threadIdx.x) < batch) {
+                const int64_t which = static_cast<int64_t>(i0 + threadIdx.x) * C + tr.pair;
+                const uint32_t* off = offsets + which * tiles_per_chunk + tr.tile;
+                first = off[0];
+                const uint32_t last = (tr.tile + 1 < tiles_per_chunk) ? off[1] : static_cast<uint32_t>(K);
+                count = last - first;
+            }
+            uint32_t total;
+            const uint32_t start = block_exclusive_scan_u32(count, stage_scan, total);
+            stage_first[threadIdx.x] = first;
+            stage_start[threadIdx.x] = start;
+            if (threadIdx.x == 0) stage_start[kThreads] = total;
+            __syncthreads();
+            if (total <= static_cast<uint32_t>(kServerStage)) {
+                // (B) entry e of the stage belongs to the worker w with stage_start[w] <= e < stage_start[w + 1]
+                for (uint32_t e = threadIdx.x; e < total; e += kThreads) {
+                    int lo = 0, hi = batch;                    // last w with stage_start[w] <= e
+                    while (hi - lo > 1) {
+                        const int mid = (lo + hi) >> 1;
+                        if (stage_start[mid] <= e) lo = mid; else hi = mid;
+                    }
+                    const int64_t src = (static_cast<int64_t>(i0 + lo) * C + tr.pair) * K + stage_first[lo] + (e - stage_start[lo]);
+                    const float value = val[src];
+                    stage[e] = make_uint2(idx[src] - static_cast<uint32_t>(tile_lo), __builtin_bit_cast(uint32_t, value));
+                }
+                __syncthreads();
+                // (C)
+                for (int32_t w = 0; w < batch; ++w) {
+                    const uint32_t lo = stage_start[w], hi = stage_start[w + 1];
+                    for (uint32_t e = lo + lane; e < hi; e += kWaveSize) {
+                        const uint2 entry = stage[e];
+                        const uint32_t j = entry.x;
+                        if (j < static_cast<uint32_t>(kTopkTile) && (j >> kQuarterShift) == wave)
+                            acc[j] = acc[j] + __builtin_bit_cast(float, entry.y);
+                    }
+                }
+            } else {
+                // more entries than the stage holds (K far above what a tile usually carries): worker by worker
+                for (int32_t w = 0; w < batch; ++w) {
+                    const int64_t list = (static_cast<int64_t>(i0 + w) * C + tr.pair) * K;
+                    const uint32_t lo = stage_first[w], hi = lo + (stage_start[w + 1] - stage_start[w]);
+                    for (uint32_t t = lo + lane; t < hi; t += kWaveSize) {
+                        const uint32_t j = idx[list + t] - static_cast<uint32_t>(tile_lo);
+                        const float value = val[list + t];
+                        if (j < static_cast<uint32_t>(kTopkTile) && (j >> kQuarterShift) == wave) acc[j] = acc[j] + value;
+                    }
+                }
+            }
+            __syncthreads();                                   // before the next batch reuses the stage tables
+        }
+    }
+    f32x4 ubar[kTileRows];
+    uint32_t take_mask = 0;
+    uint64_t packed = 0;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int local = threadIdx.x * 4 + r * kRowStride;
         const int64_t off = tile_lo + local;
+        ubar[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (off >= L) continue;
         const int64_t p = tr.base + off;
-        const f32x4 ve = load_stream(serr + p);
-        f32x4 ubar;
+        uint32_t count = 0;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float mean = acc[local + c] * inv_n;
-            ubar[c] = mean + ve[c];
-            atomicAdd(&lds_hist[key_of(ubar[c]) >> 20], 1u);
+            ubar[r][c] = mean + ve[r][c];
+            const float value = ubar[r][c];
+            const uint32_t key = key_of(value);
+            if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
+                atomicAdd(&lds_hist[key >> 20], 1u);
+                take_mask |= 1u << (4 * r + c);
+                ++count;
+            }
         }
-        store_stream(serr + p, ubar);
+        packed |= static_cast<uint64_t>(count) << (16 * r);
+        store_stream(serr + p, ubar[r]);
     }
-    __syncthreads();
+    const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
+    const uint32_t marked = write_tile_slots(ubar, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
+                                             slots_per_tile);        // its barriers also cover lds_hist
+    if (threadIdx.x == 0) {
+        tile_split[tile_id] = marked;
+        if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
+    }
     flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
 }
 
@@ -326,13 +425,16 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
 // histogram for the next level.
 // At key level 0 with a guess table: checks the guess the slots were filled on against the bin found (see
 // topk_worker_u_kernel) and leaves the next call's guess.
+// only_rehist: the second level-0 pick of a call, for the pairs whose first histogram fell short (kStRehist).
 template <bool kIdx>
 __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
-                                                             int level, uint32_t K, uint32_t* __restrict__ guess) {
+                                                             int level, uint32_t K, uint32_t* __restrict__ guess,
+                                                             bool only_rehist) {
     __shared__ uint32_t lds[kWaves];
     const int64_t pair = blockIdx.x;
     uint32_t* h = hist + pair * kTopkBins;
     uint32_t* st = state + pair * kTopkStateWords;
+    if (only_rehist && st[kStRehist] == 0u) return;            // whole workgroup
     const bool tie_needed = kIdx ? (st[kStTieNeeded] != 0u) : true;
     if (kIdx && !tie_needed) {                                 // every element equal to T is kept
         if (level == 2 && threadIdx.x == 0) st[kStIdxT] = 0xFFFFFFFFu;
@@ -358,6 +460,12 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
     for (int q = 0; q < kPer; ++q) {
         const int pos = threadIdx.x * kPer + q;
         if (pos < nb) h[kIdx ? pos : nb - 1 - pos] = 0u;
+    }
+    if (!kIdx && level == 0 && !only_rehist && total < remaining) {
+        // the bins the first pass counted (those at or above its guess) do not reach down to the K-th largest
+        // key: the whole level-0 histogram is needed (topk_key_hist_walk_kernel, then this kernel again)
+        if (threadIdx.x == 0) st[kStRehist] = 1u;
+        return;
     }
     if (before_me < remaining && remaining <= before_me + mine) {           // exactly one thread
         uint32_t before = before_me;
@@ -442,6 +550,37 @@ __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ s
             if (flags[q] != 0u) body(p0 + q);
         __syncthreads();                                       // before the next round overwrites the flags
     }
+}
+
+// The whole level-0 histogram of the pairs marked kStRehist (their first pass counted only the bins at or
+// above a guess that proved too high, or had no guess to go by), from the buffer: per-element LDS atomics,
+// one flush per workgroup and pair.  topk_pick_kernel has cleared those pairs' histograms.
+__global__ __launch_bounds__(kThreads) void topk_rehist_kernel(const float* __restrict__ buf, uint32_t* __restrict__ hist,
+                                                               const uint32_t* __restrict__ state, int64_t d, int64_t L,
+                                                               int32_t C, int64_t pairs, int32_t tiles_per_chunk) {
+    __shared__ uint32_t lds_hist[kTopkBins];
+    for_flagged_pairs(state, pairs, kStRehist, kStRehist, [&](int64_t pair) {
+        for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
+        __syncthreads();
+        const int64_t slice = pair / C;
+        const int64_t base = slice * d + (pair - slice * C) * L;
+        for (int64_t tile = blockIdx.x; tile < tiles_per_chunk; tile += gridDim.x) {
+#pragma unroll
+            for (int r = 0; r < kTileRows; ++r) {
+                const int64_t off = tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+                if (off >= L) continue;
+                const f32x4 v = load_stream(buf + base + off);
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float value = v[c];
+                    atomicAdd(&lds_hist[key_of(value) >> 20], 1u);
+                }
+            }
+        }
+        __syncthreads();
+        flush_histogram(lds_hist, hist + pair * kTopkBins);
+        __syncthreads();                                       // before the next pair clears the LDS histogram
+    });
 }
 
 // After the level-0 pick, for the pairs marked kStResplit (every pair of a call that had no guess to go by):
@@ -825,6 +964,7 @@ __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restri
     for (int64_t p = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x; p < pairs; p += stride) {
         state[p * kTopkStateWords + kStOverflow] = 0u;
         state[p * kTopkStateWords + kStResplit] = resplit;
+        state[p * kTopkStateWords + kStRehist] = 0u;
     }
 }
 
@@ -835,8 +975,7 @@ __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restri
     } while (0)
 
 // The selection + emission over `slices` x C pairs of `buf` ([slices][d]) whose level-0 histogram is filled.
-// `guess`: the per-pair table the first pass filled the slots on (see topk_worker_u_kernel), or nullptr if it
-// did not fill them (every pair is then marked kStResplit).
+// `guess`: the per-pair table the first pass counted and filled the slots on (see topk_worker_u_kernel).
 hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float* buf, uint32_t* idx, float* val,
                            uint32_t* guess, const TopkScratch& s, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
@@ -862,8 +1001,17 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
             APMS_RETURN_IF_ERROR();
         }
         hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                           level == 0 ? guess : static_cast<uint32_t*>(nullptr));
+                           level == 0 ? guess : static_cast<uint32_t*>(nullptr), false);
         APMS_RETURN_IF_ERROR();
+        if (level == 0) {
+            // pairs whose first pass did not count down to the threshold bin: full histogram, pick again
+            hipLaunchKernelGGL(topk_rehist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L, geo.C,
+                               pairs, tpc);
+            APMS_RETURN_IF_ERROR();
+            hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32, guess,
+                               true);
+            APMS_RETURN_IF_ERROR();
+        }
     }
     for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
         hipLaunchKernelGGL(topk_cand_hist_kernel<true>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
@@ -873,7 +1021,7 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                            geo.C, pairs, tpc, level);
         APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                           static_cast<uint32_t*>(nullptr));
+                           static_cast<uint32_t*>(nullptr), false);
         APMS_RETURN_IF_ERROR();
     }
     const dim3 per_wave_tile(static_cast<uint32_t>((tiles_total + kWaves - 1) / kWaves));
@@ -935,15 +1083,17 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
                                      const TopkScratch& scratch, hipStream_t stream) {
     if (geo.C <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
-    hipError_t e = begin_call(geo.C, /*resplit=*/true, scratch, stream);
+    hipError_t e = begin_call(geo.C, /*resplit=*/false, scratch, stream);
     if (e != hipSuccess) return e;
     e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, kTopkTile, K, idx, scratch, stream);
     if (e != hipSuccess) return e;
+    uint32_t* server_guess = scratch.guess + static_cast<int64_t>(geo.n) * geo.C;   // after the workers' entries
     hipLaunchKernelGGL(topk_server_u_kernel, dim3(static_cast<uint32_t>(static_cast<int64_t>(geo.C) * tpc)),
-                       dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.tile_counts, geo.d, geo.L,
+                       dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.state, server_guess,
+                       scratch.tile_counts, scratch.tile_split, scratch.slots, scratch.slots_per_tile, geo.d, geo.L,
                        geo.C, geo.n, static_cast<int32_t>(K), tpc, inv_n);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, 1, K, serr, sidx, sval, nullptr, scratch, stream);
+    return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, scratch, stream);
 }
 
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
