@@ -564,17 +564,24 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
             m_arg = nullptr;
         }
     }
-    if (e == hipSuccess)
+    const bool eager = !(c->deferral & APMS_DEFER_ERRORS);
+    // eager errors and a chunk that fits on chip: one pass writes the finished error (its scales have the
+    // bits of the two-pass route with one tile per workgroup, so that is the tiling it stands in for)
+    const bool onepass = eager && c->L <= apms::kOnePassMaxChunk && c->w_tiles_per_block == 1;
+    if (e == hipSuccess && onepass)
+        e = apms::launch_compress_onepass(geo, momentum, m_arg, g, grad_format, worker_err, packed, scales,
+                                          c->w_pending, prev, gather ? c->pending_spacked : nullptr,
+                                          gather ? c->g_pending : nullptr, beta, 1.0f - beta, s);
+    if (e == hipSuccess && !onepass)
         e = apms::launch_compress(geo, c->w_tiles_per_block, c->w_blocks_per_chunk, momentum, m_arg, g,
                                   grad_format, worker_err, packed, c->w_partials, prev,
                                   gather ? c->pending_spacked : nullptr, gather ? c->g_pending : nullptr,
                                   beta, 1.0f - beta, pad, s);
     if (e == hipSuccess && sample) e = hipEventRecord(sample[1], s);
-    if (e == hipSuccess)
+    if (e == hipSuccess && !onepass)
         e = apms::launch_scales(static_cast<int64_t>(c->n) * c->C, c->w_blocks_per_chunk, c->L, c->w_partials, scales,
                                 c->w_pending, s);
-    const bool eager = !(c->deferral & APMS_DEFER_ERRORS);
-    if (e == hipSuccess && eager)
+    if (e == hipSuccess && eager && !onepass)
         e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
     if (e != hipSuccess) return hip_fail(c, e);
     // every launch of the call is queued: m holds the gathered momentum (unless implicit); deferred, the

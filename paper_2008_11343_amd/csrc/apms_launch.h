@@ -22,6 +22,13 @@ constexpr int kServerTile = tile_elems(kServerRows);
 constexpr int kApplyTile = tile_elems(kApplyRows);
 constexpr int kFinalizeTile = tile_elems(kFinalizeRows);
 
+// The one-pass worker kernel: one workgroup of kOnePassThreads threads holds a whole chunk of up to
+// kOnePassMaxTiles compress tiles (65536 elements) on chip.
+constexpr int kOnePassThreads = 1024;
+constexpr int kOnePassMaxTiles = 16;
+constexpr int64_t kOnePassMaxChunk = static_cast<int64_t>(kOnePassMaxTiles) * kCompressTile;
+constexpr int32_t kOnePassLdsBytes = (kOnePassMaxTiles / (kOnePassThreads / kThreads) / 2) * kCompressRows * kOnePassThreads * 16;
+
 // Most workers the server kernel takes: their scales of one chunk are staged in LDS (16 KB).
 constexpr int kServerMaxWorkers = 4096;
 
@@ -63,6 +70,14 @@ hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t
                            double* partials, const float* prev_scales, const uint32_t* gather_words,
                            const float* gather_scales, float beta, float one_minus_beta, int32_t lds_pad,
                            hipStream_t stream);
+
+// The same worker step for chunks of at most kOnePassMaxChunk elements, with the finished error delta' = u - C[u]
+// in werr and the scales in scales_out (and pending_out, nullable) when the kernel ends: no partials, no
+// second pass.  The scales have the bits launch_compress (one tile per workgroup) + launch_scales give.
+hipError_t launch_compress_onepass(const Geometry& geo, int momentum, float* m, const void* g, int grad_format,
+                                   float* werr, uint32_t* packed, float* scales_out, float* pending_out,
+                                   const float* prev_scales, const uint32_t* gather_words,
+                                   const float* gather_scales, float beta, float one_minus_beta, hipStream_t stream);
 
 // Reduce partials [pairs][blocks_per_chunk] in fixed order, scale = fl32(sqrt(S / L));
 // writes scales_out[pair] and pending_out[pair] (either may be null).

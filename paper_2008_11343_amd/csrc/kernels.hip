@@ -55,13 +55,17 @@ __device__ __forceinline__ void accumulate_squares(double (&acc)[4], f32x4 u) {
 //               of every worker is the decoded server message (gather_words, gather_scale); write it to m
 //               (unless m is null: implicit-momentum mode) and use it directly instead of reading m back.
 //   kMomNone    APGSqueeze variant (Section 5.3): the gradient itself is compensated, u = g + delta.
-template <bool kFull, int MOM, int G>
+//
+// kKeep: u is handed back in `keep` (zero where the tile has no row) instead of being stored into the error
+// buffer: the one-pass kernel holds the whole chunk on chip and writes the finished error itself.
+template <bool kFull, int MOM, int G, bool kKeep = false>
 __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void* __restrict__ g,
                                               float* __restrict__ e, uint32_t* __restrict__ packed,
                                               const uint32_t* __restrict__ gather_words, float gather_scale,
                                               int64_t vec_base, int64_t chunk_base, int64_t tile_off, int64_t L,
                                               int lane_off, int lane, int wave, float beta, float omb,
-                                              float prev_scale, double (&acc)[4]) {
+                                              float prev_scale, double (&acc)[4],
+                                              f32x4 (*keep)[kCompressRows] = nullptr) {
     constexpr int ROWS = kCompressRows;
     const int64_t off0 = tile_off + lane_off;             // inside the chunk
     bool ok[ROWS];
@@ -99,9 +103,14 @@ __device__ __forceinline__ void compress_tile(float* __restrict__ m, const void*
             } else {
                 u = compensated(vm[r], vg[r], ve[r], beta, omb, prev_scale);
             }
-            store_stream(e + chunk_base + off0 + 32 * r, u);
+            if constexpr (kKeep)
+                (*keep)[r] = u;
+            else
+                store_stream(e + chunk_base + off0 + 32 * r, u);
             accumulate_squares(acc, u);
             nib = sign_nibble(u) << shift;
+        } else if constexpr (kKeep) {
+            (*keep)[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         }
         words[r] = or_across_group8(nib);                 // all 64 lanes take part
     }
@@ -168,6 +177,120 @@ __global__ __launch_bounds__(kThreads) void scales_kernel(const double* __restri
         const float s = static_cast<float>(sqrt(mean_sq));
         if (scales_out) scales_out[pair] = s;
         if (pending_out) pending_out[pair] = s;
+    }
+}
+
+// ------------------------------------------------------------------------
+// Worker step in ONE pass, for chunks that fit on chip (Algorithm 1 lines 6-7 with the error final when the
+// kernel ends): one workgroup of kOnePassThreads threads per (worker, chunk) forms u for the whole chunk, keeps
+// it (half in registers, half in LDS), reduces the squared norm, and writes delta' = u - C[u] without u
+// ever going to memory: 16.125 B per worker element where the two-pass eager route moves 24.125.
+//
+// The workgroup works as kOnePassGroups groups of kThreads threads; a group takes tiles exactly as a workgroup
+// of compress_kernel does (same lane layout, same per-thread sums, same wave tree, wave sums added in wave
+// order), and the tile sums are then combined as scales_kernel combines them, so the scale has the bits of the
+// two-pass route.
+// ------------------------------------------------------------------------
+constexpr int kOnePassGroups = kOnePassThreads / kThreads;
+constexpr int kOnePassTilesPerGroup = kOnePassMaxTiles / kOnePassGroups;
+constexpr int kOnePassInRegs = kOnePassTilesPerGroup / 2;       // tiles per group whose u stays in registers
+static_assert(kOnePassMaxTiles <= kWaveSize, "the tile sums are combined by one wave");
+
+__device__ __forceinline__ double wave_sum_f64(double v) {     // the tree of block_sum_f64
+#pragma unroll
+    for (int off = kWaveSize / 2; off > 0; off >>= 1) v += __shfl_down(v, off);
+    return v;
+}
+
+template <int MOM, int G>
+__global__ __launch_bounds__(kOnePassThreads) void compress_onepass_kernel(
+    float* __restrict__ m, const void* __restrict__ g, float* __restrict__ e, uint32_t* __restrict__ packed,
+    float* __restrict__ scales_out, float* __restrict__ pending_out, const float* __restrict__ prev_scales,
+    const uint32_t* __restrict__ gather_words, const float* __restrict__ gather_scales, int64_t d, int64_t L,
+    int32_t C, int32_t tiles_per_chunk, float beta, float omb) {
+    constexpr int ROWS = kCompressRows;
+    extern __shared__ __align__(16) unsigned char onepass_lds[];
+    // u of the tiles that do not stay in registers: [tile slot][row][thread]
+    f32x4* stash = reinterpret_cast<f32x4*>(onepass_lds);
+    __shared__ double wave_sums[kOnePassMaxTiles][kWaves];
+    __shared__ double tile_sums[kOnePassMaxTiles];
+    __shared__ float chunk_scale;
+    const int64_t pair = blockIdx.x;                      // worker * C + chunk
+    const int64_t worker = pair / C;
+    const int64_t chunk = pair - worker * C;
+    const int64_t vec_base = chunk * L;
+    const int64_t chunk_base = worker * d + vec_base;
+    const float prev_scale = prev_scales ? prev_scales[pair] : 0.0f;
+    const float gather_scale = (MOM == kMomGather) ? gather_scales[chunk] : 0.0f;
+    const int group = threadIdx.x / kThreads;
+    const int t = threadIdx.x - group * kThreads;          // thread inside the group
+    const int lane = t & (kWaveSize - 1);
+    const int wave = t >> 6;
+    const int lane_off = packing_lane_offset<ROWS>(wave, lane);
+    f32x4 in_regs[kOnePassInRegs][ROWS];
+#pragma unroll
+    for (int q = 0; q < kOnePassTilesPerGroup; ++q) {
+        const int32_t tile = q * kOnePassGroups + group;
+        double acc[4] = {0.0, 0.0, 0.0, 0.0};
+        f32x4 keep[ROWS];
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) keep[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (tile < tiles_per_chunk) {                      // uniform inside a group: the shuffles in there are whole waves'
+            const int64_t tile_off = static_cast<int64_t>(tile) * kCompressTile;
+            if (tile_off + kCompressTile <= L)
+                compress_tile<true, MOM, G, true>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+                                                  tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc, &keep);
+            else
+                compress_tile<false, MOM, G, true>(m, g, e, packed, gather_words, gather_scale, vec_base, chunk_base,
+                                                   tile_off, L, lane_off, lane, wave, beta, omb, prev_scale, acc, &keep);
+        }
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (q < kOnePassInRegs)
+                in_regs[q < kOnePassInRegs ? q : 0][r] = keep[r];
+            else
+                stash[((q - kOnePassInRegs) * ROWS + r) * kOnePassThreads + threadIdx.x] = keep[r];
+        }
+        const double mine = (acc[0] + acc[1]) + (acc[2] + acc[3]);
+        const double wsum = wave_sum_f64(mine);
+        if (lane == 0) wave_sums[tile][wave] = wsum;
+    }
+    __syncthreads();
+    if (threadIdx.x < kOnePassMaxTiles) {                  // as thread 0 of a compress_kernel workgroup does
+        double total = 0.0;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) total += wave_sums[threadIdx.x][w];
+        tile_sums[threadIdx.x] = static_cast<int32_t>(threadIdx.x) < tiles_per_chunk ? total : 0.0;
+    }
+    __syncthreads();
+    if (threadIdx.x < kWaveSize) {                         // as scales_kernel does with one partial per thread
+        const double mine = threadIdx.x < kOnePassMaxTiles ? tile_sums[threadIdx.x] : 0.0;
+        const double S = wave_sum_f64(mine);
+        if (threadIdx.x == 0) {
+            const double mean_sq = S / static_cast<double>(L);
+            const float s = static_cast<float>(sqrt(mean_sq));
+            chunk_scale = s;
+            scales_out[pair] = s;
+            if (pending_out) pending_out[pair] = s;
+        }
+    }
+    __syncthreads();
+    const float s = chunk_scale;
+#pragma unroll
+    for (int q = 0; q < kOnePassTilesPerGroup; ++q) {
+        const int32_t tile = q * kOnePassGroups + group;
+        if (tile >= tiles_per_chunk) continue;
+        const int64_t off0 = static_cast<int64_t>(tile) * kCompressTile + lane_off;
+#pragma unroll
+        for (int r = 0; r < ROWS; ++r) {
+            if (off0 + 32 * r >= L) continue;
+            const f32x4 u = q < kOnePassInRegs ? in_regs[q < kOnePassInRegs ? q : 0][r]
+                                               : stash[((q - kOnePassInRegs) * ROWS + r) * kOnePassThreads + threadIdx.x];
+            f32x4 out;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) out[c] = read_error(u[c], s);
+            store_stream(e + chunk_base + off0 + 32 * r, out);
+        }
     }
 }
 
@@ -566,7 +689,46 @@ hipError_t set_compress_lds_limit() {
         hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLdsPad);
         if (e != hipSuccess) return e;
     }
+    const void* onepass[] = {reinterpret_cast<const void*>(compress_onepass_kernel<kMomRead, G>),
+                             reinterpret_cast<const void*>(compress_onepass_kernel<kMomGather, G>),
+                             reinterpret_cast<const void*>(compress_onepass_kernel<kMomNone, G>)};
+    for (const void* k : onepass) {
+        hipError_t e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, kOnePassLdsBytes);
+        if (e != hipSuccess) return e;
+    }
     return hipSuccess;
+}
+
+template <int MOM, int G>
+void launch_onepass_as(int64_t pairs, hipStream_t stream, float* m, const void* g, float* werr, uint32_t* packed,
+                       float* scales_out, float* pending_out, const float* prev_scales, const uint32_t* gather_words,
+                       const float* gather_scales, const Geometry& geo, int32_t tpc, float beta, float omb) {
+    hipLaunchKernelGGL((compress_onepass_kernel<MOM, G>), dim3(static_cast<uint32_t>(pairs)), dim3(kOnePassThreads),
+                       kOnePassLdsBytes, stream, m, g, werr, packed, scales_out, pending_out, prev_scales, gather_words,
+                       gather_scales, geo.d, geo.L, geo.C, tpc, beta, omb);
+}
+
+template <int G>
+hipError_t launch_onepass_mom(int momentum, int64_t pairs, hipStream_t stream, float* m, const void* g, float* werr,
+                              uint32_t* packed, float* scales_out, float* pending_out, const float* prev_scales,
+                              const uint32_t* gather_words, const float* gather_scales, const Geometry& geo,
+                              int32_t tpc, float beta, float omb) {
+    switch (momentum) {
+        case kMomRead:
+            launch_onepass_as<kMomRead, G>(pairs, stream, m, g, werr, packed, scales_out, pending_out, prev_scales,
+                                           gather_words, gather_scales, geo, tpc, beta, omb);
+            break;
+        case kMomGather:
+            launch_onepass_as<kMomGather, G>(pairs, stream, m, g, werr, packed, scales_out, pending_out, prev_scales,
+                                             gather_words, gather_scales, geo, tpc, beta, omb);
+            break;
+        case kMomNone:
+            launch_onepass_as<kMomNone, G>(pairs, stream, m, g, werr, packed, scales_out, pending_out, prev_scales,
+                                           gather_words, gather_scales, geo, tpc, beta, omb);
+            break;
+        default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
 }
 
 template <int G>
@@ -640,6 +802,28 @@ hipError_t launch_compress(const Geometry& geo, int32_t tiles_per_block, int32_t
             return launch_compress_mom<kGradBF16>(momentum, grid, lds_pad, stream, m, g, werr, packed, partials,
                                                   prev_scales, gather_words, gather_scales, geo, tpc, tiles_per_block,
                                                   blocks_per_chunk, beta, one_minus_beta);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_compress_onepass(const Geometry& geo, int momentum, float* m, const void* g, int grad_format,
+                                   float* werr, uint32_t* packed, float* scales_out, float* pending_out,
+                                   const float* prev_scales, const uint32_t* gather_words,
+                                   const float* gather_scales, float beta, float one_minus_beta, hipStream_t stream) {
+    const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
+    if (pairs <= 0) return hipSuccess;
+    if (geo.L > kOnePassMaxChunk) return hipErrorInvalidValue;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kCompressTile));
+    switch (grad_format) {
+        case kGradF32:
+            return launch_onepass_mom<kGradF32>(momentum, pairs, stream, m, g, werr, packed, scales_out, pending_out,
+                                                prev_scales, gather_words, gather_scales, geo, tpc, beta, one_minus_beta);
+        case kGradF16:
+            return launch_onepass_mom<kGradF16>(momentum, pairs, stream, m, g, werr, packed, scales_out, pending_out,
+                                                prev_scales, gather_words, gather_scales, geo, tpc, beta, one_minus_beta);
+        case kGradBF16:
+            return launch_onepass_mom<kGradBF16>(momentum, pairs, stream, m, g, werr, packed, scales_out, pending_out,
+                                                 prev_scales, gather_words, gather_scales, geo, tpc, beta, one_minus_beta);
         default: return hipErrorInvalidValue;
     }
 }

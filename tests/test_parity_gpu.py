@@ -338,6 +338,43 @@ def test_warmup_freeze_then_compressed():
     run.close()
 
 
+@pytest.mark.parametrize("n,L,C", [(4, 65536, 2), (3, 4096 * 9 + 160, 3), (2, 32, 4), (5, 4096, 1), (2, 65536 + 4096, 1)],
+                         ids=["max-onepass", "ragged", "one-word-rows", "one-tile", "just-too-long"])
+def test_eager_one_pass_has_the_bits_of_the_two_pass_route(n, L, C):
+    """With eager errors a chunk of up to 65536 elements is compressed in ONE pass (u held on chip, the finished
+    error written directly); longer chunks take two passes.  Both must give the bits of the deferred route
+    (partials per tile + scales kernel): sign words, scales, errors, every step; and match the oracle."""
+    d = L * C
+    wl = W.Workload("onepass", 1, d=d, n=n, chunk=L, steps=4)
+    st = W.host_state(wl)
+    ost = oracle_state(wl.d_pad, wl.n, wl.L, st)
+    eager = from_host_state(wl, st, DEV, deferred=False)
+    later = from_host_state(wl, st, DEV, deferred=True)
+    mixed = from_host_state(wl, st, DEV, deferred=B.APMS_DEFER_GATHER)       # eager errors, gather pending
+    gd = torch.empty(wl.n, wl.d_pad, dtype=torch.float32, device=DEV)
+    for step in range(wl.steps):
+        say("one pass n=%d L=%d C=%d step %d" % (n, L, C, step))
+        g = W.host_grad(wl, step)
+        gd.copy_(torch.from_numpy(g))
+        ost.step(g, wl.beta, wl.lr, wl.eps)
+        for r in (eager, later, mixed):
+            r.step(gd, wl.beta, wl.lr, wl.eps)
+        torch.cuda.synchronize()
+        for r, tag in ((later, "deferred"), (mixed, "eager errors + deferred gather")):
+            for name in ("packed", "scales", "spacked", "sscales", "x"):
+                assert torch.equal(getattr(eager, name), getattr(r, name)), "step %d, %s: %s" % (step, tag, name)
+        assert torch.equal(eager.werr, mixed.werr) and torch.equal(eager.serr, mixed.serr), "step %d: errors" % step
+        compare_all(eager, ost, "eager, step %d" % step, errors=True, momentum=True)
+    for r in (later, mixed):
+        r.finalize()
+    torch.cuda.synchronize()
+    for r in (later, mixed):
+        for name in ("m", "werr", "serr"):
+            assert torch.equal(getattr(eager, name), getattr(r, name)), name
+    for r in (eager, later, mixed):
+        r.close()
+
+
 def test_gather_forms_agree_and_auto_decides():
     """The pending gather can be carried out by a fill of its own (split) or inside the worker kernel (fused);
     APMS_GATHER_AUTO times both on its first gathers and keeps the faster.  All three give the same bits in
