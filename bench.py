@@ -453,12 +453,13 @@ def main():
     elif fused or deferral & B.APMS_IMPLICIT_MOMENTUM:
         kernel = "compress_kernel<momentum: pending gather%s, gradient: %s> (apms_compress)" % (
             ", m not written" if deferral & B.APMS_IMPLICIT_MOMENTUM else " written to m", args.grad_dtype)
-        kname = "apms::compress_kernel<1, 0>"
+        kname = "apms::compress_kernel<1, 0>[fused]"
     else:
         kernel = ("apms_compress as two kernels: apply_kernel<write m only> (the gather as a fill) + "
                   "compress_kernel<momentum: pending gather, m not written, gradient: %s>" % args.grad_dtype)
+        kname = "apms_compress[split]"
     traffic, traffic_source = (None, "not measured for this configuration")
-    if kname and plain and wl.name == "bert-large-flat":
+    if kname and plain and wl.name == "bert-large-flat" and (deferral & B.APMS_DEFER_ERRORS):
         traffic, traffic_source = measured_traffic(kname)
 
     # per call: which roof bounds it.  The server step decodes n sign streams per element: at large n its
