@@ -350,7 +350,8 @@ def main():
     ap.add_argument("--server-tiles", type=int, default=0)
     ap.add_argument("--algo", choices=["momentum", "gradient", "topk"], default="momentum",
                     help="momentum: APMSqueeze with the 1-bit compressor (the benchmark); gradient: the APGSqueeze "
-                         "variant of Section 5.3; topk: APMSqueeze with the top-k compressor of Section 5.1 (eager)")
+                         "variant of Section 5.3; topk: APMSqueeze with the top-k compressor of Section 5.1 "
+                         "(--mode eager or deferred-errors)")
     ap.add_argument("--topk-percent", type=float, default=1.0, help="kept fraction of every chunk, in percent")
     ap.add_argument("--grad-dtype", choices=["f32", "f16", "bf16"], default="f32",
                     help="element type of the gradient input (f32 is the benchmark's configuration)")
@@ -393,8 +394,8 @@ def main():
     if args.chunk_elems:
         import dataclasses
         wl = dataclasses.replace(wl, chunk=args.chunk_elems, name="%s-chunk%d" % (wl.name, args.chunk_elems))
-    if args.algo == "topk" and (args.mode != "eager" or args.grad_dtype != "f32"):
-        sys.exit("bench.py: --algo topk is eager and fp32 only (use --mode eager)")
+    if args.algo == "topk" and (args.mode not in ("eager", "deferred-errors") or args.grad_dtype != "f32"):
+        sys.exit("bench.py: --algo topk takes fp32 gradients and --mode eager or deferred-errors (its gather is always eager)")
     d, n, L = wl.d_pad, wl.n, wl.L
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))

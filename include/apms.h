@@ -349,7 +349,12 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
  * K = k% of chunk_elems, chosen by the caller) and zeroes the rest.  Between equal magnitudes the lower
  * index is kept first (the paper is silent; this makes the result unique).  The wire form of a chunk is
  * K (index, value) pairs, indices local to the chunk and ascending; the selection is exact.
- * These calls are eager (no deferral) and return ESTATE while the 1-bit path has a buffer pending;
+ * The gather is always eager here (apms_topk_apply writes m).  APMS_DEFER_ERRORS applies: eagerly, a call
+ * zeroes the kept positions of its error buffer before its work ends (scattered stores); deferred, it leaves the
+ * compensated vector in the buffer whole and the context remembers each chunk's threshold, and the next
+ * apms_topk_compress / apms_topk_server_reduce on the SAME buffer (or apms_finalize) reads the kept positions as
+ * zero - the same values.  A buffer left so by a top-k call and one left by a 1-bit call are different forms:
+ * each path returns ESTATE while the other has a buffer pending, and for a pending buffer other than its own.
  * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31 or K > 2^31 - 1.
  *
  * apms_topk_reserve(ctx, K_max) is the set-up call that allocates the selection's scratch, sized for calls

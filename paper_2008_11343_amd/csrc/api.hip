@@ -43,6 +43,8 @@ struct apms_ctx {
     // deferral bookkeeping (host side, follows call order = stream order)
     const void* pending_werr = nullptr;       // error buffers that hold u instead of delta
     const void* pending_serr = nullptr;
+    bool pending_werr_topk = false;           // ... left so by a top-k call (kept positions still in, see TopkScratch.keep)
+    bool pending_serr_topk = false;           //     rather than by a 1-bit call (context scales w_pending / s_pending)
     const void* pending_m = nullptr;          // momentum buffer whose gather is still to be written ...
     const uint32_t* pending_spacked = nullptr;  // ... from these sign words (caller's buffer) and g_pending
     int deferral = 0;                         // APMS_DEFER_* flags
@@ -161,7 +163,8 @@ struct DeviceScope {
 };
 
 void free_topk_scratch(apms_ctx* c) {
-    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.tile_counts, c->topk.tile_split,
+                      c->topk.slots};
     for (void* a : arrays)
         if (a) (void)hipFree(a);
     c->topk = {};
@@ -175,7 +178,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
     const int64_t guesses = pairs + c->C;                     // the worker call's pairs, then the server call's chunks
-    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords) + guesses) * 4 + 2 * tiles * 4;
+    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords) + 3 * guesses) * 4 + 2 * tiles * 4;
     const int32_t want = apms::topk_slots_for(K_max, c->L);
     if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
     hipError_t e = hipDeviceSynchronize();                     // kernels of earlier calls may still use the scratch
@@ -184,6 +187,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
         e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), guesses * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.keep), guesses * 8);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
         if (e != hipSuccess) {
@@ -466,14 +470,20 @@ int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, v
     hipStream_t s = static_cast<hipStream_t>(stream);
     const apms::Geometry geo = geometry(c);
     if (worker_err && c->pending_werr == worker_err) {
-        hipError_t e = apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
+        hipError_t e = c->pending_werr_topk
+                           ? apms::launch_topk_finalize(geo, /*server=*/false, worker_err, c->topk, s)
+                           : apms::launch_finalize(geo, c->n, worker_err, c->w_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_werr = nullptr;
+        c->pending_werr_topk = false;
     }
     if (server_err && c->pending_serr == server_err) {
-        hipError_t e = apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
+        hipError_t e = c->pending_serr_topk
+                           ? apms::launch_topk_finalize(geo, /*server=*/true, server_err, c->topk, s)
+                           : apms::launch_finalize(geo, 1, server_err, c->s_pending, c->lds_pad[APMS_KERNEL_FINALIZE], s);
         if (e != hipSuccess) return hip_fail(c, e);
         c->pending_serr = nullptr;
+        c->pending_serr_topk = false;
     }
     if (m && c->pending_m == m) {
         hipError_t e = apms::launch_apply(geo, c->pending_spacked, c->g_pending, nullptr, nullptr, m, nullptr,
@@ -536,7 +546,7 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
                        {m, with_momentum ? all : 0}, {c->pending_spacked, gather ? c->d / 8 : 0}};
     if (int rc = check_arrays(r, 6)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
-    if (c->pending_werr && c->pending_werr != worker_err) return APMS_ESTATE;
+    if (c->pending_werr && (c->pending_werr != worker_err || c->pending_werr_topk)) return APMS_ESTATE;
     if (gather && c->pending_m != m) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
@@ -623,6 +633,7 @@ int apms_freeze(apms_ctx* c, float* m, float* worker_err, float* server_err, voi
     if (e != hipSuccess) return hip_fail(c, e);
     c->pending_werr = nullptr;
     c->pending_serr = nullptr;
+    c->pending_werr_topk = c->pending_serr_topk = false;
     return APMS_OK;
 }
 
@@ -649,7 +660,7 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     const Range r[] = {{packed, vec / 32 * c->n}, {scales, c->n * c->C * 4}, {server_err, vec},
                        {spacked, vec / 32}, {sscales, c->C * 4}};
     if (int rc = check_arrays(r, 5)) return rc;
-    if (c->pending_serr && c->pending_serr != server_err) return APMS_ESTATE;
+    if (c->pending_serr && (c->pending_serr != server_err || c->pending_serr_topk)) return APMS_ESTATE;
     // a pending gather still needs the sign words at that address
     if (c->pending_m && overlap({c->pending_spacked, vec / 32}, {spacked, vec / 32})) return APMS_ESTATE;
     int status;
@@ -779,15 +790,21 @@ int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worke
     const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {idx, lists}, {val, lists}};
     if (int rc = check_arrays(r, 5)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
-    if (c->pending_werr || c->pending_m) return APMS_ESTATE;   // this path reads m and the error as they are
+    // this path reads m as it is, and the error either final or as a top-k call left it
+    if (c->pending_m || (c->pending_werr && !(c->pending_werr_topk && c->pending_werr == worker_err))) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
     if (!topk_reserved_for(c, K)) return APMS_ESTATE;
-    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta, c->topk,
-                                       static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+    const bool defer = (c->deferral & APMS_DEFER_ERRORS) != 0;
+    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta,
+                                              c->pending_werr != nullptr, defer, c->topk,
+                                              static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(c, e);
+    c->pending_werr = defer ? worker_err : nullptr;
+    c->pending_werr_topk = defer;
+    return APMS_OK;
 }
 
 int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, int64_t K, float* server_err,
@@ -798,16 +815,20 @@ int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, 
     const int64_t lists = c->n * c->C * K * 4, slists = c->C * K * 4;
     const Range r[] = {{idx, lists}, {val, lists}, {server_err, c->d * 4}, {sidx, slists}, {sval, slists}};
     if (int rc = check_arrays(r, 5)) return rc;
-    if (c->pending_serr) return APMS_ESTATE;
+    if (c->pending_serr && !(c->pending_serr_topk && c->pending_serr == server_err)) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
     if (!topk_reserved_for(c, K)) return APMS_ESTATE;
+    const bool defer = (c->deferral & APMS_DEFER_ERRORS) != 0;
     hipError_t e = apms::launch_topk_server_reduce(geometry(c), K, idx, val, server_err, sidx, sval,
-                                            1.0f / static_cast<float>(c->n), c->topk,
-                                            static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+                                                   1.0f / static_cast<float>(c->n), c->pending_serr != nullptr, defer,
+                                                   c->topk, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(c, e);
+    c->pending_serr = defer ? server_err : nullptr;
+    c->pending_serr_topk = defer;
+    return APMS_OK;
 }
 
 int apms_topk_apply(apms_ctx* c, const uint32_t* sidx, const float* sval, int64_t K, const float* v, float* x,

@@ -49,10 +49,13 @@ inline int32_t topk_slots_for(int64_t K, int64_t L) {
 //   guess       [pairs + C] u32          the first pass's guess of that bin (less one) from the previous call: the
 //                                        worker call's n * C entries, then the server call's C;
 //                                        0xFFFFFFFF in a new context and whenever the slots are re-allocated
+//   keep        [pairs + C] uint2        {T, idxT} of the last call per pair, for an error buffer left in deferred
+//                                        form (APMS_DEFER_ERRORS): worker pairs, then the server's chunks
 struct TopkScratch {
     uint32_t* hist;
     uint32_t* state;
     uint32_t* guess;
+    uint2* keep;
     uint32_t* tile_counts;
     uint32_t* tile_split;
     uint2* slots;
@@ -62,15 +65,21 @@ struct TopkScratch {
 // Worker: u = beta*m + (1-beta)*g + delta for all (worker, chunk) pairs, written into werr, then the K
 // largest-magnitude elements of every chunk go to idx/val [n][C][K] (chunk-local indices, ascending) and
 // their positions in werr are zeroed, which leaves werr = u - C[u].
+// werr_pending: werr holds the previous call's compensated vector with the kept positions still in (deferred
+// form; scratch.keep says which they are).  defer: leave it in that form again instead of zeroing them.
 hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, const float* g, float* werr,
-                                uint32_t* idx, float* val, float beta, float one_minus_beta,
-                                const TopkScratch& scratch, hipStream_t stream);
+                                uint32_t* idx, float* val, float beta, float one_minus_beta, bool werr_pending,
+                                bool defer, const TopkScratch& scratch, hipStream_t stream);
 
 // Server: ubar = (sum over workers of the decoded lists, worker order) * inv_n + serr, written into serr,
 // then top-K per chunk to sidx/sval [C][K], kept positions of serr zeroed.
 hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint32_t* idx, const float* val,
-                                     float* serr, uint32_t* sidx, float* sval, float inv_n,
-                                     const TopkScratch& scratch, hipStream_t stream);
+                                     float* serr, uint32_t* sidx, float* sval, float inv_n, bool serr_pending,
+                                     bool defer, const TopkScratch& scratch, hipStream_t stream);
+
+// Zero the kept positions of an error buffer in deferred form (worker errors [n][d], or the server's [d]).
+hipError_t launch_topk_finalize(const Geometry& geo, bool server, float* err, const TopkScratch& scratch,
+                                hipStream_t stream);
 
 // Gather + model update: every slice of m becomes the decoded server list (zero elsewhere);
 // x <- x - lr * m / (sqrt(v) + eps).

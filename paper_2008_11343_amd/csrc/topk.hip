@@ -67,6 +67,13 @@ __device__ __forceinline__ bool kept(uint32_t key, uint32_t j, uint32_t T, uint3
     return key > T || (key == T && j <= idxT);
 }
 
+// What an error buffer left in deferred form holds is the compensated vector v of the previous call; its
+// error is v where the element was not kept and zero where it was.  `keep` = {T, idxT} of that call for the
+// pair ({0xFFFFFFFF, 0}: nothing was kept, which is also how a buffer in final form is read).
+__device__ __forceinline__ float deferred_error(float stored, uint32_t j, uint2 keep) {
+    return kept(key_of(stored), j, keep.x, keep.y) ? 0.0f : stored;
+}
+
 // One atomic per distinct bin per wave.  Must be called by all 64 lanes (inactive ones pass active = false).
 __device__ __forceinline__ void hist_add_aggregated(uint32_t* __restrict__ hist, bool active, uint32_t bin) {
     const int lane = threadIdx.x & (kWaveSize - 1);
@@ -205,6 +212,7 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
                                                                  const uint32_t* __restrict__ guess,
                                                                  uint32_t* __restrict__ tile_split,
                                                                  uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                                 const uint2* __restrict__ prev_keep,
                                                                  int64_t d, int64_t L, int32_t C,
                                                                  int32_t tiles_per_chunk, float beta, float omb) {
     __shared__ uint32_t lds_hist[kTopkBins];
@@ -213,6 +221,7 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
     __syncthreads();
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
     const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
+    const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);   // error buffer in deferred form?
     const uint32_t guessed = guess[tr.pair];
     const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
     f32x4 u[kTileRows];
@@ -231,7 +240,8 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
             const float bm = beta * vm[c];
             const float bg = omb * vg[c];
             const float mi = bm + bg;
-            u[r][c] = mi + ve[c];
+            const float stored = ve[c];
+            u[r][c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const uint32_t key = key_of(u[r][c]);
             if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
                 atomicAdd(&lds_hist[key >> 20], 1u);
@@ -288,6 +298,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
                                                                  const uint32_t* __restrict__ offsets,
                                                                  uint32_t* __restrict__ tile_split,
                                                                  uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                                 const uint2* __restrict__ prev_keep,
                                                                  int64_t d, int64_t L, int32_t C, int32_t n,
                                                                  int32_t K, int32_t tiles_per_chunk, float inv_n) {
     __shared__ uint32_t lds_hist[kTopkBins];
@@ -303,6 +314,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
     const int64_t tile_lo = tr.tile * kTopkTile;
     const uint32_t guessed = guess[tr.pair];
     const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
+    const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);
     // the tile of the server error, requested now: it arrives while the messages are being decoded
     f32x4 ve[kTileRows];
 #pragma unroll
@@ -394,7 +406,8 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float mean = acc[local + c] * inv_n;
-            ubar[r][c] = mean + ve[r][c];
+            const float stored = ve[r][c];
+            ubar[r][c] = mean + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const float value = ubar[r][c];
             const uint32_t key = key_of(value);
             if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
@@ -801,7 +814,7 @@ __global__ __launch_bounds__(kThreads) void topk_slot_emit_kernel(float* __restr
                                                                   uint32_t* __restrict__ idx, float* __restrict__ val,
                                                                   int64_t d, int64_t L, int32_t C,
                                                                   int32_t tiles_per_chunk, int64_t tiles_total,
-                                                                  int64_t K) {
+                                                                  int64_t K, bool zero_kept) {
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int64_t tile_id = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
     if (tile_id >= tiles_total) return;
@@ -830,7 +843,7 @@ __global__ __launch_bounds__(kThreads) void topk_slot_emit_kernel(float* __restr
                 const uint32_t bits = entry.y;
                 out_val[rank] = __builtin_bit_cast(float, bits);
             }
-            chunk_buf[j] = 0.0f;
+            if (zero_kept) chunk_buf[j] = 0.0f;
         }
         done += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes)));
     }
@@ -842,7 +855,7 @@ __global__ __launch_bounds__(kThreads) void topk_emit_walk_kernel(float* __restr
                                                                   const uint32_t* __restrict__ tile_offsets,
                                                                   uint32_t* __restrict__ idx, float* __restrict__ val,
                                                                   int64_t d, int64_t L, int32_t C, int64_t pairs,
-                                                                  int32_t tiles_per_chunk, int64_t K) {
+                                                                  int32_t tiles_per_chunk, int64_t K, bool zero_kept) {
     static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
     __shared__ uint64_t lds[kWaves];
     for_flagged_pairs(state, pairs, kStOverflow, kStOverflow, [&](int64_t pair) {
@@ -888,7 +901,7 @@ __global__ __launch_bounds__(kThreads) void topk_emit_walk_kernel(float* __restr
                             out_idx[rank] = static_cast<uint32_t>(off + c);
                             out_val[rank] = v[r][c];
                         }
-                        buf[base + off + c] = 0.0f;
+                        if (zero_kept) buf[base + off + c] = 0.0f;
                         ++rank;
                     }
                 }
@@ -954,6 +967,31 @@ __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __
     }
 }
 
+// End of a call that leaves its error buffer in deferred form: remember {T, idxT} of every pair.
+__global__ __launch_bounds__(kThreads) void topk_save_keep_kernel(const uint32_t* __restrict__ state,
+                                                                  uint2* __restrict__ keep, int64_t pairs) {
+    const int64_t p = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
+    if (p < pairs) keep[p] = make_uint2(state[p * kTopkStateWords + kStKeyT], state[p * kTopkStateWords + kStIdxT]);
+}
+
+// apms_finalize on an error buffer in deferred form: zero the kept positions, which leaves v - C[v].
+__global__ __launch_bounds__(kThreads) void topk_finalize_kernel(float* __restrict__ buf, const uint2* __restrict__ keep,
+                                                                 int64_t d, int64_t L, int32_t C, int32_t tiles_per_chunk) {
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    const uint2 k = keep[tr.pair];
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {
+        const int64_t off = tr.tile * kTopkTile + threadIdx.x * 4 + r * kRowStride;
+        if (off >= L) continue;
+        const f32x4 v = load_stream(buf + tr.base + off);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) {
+            const float value = v[c];
+            if (kept(key_of(value), static_cast<uint32_t>(off + c), k.x, k.y)) buf[tr.base + off + c] = 0.0f;
+        }
+    }
+}
+
 // Start of a call: clear the histograms and the per-pair flags.  resplit = 1 marks every pair for
 // topk_split_kernel (calls whose first pass does not fill the slots).
 __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restrict__ hist, int64_t count,
@@ -976,8 +1014,10 @@ __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restri
 
 // The selection + emission over `slices` x C pairs of `buf` ([slices][d]) whose level-0 histogram is filled.
 // `guess`: the per-pair table the first pass counted and filled the slots on (see topk_worker_u_kernel).
+// `save_keep`: null = eager (the kept positions of buf are zeroed); else the call leaves buf in deferred form
+// and {T, idxT} of every pair go there.
 hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float* buf, uint32_t* idx, float* val,
-                           uint32_t* guess, const TopkScratch& s, hipStream_t stream) {
+                           uint32_t* guess, uint2* save_keep, const TopkScratch& s, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
@@ -1034,11 +1074,18 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     hipLaunchKernelGGL(topk_scan_kernel, per_pair, block, 0, stream, s.tile_counts, tpc);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_slot_emit_kernel, per_wave_tile, block, 0, stream, buf, s.slots, s.slots_per_tile,
-                       s.tile_split, s.state, s.tile_counts, idx, val, geo.d, geo.L, geo.C, tpc, tiles_total, K);
+                       s.tile_split, s.state, s.tile_counts, idx, val, geo.d, geo.L, geo.C, tpc, tiles_total, K,
+                       save_keep == nullptr);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_emit_walk_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_counts, idx, val, geo.d,
-                       geo.L, geo.C, pairs, tpc, K);
-    return hipGetLastError();
+                       geo.L, geo.C, pairs, tpc, K, save_keep == nullptr);
+    APMS_RETURN_IF_ERROR();
+    if (save_keep) {
+        hipLaunchKernelGGL(topk_save_keep_kernel, dim3(static_cast<uint32_t>((pairs + kThreads - 1) / kThreads)), block, 0,
+                           stream, s.state, save_keep, pairs);
+        APMS_RETURN_IF_ERROR();
+    }
+    return hipSuccess;
 }
 
 // Fills s.tile_counts[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries.
@@ -1061,8 +1108,8 @@ hipError_t begin_call(int64_t pairs, bool resplit, const TopkScratch& s, hipStre
 }  // namespace
 
 hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, const float* g, float* werr,
-                                uint32_t* idx, float* val, float beta, float one_minus_beta,
-                                const TopkScratch& scratch, hipStream_t stream) {
+                                uint32_t* idx, float* val, float beta, float one_minus_beta, bool werr_pending,
+                                bool defer, const TopkScratch& scratch, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
     if (pairs <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
@@ -1073,14 +1120,15 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, 
     constexpr uint32_t kWorkerPassPad = 44 * 1024;
     hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), kWorkerPassPad, stream, m, g,
                        werr, scratch.hist, scratch.state, scratch.guess, scratch.tile_split, scratch.slots,
-                       scratch.slots_per_tile, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
+                       scratch.slots_per_tile, werr_pending ? scratch.keep : static_cast<const uint2*>(nullptr), geo.d,
+                       geo.L, geo.C, tpc, beta, one_minus_beta);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, scratch, stream);
+    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, defer ? scratch.keep : nullptr, scratch, stream);
 }
 
 hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint32_t* idx, const float* val,
-                                     float* serr, uint32_t* sidx, float* sval, float inv_n,
-                                     const TopkScratch& scratch, hipStream_t stream) {
+                                     float* serr, uint32_t* sidx, float* sval, float inv_n, bool serr_pending,
+                                     bool defer, const TopkScratch& scratch, hipStream_t stream) {
     if (geo.C <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     hipError_t e = begin_call(geo.C, /*resplit=*/false, scratch, stream);
@@ -1088,12 +1136,25 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
     e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, kTopkTile, K, idx, scratch, stream);
     if (e != hipSuccess) return e;
     uint32_t* server_guess = scratch.guess + static_cast<int64_t>(geo.n) * geo.C;   // after the workers' entries
+    uint2* server_keep = scratch.keep + static_cast<int64_t>(geo.n) * geo.C;
     hipLaunchKernelGGL(topk_server_u_kernel, dim3(static_cast<uint32_t>(static_cast<int64_t>(geo.C) * tpc)),
                        dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.state, server_guess,
-                       scratch.tile_counts, scratch.tile_split, scratch.slots, scratch.slots_per_tile, geo.d, geo.L,
-                       geo.C, geo.n, static_cast<int32_t>(K), tpc, inv_n);
+                       scratch.tile_counts, scratch.tile_split, scratch.slots, scratch.slots_per_tile,
+                       serr_pending ? server_keep : static_cast<const uint2*>(nullptr), geo.d, geo.L, geo.C, geo.n,
+                       static_cast<int32_t>(K), tpc, inv_n);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, scratch, stream);
+    return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, defer ? server_keep : nullptr, scratch, stream);
+}
+
+hipError_t launch_topk_finalize(const Geometry& geo, bool server, float* err, const TopkScratch& scratch,
+                                hipStream_t stream) {
+    const int64_t pairs = server ? geo.C : static_cast<int64_t>(geo.n) * geo.C;
+    if (pairs <= 0) return hipSuccess;
+    const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+    const uint2* keep = scratch.keep + (server ? static_cast<int64_t>(geo.n) * geo.C : 0);
+    hipLaunchKernelGGL(topk_finalize_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), 0, stream, err, keep,
+                       geo.d, geo.L, geo.C, tpc);
+    return hipGetLastError();
 }
 
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,

@@ -459,16 +459,19 @@ def test_hip_graph_replay_matches_eager():
         r.close()
 
 
+@pytest.mark.parametrize("deferred", [True, False, B.APMS_DEFER_GATHER], ids=["deferred", "eager", "eager-errors"])
 @pytest.mark.parametrize("fmt", ["f16", "bf16"])
-def test_sixteen_bit_gradients(fmt):
+def test_sixteen_bit_gradients(fmt, deferred):
     """16-bit gradient inputs (binary16 / bfloat16, widened exactly): 3 Adam warm-up steps, freeze, 5
-    compressed steps in the fully deferred mode, ragged chunks; subnormal, zero and extreme 16-bit values
-    planted in the first step."""
+    compressed steps, ragged chunks; subnormal, zero and extreme 16-bit values planted in the first step.
+    Fully deferred (two-pass worker kernel), eager and eager errors with the gather deferred (the one-pass
+    worker kernel reading m, and decoding the pending gather)."""
     ofmt = {"f16": oracle.GRAD_F16, "bf16": oracle.GRAD_BF16}[fmt]
     wl = W.Workload("g16", 0, d=3 * (4096 * 3 + 96), n=3, chunk=4096 * 3 + 96, steps=5, warmup_steps=3)
     d, n, L = wl.d_pad, wl.n, wl.L
     st = W.host_state(wl, warm_start=True)
-    run = DeviceRun(d, n, L, DEV, deferred=True)
+    run = DeviceRun(d, n, L, DEV, deferred=deferred)
+    flags = run.deferral
     run.x.copy_(torch.from_numpy(st["x"]))
     run.v.zero_()
     ox, om, ov = st["x"].copy(), st["m"].copy(), st["v"].copy()
@@ -493,7 +496,8 @@ def test_sixteen_bit_gradients(fmt):
             bits[2, L + 7:L + 7 + special.size] = special
         run.step(W.g16_bits_to_tensor(bits, fmt, DEV), wl.beta, wl.lr, wl.eps)
         ost.step(oracle.widen_g16(bits, ofmt), wl.beta, wl.lr, wl.eps)
-        compare_all(run, ost, "g16 %s step %d" % (fmt, step), errors=False, momentum=False)
+        compare_all(run, ost, "g16 %s step %d" % (fmt, step), errors=not (flags & B.APMS_DEFER_ERRORS),
+                    momentum=not (flags & B.APMS_DEFER_GATHER))
     run.finalize()
     compare_all(run, ost, "g16 %s end" % fmt)
     run.close()

@@ -36,21 +36,37 @@ def same(a, b, what):
     assert bad.size == 0, "%s: %d of %d entries differ, first at %d" % (what, bad.size, a.size, bad[0])
 
 
-def compare(run, ost, tag):
+def compare(run, ost, tag, errors=True):
+    """errors=False: the error buffers are in deferred form (APMS_DEFER_ERRORS) and not compared."""
     same(host(run.idx), ost.idx, tag + " worker indices")
     same(host(run.val), ost.val, tag + " worker values")
     same(host(run.sidx), ost.sidx, tag + " server indices")
     same(host(run.sval), ost.sval, tag + " server values")
-    same(host(run.werr), ost.werr, tag + " worker_err")
-    same(host(run.serr), ost.serr, tag + " server_err")
+    if errors:
+        same(host(run.werr), ost.werr, tag + " worker_err")
+        same(host(run.serr), ost.serr, tag + " server_err")
     same(host(run.m), ost.m, tag + " momentum")
     np.testing.assert_allclose(host(run.x), ost.x, rtol=1e-5, atol=1e-7, err_msg=tag + " x")
 
 
-def make(d, n, L, st):
+def make(d, n, L, st, deferred=0):
     ost = oracle.State(d, n, L, st["x"], st["m"], st["v"], st["werr"], st["serr"])
-    run = DeviceRun(d, n, L, DEV, state={k: torch.from_numpy(v) for k, v in st.items()})
+    run = DeviceRun(d, n, L, DEV, deferred=deferred, state={k: torch.from_numpy(v) for k, v in st.items()})
     return run, ost
+
+
+def settle(run, ost, tag, deferred, now):
+    """With the errors deferred they are final only after apms_finalize: materialise and compare them `now`
+    (mid-run: the run then goes on from final buffers) or leave them pending."""
+    if deferred and now:
+        run.finalize()
+        torch.cuda.synchronize()
+        same(host(run.werr), ost.werr, tag + " worker_err after finalize")
+        same(host(run.serr), ost.serr, tag + " server_err after finalize")
+
+
+MODES = [0, B.APMS_DEFER_ERRORS]
+MODE_IDS = ["eager", "defer-errors"]
 
 
 CASES = [
@@ -66,19 +82,23 @@ CASES = [
 ]
 
 
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("n,L,C,K", CASES)
-def test_topk_trajectory(n, L, C, K):
+def test_topk_trajectory(n, L, C, K, deferred):
+    """Eager: the kept positions of both error buffers are zeroed by the call.  APMS_DEFER_ERRORS: they stay in
+    and the next call (or apms_finalize: after step 1 and at the end) reads them as zero; same bits."""
     d = L * C
     wl = W.Workload("topk", 2, d=d, n=n, chunk=L, steps=4)
     st = W.host_state(wl)
     st["werr"] = np.random.default_rng(L + K).normal(0, 3e-3, (n, d)).astype(F)
-    run, ost = make(d, n, L, st)
+    run, ost = make(d, n, L, st, deferred)
     for step in range(wl.steps):
-        say("n=%d L=%d C=%d K=%d step %d" % (n, L, C, K, step))
+        say("n=%d L=%d C=%d K=%d mode %d step %d" % (n, L, C, K, deferred, step))
         g = W.host_grad(wl, step)
         run.step_topk(torch.from_numpy(g).to(DEV), K, wl.beta, wl.lr, wl.eps)
         ost.step_topk(g, K, wl.beta, wl.lr, wl.eps)
-        compare(run, ost, "step %d" % step)
+        compare(run, ost, "step %d" % step, errors=not deferred)
+        settle(run, ost, "step %d" % step, deferred, now=step in (1, wl.steps - 1))
     run.close()
 
 
@@ -101,8 +121,9 @@ def test_topk_changing_K_between_steps():
     run.close()
 
 
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("K", [1, 100, 1500, 3000, 8000])
-def test_topk_ties(K):
+def test_topk_ties(K, deferred):
     """Values from a five-element set, so almost everything ties: the kept set is decided by the index rule,
     through both radix selects (the threshold falls inside a large group of equal magnitudes)."""
     n, L, C = 3, 4096 * 2 + 224, 2
@@ -110,20 +131,22 @@ def test_topk_ties(K):
     rng = np.random.default_rng(K)
     z = np.zeros
     st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=z((n, d), F), serr=z(d, F))
-    run, ost = make(d, n, L, st)
+    run, ost = make(d, n, L, st, deferred)
     for step in range(3):
-        say("ties K=%d step %d" % (K, step))
+        say("ties K=%d mode %d step %d" % (K, deferred, step))
         g = (rng.integers(-2, 3, (n, d)) * 0.25).astype(F)
         if step == 1:
             g[:] = 0.0                                        # a step where the new information is all zero
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.5, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.5, 1e-3, 1e-8)
-        compare(run, ost, "ties step %d" % step)
+        compare(run, ost, "ties step %d" % step, errors=not deferred)
+        settle(run, ost, "ties step %d" % step, deferred, now=step == 2)
     run.close()
 
 
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
 @pytest.mark.parametrize("level", ["threshold", "above", "below"])
-def test_topk_one_constant_tile_among_random_ones(level):
+def test_topk_one_constant_tile_among_random_ones(level, deferred):
     """One tile of one (worker, chunk) pair holds 4096 equal magnitudes at, above or below the chunk's
     threshold while everything else is random: that pair's tile has more candidates than slots when the
     constant shares the threshold's level-0 bin, so the pair takes the full passes and its neighbours the
@@ -138,15 +161,16 @@ def test_topk_one_constant_tile_among_random_ones(level):
     lo = L + 4096 * 2                                         # worker 1, chunk 1, tile 2
     werr[1, lo:lo + 4096] = const * np.where(np.arange(4096) % 3 == 0, -1.0, 1.0).astype(F)
     st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=werr, serr=z(d, F))
-    run, ost = make(d, n, L, st)
-    for step in range(2):
-        say("constant tile (%s) step %d" % (level, step))
+    run, ost = make(d, n, L, st, deferred)
+    for step in range(3):
+        say("constant tile (%s) mode %d step %d" % (level, deferred, step))
         g = rng.normal(0, 1e-2, (n, d)).astype(F)
         if step == 0:
             g[1, lo:lo + 4096] = 0.0
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
-        compare(run, ost, "constant tile (%s) step %d" % (level, step))
+        compare(run, ost, "constant tile (%s) step %d" % (level, step), errors=not deferred)
+        settle(run, ost, "constant tile (%s) step %d" % (level, step), deferred, now=step == 2)
     run.close()
 
 
@@ -274,6 +298,38 @@ def test_topk_refused_while_onebit_state_is_pending():
     assert ei.value.status == B.APMS_ESTATE
     run.finalize()
     run.step_topk(g, K, 0.9, 1e-4, 1e-8)
+    torch.cuda.synchronize()
+    run.close()
+
+
+def test_topk_deferred_errors_state_machine():
+    """A buffer a top-k call left in deferred form is read correctly only by the next top-k call on it or by
+    apms_finalize: the 1-bit calls, and top-k calls on another buffer, are refused until then."""
+    n, L, C, K = 2, 4096 * 2, 2, 50
+    d = L * C
+    wl = W.Workload("topk-defer", 2, d=d, n=n, chunk=L)
+    st = W.host_state(wl)
+    run, ost = make(d, n, L, st, B.APMS_DEFER_ERRORS)
+    g = W.host_grad(wl, 0)
+    gd = torch.from_numpy(g).to(DEV)
+    run.step_topk(gd, K, 0.9, 1e-4, 1e-8)
+    ost.step_topk(g, K, 0.9, 1e-4, 1e-8)
+    other = torch.zeros_like(run.werr)
+    for call in (lambda: run.compress(gd, 0.9),                                      # 1-bit worker call
+                 lambda: run.server_reduce(),                                       # 1-bit server call
+                 lambda: B.apms_topk_compress(run.ctx, run.m, gd, other, run.idx, run.val, K, 0.9)):
+        with pytest.raises(B.ApmsError) as ei:
+            call()
+        assert ei.value.status == B.APMS_ESTATE
+    # still in deferred form: kept positions hold their values, so the buffer differs from the final error there
+    assert not np.array_equal(host(run.werr), ost.werr)
+    # switching to eager while pending: the next call reads the deferred form and leaves final buffers
+    B.apms_set_deferral(run.ctx, 0)
+    g = W.host_grad(wl, 1)
+    run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-4, 1e-8)
+    ost.step_topk(g, K, 0.9, 1e-4, 1e-8)
+    compare(run, ost, "eager after deferred")
+    run.step(gd, 0.9, 1e-4, 1e-8)                                                   # nothing pending: the 1-bit path runs
     torch.cuda.synchronize()
     run.close()
 
