@@ -201,7 +201,7 @@ int apms_set_gather_mode(apms_ctx *ctx, int mode);
  * APMS_IMPLICIT_MOMENTUM (only together with APMS_DEFER_GATHER; EINVAL otherwise).  The momentum is
  * kept ONLY as the server's sign words and scales: the apms_compress that consumes a pending gather
  * decodes them and writes nothing to m, so m[n][d] is never touched by a step (4n fewer bytes written
- * per parameter).  This departs from the state model "per-worker fp32 momentum resident in memory":
+ * per parameter).  This departs from a state model in which every worker holds its fp32 momentum in memory:
  * m is defined only if apms_finalize(m) is called between apms_apply and the next apms_compress.
  *
  * While a buffer is pending its contents are not final: call apms_finalize before reading it
@@ -232,7 +232,7 @@ int apms_warmup_step(apms_ctx *ctx, float *x, float *m, float *v, const float *g
                      float lr, float beta1, float beta2, float eps, int64_t t, void *stream);
 
 /*
- * The same step with 16-bit gradients (Section 5.1 reports "float16 type training"): g is [n][d]
+ * The same step with 16-bit gradients (Section 5.1 trains with 16-bit floating-point values): g is [n][d]
  * binary16 or bfloat16 values (grad_format = APMS_GRAD_F16 / APMS_GRAD_BF16).  Every value is widened
  * to binary32 exactly, then the arithmetic is that of apms_warmup_step.  EINVAL for another format.
  */

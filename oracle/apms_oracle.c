@@ -393,7 +393,7 @@ int apms_oracle_freeze(int64_t d, int32_t n, const float *m_warm, float *m,
 }
 
 /* ------------------------------------------------------------------------ */
-/* 16-bit gradient inputs (Section 5.1 mentions "float16 type training").   */
+/* 16-bit gradient inputs (Section 5.1 trains in a 16-bit float type).       */
 /* ------------------------------------------------------------------------ */
 
 #define APMS_ORACLE_GRAD_F16 1  /* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits */
