@@ -163,8 +163,8 @@ struct DeviceScope {
 };
 
 void free_topk_scratch(apms_ctx* c) {
-    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.tile_counts, c->topk.tile_split,
-                      c->topk.slots};
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.near, c->topk.tile_counts,
+                      c->topk.tile_split, c->topk.slots};
     for (void* a : arrays)
         if (a) (void)hipFree(a);
     c->topk = {};
@@ -178,7 +178,8 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
     const int64_t guesses = pairs + c->C;                     // the worker call's pairs, then the server call's chunks
-    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords) + 3 * guesses) * 4 + 2 * tiles * 4;
+    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords + 2 * apms::kTopkNearCap) + 3 * guesses) * 4 +
+                          2 * tiles * 4;
     const int32_t want = apms::topk_slots_for(K_max, c->L);
     if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
     hipError_t e = hipDeviceSynchronize();                     // kernels of earlier calls may still use the scratch
@@ -188,6 +189,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), guesses * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.keep), guesses * 8);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.near), pairs * apms::kTopkNearCap * 8);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
         if (e != hipSuccess) {

@@ -28,6 +28,7 @@ constexpr int kTopkStateWords = 16;    // per-pair selection state, see topk.hip
 constexpr int kTopkTile = 4096;        // elements per tile of the split / emit / server / gather kernels
 constexpr int kTopkMinSlots = 64;      // slots per tile: a power of two in this range, see topk_slots_for
 constexpr int kTopkMaxSlots = 512;
+constexpr int kTopkNearCap = 1024;     // entries of a pair's near list, see topk_near_kernel
 
 // Slots per tile for keeping K of L elements per chunk: room for three times the tile's expected share of
 // the kept elements (those above the threshold's level-0 bin plus the bin's own, typically under twice the
@@ -49,6 +50,8 @@ inline int32_t topk_slots_for(int64_t K, int64_t L) {
 //   guess       [pairs + C] u32          the first pass's guess of that bin (less one) from the previous call: the
 //                                        worker call's n * C entries, then the server call's C;
 //                                        0xFFFFFFFF in a new context and whenever the slots are re-allocated
+//   near        [pairs][kTopkNearCap] uint2   the slot entries that share the top 22 key bits of the pair's threshold:
+//                                        (chunk-local index, key), in no particular order
 //   keep        [pairs + C] uint2        {T, idxT} of the last call per pair, for an error buffer left in deferred
 //                                        form (APMS_DEFER_ERRORS): worker pairs, then the server's chunks
 struct TopkScratch {
@@ -56,6 +59,7 @@ struct TopkScratch {
     uint32_t* state;
     uint32_t* guess;
     uint2* keep;
+    uint2* near;
     uint32_t* tile_counts;
     uint32_t* tile_split;
     uint2* slots;

@@ -42,6 +42,9 @@ enum : int {
     kStOverflow = 8,      // 1 if a tile of this pair had more entries than slots: full passes instead
     kStResplit = 9,       // 1 if the pair's slots have to be filled again, from the threshold bin now known
     kStRehist = 10,       // 1 if the level-0 histogram of the first pass did not reach down to the threshold bin
+    kStNearCount = 11,    // slot entries that share the threshold's top 22 key bits (appended to the near list)
+    kStNearOverflow = 12, // 1 if there were more of them than the near list holds: tie levels and counts from the slots
+    kStTieDone = 13,      // 1 if kStIdxT and the per-tile counts were settled from the near list
 };
 
 constexpr uint32_t kNoGuess = 0xFFFFFFFFu;      // guess[pair]: no earlier call to go by
@@ -153,15 +156,31 @@ __device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int
 }
 
 constexpr int kTileRows = kTopkTile / (kThreads * 4);   // 128-bit rows per thread per tile, plain layout
-constexpr int kServerStage = 2048;                       // entries of the server kernel's LDS stage (16 KB)
+constexpr int kServerStage = 1024;                       // entries of the server kernel's LDS stage (8 KB)
 constexpr int kRowStride = kThreads * 4;
 
 // Flush a workgroup's LDS histogram into the pair's global histogram (non-zero bins only).
-__device__ __forceinline__ void flush_histogram(const uint32_t* lds_hist, uint32_t* __restrict__ hist) {
-    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) {
+__device__ __forceinline__ void flush_histogram(const uint32_t* lds_hist, uint32_t* __restrict__ hist,
+                                                int bins = kTopkBins) {
+    for (int b = threadIdx.x; b < bins; b += kThreads) {
         const uint32_t c = lds_hist[b];
         if (c) atomicAdd(&hist[b], c);
     }
+}
+
+// The first pass counts only the bins at or above its guess, and ordinary data reaches a few dozen bins above
+// the threshold's (8 bins per binade): a workgroup keeps a window of kHistWindow bins starting at the guessed
+// one in LDS and sends the rare element beyond it to the pair's histogram directly.
+constexpr int kHistWindow = 256;
+static_assert(kHistWindow == kThreads, "one window bin per thread");
+__device__ __forceinline__ void count_in_window(uint32_t* lds_window, uint32_t* __restrict__ hist, uint32_t guessed,
+                                                uint32_t bin) {
+    const uint32_t rel = bin - guessed;                        // callers pass bins at or above the guessed one only
+    if (rel < static_cast<uint32_t>(kHistWindow)) atomicAdd(&lds_window[rel], 1u); else atomicAdd(&hist[bin], 1u);
+}
+__device__ __forceinline__ void flush_window(const uint32_t* lds_window, uint32_t* __restrict__ hist, uint32_t guessed) {
+    const uint32_t c = lds_window[threadIdx.x];
+    if (c) atomicAdd(&hist[guessed + threadIdx.x], c);         // counted, so the bin exists
 }
 
 // Copies the marked elements of a tile (bit 4*r + c of take_mask: element c of row r of this thread; packed:
@@ -205,6 +224,9 @@ __device__ __forceinline__ uint32_t write_tile_slots(const f32x4 (&v)[kTileRows]
 // and the extra entries fail every later test; if it is (the counted bins hold fewer than K elements), the
 // pair is marked kStRehist and takes a full histogram pass; where the guess was too high, or a tile
 // overflowed on it, the pair is marked kStResplit and topk_split_kernel fills its slots again.
+// One tile per workgroup: taking several tiles in a loop (one histogram flush for all of them, or with the
+// next tile's loads requested ahead) was measured 3 to 10 % slower, like the 1-bit worker kernel this pass
+// streams best as many short-lived workgroups.
 __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __restrict__ m,
                                                                  const float* __restrict__ g,
                                                                  float* __restrict__ e, uint32_t* __restrict__ hist,
@@ -215,11 +237,12 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
                                                                  const uint2* __restrict__ prev_keep,
                                                                  int64_t d, int64_t L, int32_t C,
                                                                  int32_t tiles_per_chunk, float beta, float omb) {
-    __shared__ uint32_t lds_hist[kTopkBins];
+    __shared__ uint32_t lds_window[kHistWindow];
     __shared__ uint64_t lds_scan[kWaves];
-    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
+    lds_window[threadIdx.x] = 0u;
     __syncthreads();
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
+    uint32_t* pair_hist = hist + tr.pair * kTopkBins;
     const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
     const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);   // error buffer in deferred form?
     const uint32_t guessed = guess[tr.pair];
@@ -244,7 +267,7 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
             u[r][c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const uint32_t key = key_of(u[r][c]);
             if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
-                atomicAdd(&lds_hist[key >> 20], 1u);
+                count_in_window(lds_window, pair_hist, guessed, key >> 20);
                 take_mask |= 1u << (4 * r + c);
                 ++count;
             }
@@ -254,12 +277,12 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
     }
     const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
     const uint32_t marked = write_tile_slots(u, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
-                                             slots_per_tile);        // its barriers also cover lds_hist
+                                             slots_per_tile);        // its barriers also cover lds_window
     if (threadIdx.x == 0) {
         tile_split[tile_id] = marked;
         if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
     }
-    flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
+    flush_window(lds_window, pair_hist, guessed);
 }
 
 // ------------------------------------------------------------------------
@@ -290,6 +313,18 @@ __global__ __launch_bounds__(kThreads) void topk_tile_offsets_kernel(const uint3
 
 // Like the worker's first pass, it counts and slots only the elements at or above a guessed level-0 bin
 // (guess[chunk], the server's own table).
+//
+// The decoded messages have to be added position by position in worker order, and walking the workers one
+// after the other straight from memory is a chain of dependent loads (where a worker's stretch for this tile
+// starts, then its entries) per worker.  So, `workers_per_batch` workers at a time (the host sizes the batch
+// so that its entries usually fit the stage): (A) one thread per worker fetches its stretch's bounds, a
+// workgroup scan lays the stretches out back to back; (B) all threads copy the entries of all those workers
+// into an LDS stage at once; (C) each wave, which owns a quarter of the tile's positions, walks the stage
+// worker by worker and adds the entries that fall into its quarter.  A wave's LDS operations complete in
+// program order, and positions are unique inside one worker's list, so the running sums see the workers in
+// order without any barrier in (C).  The kernel waits on memory in (A) and again in (B), so what it reaches
+// depends on how many workgroups a CU holds: its LDS is kept to 26 KB (six per CU).
+constexpr int kServerBatchMax = 64;                          // workers per batch at most
 __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t* __restrict__ idx,
                                                                  const float* __restrict__ val,
                                                                  float* __restrict__ serr, uint32_t* __restrict__ hist,
@@ -300,17 +335,19 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
                                                                  uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                  const uint2* __restrict__ prev_keep,
                                                                  int64_t d, int64_t L, int32_t C, int32_t n,
-                                                                 int32_t K, int32_t tiles_per_chunk, float inv_n) {
-    __shared__ uint32_t lds_hist[kTopkBins];
+                                                                 int32_t K, int32_t tiles_per_chunk,
+                                                                 int32_t workers_per_batch, float inv_n) {
+    __shared__ uint32_t lds_window[kHistWindow];
     __shared__ uint64_t lds_scan[kWaves];
     __shared__ float acc[kTopkTile];
     __shared__ uint2 stage[kServerStage];                      // (tile-local position, value bits), worker-major
-    __shared__ uint32_t stage_first[kThreads];                 // per worker of the batch: first list entry of the tile
-    __shared__ uint32_t stage_start[kThreads + 1];             // ... and where its entries start in the stage
+    __shared__ uint32_t stage_first[kServerBatchMax];          // per worker of the batch: first list entry of the tile
+    __shared__ uint32_t stage_start[kServerBatchMax + 1];      // ... and where its entries start in the stage
     __shared__ uint32_t stage_scan[kWaves];
-    for (int b = threadIdx.x; b < kTopkBins; b += kThreads) lds_hist[b] = 0u;
+    lds_window[threadIdx.x] = 0u;
     for (int j = threadIdx.x; j < kTopkTile; j += kThreads) acc[j] = 0.0f;
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // slices = 1: pair = chunk
+    uint32_t* pair_hist = hist + tr.pair * kTopkBins;
     const int64_t tile_lo = tr.tile * kTopkTile;
     const uint32_t guessed = guess[tr.pair];
     const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
@@ -324,21 +361,18 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
         if (off < L) ve[r] = load_stream(serr + tr.base + off);
     }
     __syncthreads();
-    // The decoded messages have to be added position by position in worker order, and walking the workers one
-    // after the other straight from memory is a chain of dependent loads (where a worker's stretch for this
-    // tile starts, then its entries) per worker.  So, kThreads workers at a time: (A) one thread per worker
-    // fetches its stretch's bounds, a workgroup scan lays the stretches out back to back; (B) all threads
-    // copy the entries of all those workers into an LDS stage at once; (C) each wave, which owns a quarter of
-    // the tile's positions, walks the stage worker by worker and adds the entries that fall into its quarter.
-    // A wave's LDS operations complete in program order, and positions are unique inside one worker's list,
-    // so the running sums see the workers in order without any barrier in (C).
     {
-        const int lane = threadIdx.x & (kWaveSize - 1);
+        const uint32_t lane = threadIdx.x & (kWaveSize - 1);
         const uint32_t wave = threadIdx.x >> 6;
         constexpr uint32_t kQuarterShift = 10;                 // kTopkTile / kWaves = 1024 positions per wave
         static_assert((kTopkTile / kWaves) == (1 << kQuarterShift), "a wave's share of the tile");
-        for (int32_t i0 = 0; i0 < n; i0 += kThreads) {
-            const int32_t batch = min(n - i0, static_cast<int32_t>(kThreads));
+        const auto add_entry = [&](uint2 entry) {
+            const uint32_t j = entry.x;
+            if (j < static_cast<uint32_t>(kTopkTile) && (j >> kQuarterShift) == wave)
+                acc[j] = acc[j] + __builtin_bit_cast(float, entry.y);
+        };
+        for (int32_t i0 = 0; i0 < n; i0 += workers_per_batch) {
+            const int32_t batch = min(n - i0, workers_per_batch);
             // (A)
             uint32_t first = 0, count = 0;
             if (static_cast<int32_t>(threadIdx.x) < batch) {
@@ -350,9 +384,11 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
             }
             uint32_t total;
             const uint32_t start = block_exclusive_scan_u32(count, stage_scan, total);
-            stage_first[threadIdx.x] = first;
-            stage_start[threadIdx.x] = start;
-            if (threadIdx.x == 0) stage_start[kThreads] = total;
+            if (threadIdx.x < kServerBatchMax) {
+                stage_first[threadIdx.x] = first;
+                stage_start[threadIdx.x] = start;              // = total for the threads beyond the batch
+            }
+            if (threadIdx.x == 0) stage_start[kServerBatchMax] = total;
             __syncthreads();
             if (total <= static_cast<uint32_t>(kServerStage)) {
                 // (B) entry e of the stage belongs to the worker w with stage_start[w] <= e < stage_start[w + 1]
@@ -367,25 +403,33 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
                     stage[e] = make_uint2(idx[src] - static_cast<uint32_t>(tile_lo), __builtin_bit_cast(uint32_t, value));
                 }
                 __syncthreads();
-                // (C)
-                for (int32_t w = 0; w < batch; ++w) {
-                    const uint32_t lo = stage_start[w], hi = stage_start[w + 1];
-                    for (uint32_t e = lo + lane; e < hi; e += kWaveSize) {
-                        const uint2 entry = stage[e];
-                        const uint32_t j = entry.x;
-                        if (j < static_cast<uint32_t>(kTopkTile) && (j >> kQuarterShift) == wave)
-                            acc[j] = acc[j] + __builtin_bit_cast(float, entry.y);
+                // (C) four workers' first 64 entries are read from the stage together, then added in worker order
+                constexpr int kAhead = 4;
+                for (int32_t w = 0; w < batch; w += kAhead) {
+                    uint32_t bound[kAhead + 1];
+                    uint2 entry[kAhead];
+#pragma unroll
+                    for (int u = 0; u <= kAhead; ++u) bound[u] = stage_start[min(w + u, static_cast<int32_t>(kServerBatchMax))];
+#pragma unroll
+                    for (int u = 0; u < kAhead; ++u) {
+                        const uint32_t e = bound[u] + lane;
+                        entry[u] = make_uint2(0xFFFFFFFFu, 0u);
+                        if (e < bound[u + 1]) entry[u] = stage[e];
+                    }
+#pragma unroll
+                    for (int u = 0; u < kAhead; ++u) {
+                        add_entry(entry[u]);
+                        for (uint32_t e = bound[u] + lane + kWaveSize; e < bound[u + 1]; e += kWaveSize) add_entry(stage[e]);
                     }
                 }
             } else {
-                // more entries than the stage holds (K far above what a tile usually carries): worker by worker
+                // more entries than the stage holds (a K far above what the batch was sized for): worker by worker
                 for (int32_t w = 0; w < batch; ++w) {
                     const int64_t list = (static_cast<int64_t>(i0 + w) * C + tr.pair) * K;
                     const uint32_t lo = stage_first[w], hi = lo + (stage_start[w + 1] - stage_start[w]);
                     for (uint32_t t = lo + lane; t < hi; t += kWaveSize) {
-                        const uint32_t j = idx[list + t] - static_cast<uint32_t>(tile_lo);
                         const float value = val[list + t];
-                        if (j < static_cast<uint32_t>(kTopkTile) && (j >> kQuarterShift) == wave) acc[j] = acc[j] + value;
+                        add_entry(make_uint2(idx[list + t] - static_cast<uint32_t>(tile_lo), __builtin_bit_cast(uint32_t, value)));
                     }
                 }
             }
@@ -411,7 +455,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
             const float value = ubar[r][c];
             const uint32_t key = key_of(value);
             if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
-                atomicAdd(&lds_hist[key >> 20], 1u);
+                count_in_window(lds_window, pair_hist, guessed, key >> 20);
                 take_mask |= 1u << (4 * r + c);
                 ++count;
             }
@@ -421,12 +465,12 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
     }
     const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
     const uint32_t marked = write_tile_slots(ubar, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
-                                             slots_per_tile);        // its barriers also cover lds_hist
+                                             slots_per_tile);        // its barriers also cover lds_window
     if (threadIdx.x == 0) {
         tile_split[tile_id] = marked;
         if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
     }
-    flush_histogram(lds_hist, hist + tr.pair * kTopkBins);
+    flush_window(lds_window, pair_hist, guessed);
 }
 
 // ------------------------------------------------------------------------
@@ -448,6 +492,7 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
     uint32_t* h = hist + pair * kTopkBins;
     uint32_t* st = state + pair * kTopkStateWords;
     if (only_rehist && st[kStRehist] == 0u) return;            // whole workgroup
+    if (kIdx && st[kStTieDone] != 0u) return;                  // topk_resolve_kernel has settled kStIdxT
     const bool tie_needed = kIdx ? (st[kStTieNeeded] != 0u) : true;
     if (kIdx && !tie_needed) {                                 // every element equal to T is kept
         if (level == 2 && threadIdx.x == 0) st[kStIdxT] = 0xFFFFFFFFu;
@@ -546,16 +591,20 @@ __device__ __forceinline__ void hist_tile(const float* __restrict__ buf, uint32_
 // The kernels for the rare cases (ties to break, pairs that overflowed their slots) run on a small grid in
 // which every workgroup visits the flagged pairs and strides over their tiles.  The flags are read kThreads
 // pairs at a time, one per thread, so a launch with nothing to do costs one state read per thread.  A pair
-// is flagged if both state words named are non-zero (name one word twice to test it alone).
+// is flagged if both state words named are non-zero (name one word twice to test it alone) and, if
+// `zero_word` names one, that word is zero.
 // `body(pair)` may contain workgroup barriers: all threads see the same flags.
 template <class Body>
 __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ state, int64_t pairs, int flag_word,
-                                                  int second_flag_word, Body body) {
+                                                  int second_flag_word, int zero_word, Body body) {
     __shared__ uint32_t flags[kThreads];
     for (int64_t p0 = 0; p0 < pairs; p0 += kThreads) {
         const int64_t p = p0 + threadIdx.x;
-        const uint32_t mine = (p < pairs && state[p * kTopkStateWords + flag_word] != 0u &&
-                               state[p * kTopkStateWords + second_flag_word] != 0u) ? 1u : 0u;
+        uint32_t mine = 0u;
+        if (p < pairs) {
+            const uint32_t* st = state + p * kTopkStateWords;
+            mine = (st[flag_word] != 0u && st[second_flag_word] != 0u && (zero_word < 0 || st[zero_word] == 0u)) ? 1u : 0u;
+        }
         if (!__syncthreads_or(mine != 0u)) continue;           // same answer in every thread
         flags[threadIdx.x] = mine;
         __syncthreads();
@@ -563,6 +612,11 @@ __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ s
             if (flags[q] != 0u) body(p0 + q);
         __syncthreads();                                       // before the next round overwrites the flags
     }
+}
+template <class Body>
+__device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ state, int64_t pairs, int flag_word,
+                                                  int second_flag_word, Body body) {
+    for_flagged_pairs(state, pairs, flag_word, second_flag_word, -1, body);
 }
 
 // The whole level-0 histogram of the pairs marked kStRehist (their first pass counted only the bins at or
@@ -645,10 +699,75 @@ __global__ __launch_bounds__(kThreads) void topk_split_kernel(const float* __res
     });
 }
 
+// The kernels that read the slots take a block of consecutive tiles of one pair per workgroup.  Walking the
+// tiles one after the other is a chain of dependent loads per tile (how many slots it filled, then the
+// slots), and a tile fills about a hundred slots: too little per step to hide that latency.  So the
+// workgroup first reads all its tiles' counts into LDS with one load per thread, and then every wave takes
+// kSlotUnroll tiles at a time and requests the first 2 * 64 slots of all of them before it looks at any.
+constexpr int kSlotUnroll = 4;
+constexpr int kSlotDepth = 2;                                 // 64-entry rounds requested up front per tile
+
+// counts[q] = filled slots of tile t0 + q of the pair (0 beyond the pair's last tile), for q < block_tiles
+// <= kThreads.  Ends with a workgroup barrier.
+__device__ __forceinline__ void load_slot_counts(const uint32_t* __restrict__ tile_split, int32_t slots_per_tile,
+                                                 int64_t pair, int32_t t0, int32_t tiles_per_chunk, int block_tiles,
+                                                 uint32_t* counts /* LDS */) {
+    if (static_cast<int>(threadIdx.x) < block_tiles) {
+        const int32_t tile = t0 + static_cast<int32_t>(threadIdx.x);
+        counts[threadIdx.x] = tile < tiles_per_chunk
+                                  ? min(tile_split[pair * tiles_per_chunk + tile], static_cast<uint32_t>(slots_per_tile))
+                                  : 0u;
+    }
+    __syncthreads();
+}
+
+// For the tiles q = first, first + 1, ... < first + kSlotUnroll of the block (q indexes `counts`): calls
+// visit(q, e, entry, valid) for every 64-entry round of every tile, in slot order per tile, by all 64 lanes
+// (valid = false for lanes beyond the tile's count), so visit may vote across the wave.
+template <class Visit>
+__device__ __forceinline__ void for_slots_of_tiles(const uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                   int64_t tile_id0 /* of q = 0 */, const uint32_t* counts, int first,
+                                                   Visit visit) {
+    const uint32_t lane = threadIdx.x & (kWaveSize - 1);
+    uint32_t cnt[kSlotUnroll];
+    uint2 entry[kSlotUnroll][kSlotDepth];
+#pragma unroll
+    for (int u = 0; u < kSlotUnroll; ++u) {
+        cnt[u] = counts[first + u];
+        const uint2* mine = slots + (tile_id0 + first + u) * slots_per_tile;
+#pragma unroll
+        for (int h = 0; h < kSlotDepth; ++h) {
+            const uint32_t e = lane + h * kWaveSize;
+            entry[u][h] = make_uint2(0u, 0u);
+            if (e < cnt[u]) entry[u][h] = mine[e];
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kSlotUnroll; ++u) {
+#pragma unroll
+        for (int h = 0; h < kSlotDepth; ++h) {
+            const uint32_t e = lane + h * kWaveSize;
+            if (static_cast<uint32_t>(h * kWaveSize) < cnt[u]) visit(first + u, e, entry[u][h], e < cnt[u]);   // wave-uniform test
+        }
+        const uint2* mine = slots + (tile_id0 + first + u) * slots_per_tile;
+        for (uint32_t e0 = kSlotDepth * kWaveSize; e0 < cnt[u]; e0 += kWaveSize) {   // a tile with more entries: rare
+            const uint32_t e = e0 + lane;
+            uint2 late = make_uint2(0u, 0u);
+            if (e < cnt[u]) late = mine[e];
+            visit(first + u, e, late, e < cnt[u]);
+        }
+    }
+}
+
 // Key levels 1 and 2 (kIdx = false) and the index levels of the tie selection (kIdx = true: only pairs with
-// a tie to break) from the slots.  One workgroup takes kCandTilesPerBlock consecutive tiles of one pair, a
-// wave per tile at a time, and accumulates the level's digit histogram in LDS.
-constexpr int kCandTilesPerBlock = 256;
+// a tie to break) from the slots.  One workgroup takes kCandTilesPerBlock consecutive tiles of one pair,
+// kCandSubBlock at a time, accumulates the level's digit histogram in LDS and flushes it once (one
+// device-wide atomic per populated bin: level 1 populates nearly all of them, hence the large blocks).
+constexpr int kCandSubBlock = 256;
+constexpr int kCandTilesPerBlock = 256;                      // key levels
+constexpr int kTieTilesPerBlock = 256;                       // tie levels: few pairs, few matches: more workgroups each
+static_assert(kCandSubBlock <= kThreads && kCandSubBlock % (kWaves * kSlotUnroll) == 0 &&
+              kCandTilesPerBlock % kCandSubBlock == 0 && kTieTilesPerBlock % kCandSubBlock == 0, "tile blocks");
 template <bool kIdx>
 __global__ __launch_bounds__(kThreads) void topk_cand_hist_kernel(const uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                   const uint32_t* __restrict__ tile_split,
@@ -657,37 +776,141 @@ __global__ __launch_bounds__(kThreads) void topk_cand_hist_kernel(const uint2* _
                                                                   int32_t tiles_per_chunk, int32_t blocks_per_pair,
                                                                   int level) {
     __shared__ uint32_t lds_hist[kTopkBins];
+    __shared__ uint32_t lds_count[kCandSubBlock];
     const int64_t pair = blockIdx.x / blocks_per_pair;
     const int32_t b = static_cast<int32_t>(blockIdx.x - pair * blocks_per_pair);
     const uint32_t* st = state + pair * kTopkStateWords;
     if (st[kStOverflow] != 0u) return;                         // whole workgroup: the full passes take this pair
-    if (kIdx && st[kStTieNeeded] == 0u) return;
+    if (kIdx && (st[kStTieNeeded] == 0u || st[kStTieDone] != 0u)) return;
     for (int q = threadIdx.x; q < kTopkBins; q += kThreads) lds_hist[q] = 0u;
-    __syncthreads();
     const Level lv = kIdx ? idx_level(level) : key_level(level);
     const uint32_t digit_mask = (1u << lv.bits) - 1u;
     const uint32_t prefix = kIdx ? (level == 0 ? 0u : st[kStIdxPrefix]) : st[kStPrefix];
     const uint32_t T = st[kStKeyT];                            // final only when kIdx
+    const int wave = threadIdx.x >> 6;
+    constexpr int kBlockTiles = kIdx ? kTieTilesPerBlock : kCandTilesPerBlock;
+    const int32_t block_end = min((b + 1) * kBlockTiles, tiles_per_chunk);
+    for (int32_t t0 = b * kBlockTiles; t0 < block_end; t0 += kCandSubBlock) {
+        load_slot_counts(tile_split, slots_per_tile, pair, t0, tiles_per_chunk, kCandSubBlock, lds_count);   // barrier
+        const int sub_tiles = min(kCandSubBlock, tiles_per_chunk - t0);
+        for (int first = wave * kSlotUnroll; first < sub_tiles; first += kWaves * kSlotUnroll) {
+            for_slots_of_tiles(slots, slots_per_tile, pair * tiles_per_chunk + t0, lds_count, first,
+                               [&](int q, uint32_t, uint2 entry, bool valid) {
+                                   const uint32_t key = entry.y & 0x7FFFFFFFu;
+                                   if (kIdx) {
+                                       const uint32_t j = static_cast<uint32_t>(t0 + q) * kTopkTile + entry.x;
+                                       if (valid && key == T && (j & lv.match_mask) == prefix)
+                                           atomicAdd(&lds_hist[(j >> lv.shift) & digit_mask], 1u);
+                                   } else {
+                                       if (valid && (key & lv.match_mask) == prefix)
+                                           atomicAdd(&lds_hist[(key >> lv.shift) & digit_mask], 1u);
+                                   }
+                               });
+        }
+        __syncthreads();                                       // before the next round overwrites the counts
+    }
+    flush_histogram(lds_hist, hist + pair * kTopkBins);
+}
+
+// Key level 2 from the slots, and with it everything the rest of the selection needs from them.  The level-1
+// pick has fixed the top 22 bits of the threshold T; of a chunk's slot entries a few dozen share them (the
+// "near" entries), the others lie above (kept whatever the last 9 bits of T turn out to be) or below.  This
+// pass builds the level-2 histogram of the near entries, appends them to the pair's near list (in any order:
+// a counter in the state, entries beyond the list's capacity are only counted) and leaves the number of
+// entries above in tile_counts.  Ties at T and the kept elements among the near entries are then settled
+// from the list by topk_resolve_kernel, without further passes over the slots.
+__global__ __launch_bounds__(kThreads) void topk_near_kernel(const uint2* __restrict__ slots, int32_t slots_per_tile,
+                                                             const uint32_t* __restrict__ tile_split,
+                                                             uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
+                                                             uint32_t* __restrict__ tile_counts,
+                                                             uint2* __restrict__ near, int32_t tiles_per_chunk,
+                                                             int32_t blocks_per_pair) {
+    constexpr Level lv = key_level(2);
+    constexpr int kBins = 1 << lv.bits;
+    __shared__ uint32_t lds_hist[kBins];
+    __shared__ uint32_t lds_count[kCandSubBlock];
+    const int64_t pair = blockIdx.x / blocks_per_pair;
+    const int32_t b = static_cast<int32_t>(blockIdx.x - pair * blocks_per_pair);
+    uint32_t* st = state + pair * kTopkStateWords;
+    if (st[kStOverflow] != 0u) return;                         // whole workgroup: the full passes take this pair
+    for (int q = threadIdx.x; q < kBins; q += kThreads) lds_hist[q] = 0u;
+    const uint32_t prefix = st[kStPrefix];
     const int lane = threadIdx.x & (kWaveSize - 1);
     const int wave = threadIdx.x >> 6;
-    const int32_t t0 = b * kCandTilesPerBlock;
-    const int32_t t1 = min(t0 + kCandTilesPerBlock, tiles_per_chunk);
-    for (int32_t tile = t0 + wave; tile < t1; tile += kWaves) {
-        const int64_t tile_id = pair * tiles_per_chunk + tile;
-        const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
-        for (uint32_t e = lane; e < count; e += kWaveSize) {
-            const uint2 entry = slots[tile_id * slots_per_tile + e];
-            const uint32_t key = entry.y & 0x7FFFFFFFu;
-            if (kIdx) {
-                const uint32_t j = static_cast<uint32_t>(tile) * kTopkTile + entry.x;
-                if (key == T && (j & lv.match_mask) == prefix) atomicAdd(&lds_hist[(j >> lv.shift) & digit_mask], 1u);
-            } else {
-                if ((key & lv.match_mask) == prefix) atomicAdd(&lds_hist[(key >> lv.shift) & digit_mask], 1u);
-            }
+    uint2* my_near = near + pair * kTopkNearCap;
+    const int32_t block_end = min((b + 1) * kCandTilesPerBlock, tiles_per_chunk);
+    for (int32_t t0 = b * kCandTilesPerBlock; t0 < block_end; t0 += kCandSubBlock) {
+        load_slot_counts(tile_split, slots_per_tile, pair, t0, tiles_per_chunk, kCandSubBlock, lds_count);   // barrier
+        const int sub_tiles = min(kCandSubBlock, tiles_per_chunk - t0);
+        for (int first = wave * kSlotUnroll; first < sub_tiles; first += kWaves * kSlotUnroll) {
+            uint32_t above[kSlotUnroll] = {};
+            for_slots_of_tiles(slots, slots_per_tile, pair * tiles_per_chunk + t0, lds_count, first,
+                               [&](int q, uint32_t, uint2 entry, bool valid) {
+                                   const uint32_t key = entry.y & 0x7FFFFFFFu;
+                                   const uint32_t top = key & lv.match_mask;
+                                   above[q - first] += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(__ballot(valid && top > prefix))));
+                                   if (valid && top == prefix) {
+                                       atomicAdd(&lds_hist[key & (kBins - 1)], 1u);
+                                       const uint32_t at = atomicAdd(&st[kStNearCount], 1u);
+                                       if (at < static_cast<uint32_t>(kTopkNearCap))
+                                           my_near[at] = make_uint2(static_cast<uint32_t>(t0 + q) * kTopkTile + entry.x, key);
+                                   }
+                               });
+#pragma unroll
+            for (int u = 0; u < kSlotUnroll; ++u)
+                if (lane == 0 && first + u < sub_tiles) tile_counts[pair * tiles_per_chunk + t0 + first + u] = above[u];
         }
+        __syncthreads();                                       // before the next round overwrites the counts
     }
+    flush_histogram(lds_hist, hist + pair * kTopkBins, kBins);
+}
+
+// After the level-2 pick, one workgroup per pair: with T known, settles from the near list (i) the tie rule -
+// if only `left` of the elements equal to T may be kept, kStIdxT becomes the left-th smallest index among
+// them - and (ii) the per-tile kept counts, by adding the near entries that are kept to the counts of
+// entries above that topk_near_kernel left.  A pair whose near list overflowed is flagged instead and takes
+// the tie levels and the counts from the slots (topk_cand_hist_kernel<true>, topk_slot_count_kernel).
+__global__ __launch_bounds__(kThreads) void topk_resolve_kernel(uint32_t* __restrict__ state,
+                                                                const uint2* __restrict__ near,
+                                                                uint32_t* __restrict__ tile_counts,
+                                                                int32_t tiles_per_chunk) {
+    __shared__ uint2 lds_near[kTopkNearCap];
+    __shared__ uint32_t lds_idxT;
+    const int64_t pair = blockIdx.x;
+    uint32_t* st = state + pair * kTopkStateWords;
+    if (st[kStOverflow] != 0u) return;                         // whole workgroup: the full passes take this pair
+    const uint32_t count = st[kStNearCount];
+    if (count > static_cast<uint32_t>(kTopkNearCap)) {
+        if (threadIdx.x == 0) st[kStNearOverflow] = 1u;
+        return;
+    }
+    const uint32_t T = st[kStKeyT], left = st[kStIdxRemaining];
+    const bool tie_needed = st[kStTieNeeded] != 0u;
+    for (uint32_t i = threadIdx.x; i < count; i += kThreads) lds_near[i] = near[pair * kTopkNearCap + i];
+    if (threadIdx.x == 0) lds_idxT = 0xFFFFFFFFu;              // every element equal to T is kept
     __syncthreads();
-    flush_histogram(lds_hist, hist + pair * kTopkBins);
+    if (tie_needed) {
+        for (uint32_t i = threadIdx.x; i < count; i += kThreads) {
+            const uint2 mine = lds_near[i];
+            if (mine.y != T) continue;
+            uint32_t before = 0;                               // elements equal to T at lower indices
+            for (uint32_t k = 0; k < count; ++k) {
+                const uint2 other = lds_near[k];
+                before += (other.y == T && other.x < mine.x) ? 1u : 0u;
+            }
+            if (before + 1u == left) lds_idxT = mine.x;        // indices are distinct: exactly one thread
+        }
+        __syncthreads();
+    }
+    const uint32_t idxT = lds_idxT;
+    if (threadIdx.x == 0) {
+        st[kStIdxT] = idxT;
+        st[kStTieDone] = 1u;
+    }
+    for (uint32_t i = threadIdx.x; i < count; i += kThreads) {
+        const uint2 mine = lds_near[i];
+        if (kept(mine.y, mine.x, T, idxT)) atomicAdd(&tile_counts[pair * tiles_per_chunk + mine.x / kTopkTile], 1u);
+    }
 }
 
 // Key levels 1 and 2 for pairs that overflowed their slots: full passes over the buffer.
@@ -734,29 +957,38 @@ __global__ __launch_bounds__(kThreads) void topk_tie_hist_kernel(const float* __
 // Emission in index order: per-tile counts, scan, write.
 // ------------------------------------------------------------------------
 // Kept elements per tile, from the tile's slots (entries above the level-0 bin of T pass the test by
-// themselves).  A wave per tile.
+// themselves), for the pairs whose near list overflowed.  One workgroup per block of kEmitTilesPerBlock
+// consecutive tiles of one pair.
+constexpr int kEmitTilesPerBlock = 64;
+static_assert(kEmitTilesPerBlock <= kThreads && kEmitTilesPerBlock % (kWaves * kSlotUnroll) == 0, "tile blocks");
 __global__ __launch_bounds__(kThreads) void topk_slot_count_kernel(const uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                    const uint32_t* __restrict__ tile_split,
                                                                    const uint32_t* __restrict__ state,
                                                                    uint32_t* __restrict__ tile_counts,
-                                                                   int32_t tiles_per_chunk, int64_t tiles_total) {
+                                                                   int32_t tiles_per_chunk, int32_t blocks_per_pair) {
+    __shared__ uint32_t lds_count[kEmitTilesPerBlock];
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int64_t tile_id = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
-    if (tile_id >= tiles_total) return;
-    const int64_t pair = tile_id / tiles_per_chunk;
-    const uint32_t tile = static_cast<uint32_t>(tile_id - pair * tiles_per_chunk);
+    const int wave = threadIdx.x >> 6;
+    const int64_t pair = blockIdx.x / blocks_per_pair;
+    const int32_t t0 = static_cast<int32_t>(blockIdx.x - pair * blocks_per_pair) * kEmitTilesPerBlock;
     const uint32_t* st = state + pair * kTopkStateWords;
-    if (st[kStOverflow] != 0u) return;                         // whole wave: topk_count_walk_kernel takes this pair
+    if (st[kStOverflow] != 0u) return;                         // whole workgroup: topk_count_walk_kernel takes this pair
+    if (st[kStNearOverflow] == 0u) return;                     // topk_resolve_kernel has settled the counts
     const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
-    const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
-    uint32_t mine = 0;
-    for (uint32_t e = lane; e < count; e += kWaveSize) {
-        const uint2 entry = slots[tile_id * slots_per_tile + e];
-        mine += kept(entry.y & 0x7FFFFFFFu, tile * kTopkTile + entry.x, T, idxT) ? 1u : 0u;
-    }
+    load_slot_counts(tile_split, slots_per_tile, pair, t0, tiles_per_chunk, kEmitTilesPerBlock, lds_count);
+    const int block_tiles = min(kEmitTilesPerBlock, tiles_per_chunk - t0);
+    for (int first = wave * kSlotUnroll; first < block_tiles; first += kWaves * kSlotUnroll) {
+        uint32_t kept_in[kSlotUnroll] = {};
+        for_slots_of_tiles(slots, slots_per_tile, pair * tiles_per_chunk + t0, lds_count, first,
+                           [&](int q, uint32_t, uint2 entry, bool valid) {
+                               const uint32_t j = static_cast<uint32_t>(t0 + q) * kTopkTile + entry.x;
+                               const bool keep = valid && kept(entry.y & 0x7FFFFFFFu, j, T, idxT);
+                               kept_in[q - first] += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(__ballot(keep))));
+                           });
 #pragma unroll
-    for (int off = kWaveSize / 2; off > 0; off >>= 1) mine += static_cast<uint32_t>(__shfl_xor(static_cast<int>(mine), off));
-    if (lane == 0) tile_counts[tile_id] = mine;
+        for (int u = 0; u < kSlotUnroll; ++u)
+            if (lane == 0 && first + u < block_tiles) tile_counts[pair * tiles_per_chunk + t0 + first + u] = kept_in[u];
+    }
 }
 
 // The same from the buffer, for pairs that overflowed their slots.
@@ -804,8 +1036,8 @@ __global__ __launch_bounds__(kThreads) void topk_scan_kernel(uint32_t* __restric
 }
 
 // Writes the kept elements of a tile to the pair's (idx, val) list at the tile's offset, in index order,
-// and zeroes them in the buffer: what stays there is u - C[u].  From the slots (already in index order), a
-// wave per tile: a ballot over 64 entries at a time ranks the kept ones.
+// and (zero_kept) zeroes them in the buffer: what stays there is u - C[u].  From the slots (already in index
+// order): a ballot over 64 entries at a time ranks the kept ones.  Workgroups as in topk_slot_count_kernel.
 __global__ __launch_bounds__(kThreads) void topk_slot_emit_kernel(float* __restrict__ buf, const uint2* __restrict__ slots,
                                                                   int32_t slots_per_tile,
                                                                   const uint32_t* __restrict__ tile_split,
@@ -813,39 +1045,48 @@ __global__ __launch_bounds__(kThreads) void topk_slot_emit_kernel(float* __restr
                                                                   const uint32_t* __restrict__ tile_offsets,
                                                                   uint32_t* __restrict__ idx, float* __restrict__ val,
                                                                   int64_t d, int64_t L, int32_t C,
-                                                                  int32_t tiles_per_chunk, int64_t tiles_total,
+                                                                  int32_t tiles_per_chunk, int32_t blocks_per_pair,
                                                                   int64_t K, bool zero_kept) {
+    __shared__ uint32_t lds_count[kEmitTilesPerBlock];
+    __shared__ uint32_t lds_offset[kEmitTilesPerBlock];
     const int lane = threadIdx.x & (kWaveSize - 1);
-    const int64_t tile_id = static_cast<int64_t>(blockIdx.x) * kWaves + (threadIdx.x >> 6);
-    if (tile_id >= tiles_total) return;
-    const int64_t pair = tile_id / tiles_per_chunk;
-    const uint32_t tile = static_cast<uint32_t>(tile_id - pair * tiles_per_chunk);
+    const int wave = threadIdx.x >> 6;
+    const int64_t pair = blockIdx.x / blocks_per_pair;
+    const int32_t t0 = static_cast<int32_t>(blockIdx.x - pair * blocks_per_pair) * kEmitTilesPerBlock;
     const uint32_t* st = state + pair * kTopkStateWords;
-    if (st[kStOverflow] != 0u) return;                         // whole wave: topk_emit_walk_kernel takes this pair
+    if (st[kStOverflow] != 0u) return;                         // whole workgroup: topk_emit_walk_kernel takes this pair
     const uint32_t T = st[kStKeyT], idxT = st[kStIdxT];
     const int64_t slice = pair / C;
     float* chunk_buf = buf + slice * d + (pair - slice * C) * L;
     uint32_t* out_idx = idx + pair * K;
     float* out_val = val + pair * K;
-    const uint32_t count = min(tile_split[tile_id], static_cast<uint32_t>(slots_per_tile));
-    uint32_t done = tile_offsets[tile_id];                     // list position of this tile's next kept element
-    for (uint32_t e0 = 0; e0 < count; e0 += kWaveSize) {       // same trip count in every lane
-        const uint32_t e = e0 + lane;
-        uint2 entry = make_uint2(0u, 0u);
-        if (e < count) entry = slots[tile_id * slots_per_tile + e];
-        const uint32_t j = tile * kTopkTile + entry.x;         // chunk-local index
-        const bool keep = e < count && j < L && kept(entry.y & 0x7FFFFFFFu, j, T, idxT);
-        const uint64_t votes = __ballot(keep);
-        if (keep) {
-            const uint32_t rank = done + static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes & ((uint64_t{1} << lane) - 1))));
-            if (rank < K) {                                    // holds by construction; guards the list bounds
-                out_idx[rank] = j;
-                const uint32_t bits = entry.y;
-                out_val[rank] = __builtin_bit_cast(float, bits);
-            }
-            if (zero_kept) chunk_buf[j] = 0.0f;
-        }
-        done += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes)));
+    if (threadIdx.x < kEmitTilesPerBlock) {                    // list position of each tile's first kept element
+        const int32_t tile = t0 + static_cast<int32_t>(threadIdx.x);
+        lds_offset[threadIdx.x] = tile < tiles_per_chunk ? tile_offsets[pair * tiles_per_chunk + tile] : 0u;
+    }
+    load_slot_counts(tile_split, slots_per_tile, pair, t0, tiles_per_chunk, kEmitTilesPerBlock, lds_count);
+    const int block_tiles = min(kEmitTilesPerBlock, tiles_per_chunk - t0);
+    for (int first = wave * kSlotUnroll; first < block_tiles; first += kWaves * kSlotUnroll) {
+        uint32_t done[kSlotUnroll];
+#pragma unroll
+        for (int u = 0; u < kSlotUnroll; ++u) done[u] = lds_offset[first + u];
+        for_slots_of_tiles(slots, slots_per_tile, pair * tiles_per_chunk + t0, lds_count, first,
+                           [&](int q, uint32_t, uint2 entry, bool valid) {
+                               const uint32_t j = static_cast<uint32_t>(t0 + q) * kTopkTile + entry.x;   // chunk-local index
+                               const bool keep = valid && j < L && kept(entry.y & 0x7FFFFFFFu, j, T, idxT);
+                               const uint64_t votes = __ballot(keep);
+                               uint32_t& next = done[q - first];
+                               if (keep) {
+                                   const uint32_t rank = next + static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes & ((uint64_t{1} << lane) - 1))));
+                                   if (rank < K) {             // holds by construction; guards the list bounds
+                                       out_idx[rank] = j;
+                                       const uint32_t bits = entry.y;
+                                       out_val[rank] = __builtin_bit_cast(float, bits);
+                                   }
+                                   if (zero_kept) chunk_buf[j] = 0.0f;
+                               }
+                               next += static_cast<uint32_t>(__popcll(static_cast<unsigned long long>(votes)));
+                           });
     }
 }
 
@@ -1003,6 +1244,9 @@ __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restri
         state[p * kTopkStateWords + kStOverflow] = 0u;
         state[p * kTopkStateWords + kStResplit] = resplit;
         state[p * kTopkStateWords + kStRehist] = 0u;
+        state[p * kTopkStateWords + kStNearCount] = 0u;
+        state[p * kTopkStateWords + kStNearOverflow] = 0u;
+        state[p * kTopkStateWords + kStTieDone] = 0u;
     }
 }
 
@@ -1020,12 +1264,15 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                            uint32_t* guess, uint2* save_keep, const TopkScratch& s, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
-    const dim3 per_pair(static_cast<uint32_t>(pairs)), per_tile(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
+    const dim3 per_pair(static_cast<uint32_t>(pairs)), block(kThreads);
     const uint32_t K32 = static_cast<uint32_t>(K);
     const dim3 tie_grid(static_cast<uint32_t>(tpc < 4096 ? tpc : 4096));   // the pair-walking kernels
     const int32_t cand_blocks = (tpc + kCandTilesPerBlock - 1) / kCandTilesPerBlock;
     const dim3 cand_grid(static_cast<uint32_t>(pairs * cand_blocks));
-    const int64_t tiles_total = pairs * tpc;
+    const int32_t tie_cand_blocks = (tpc + kTieTilesPerBlock - 1) / kTieTilesPerBlock;
+    const dim3 tie_cand_grid(static_cast<uint32_t>(pairs * tie_cand_blocks));
+    const int32_t emit_blocks = (tpc + kEmitTilesPerBlock - 1) / kEmitTilesPerBlock;
+    const dim3 emit_grid(static_cast<uint32_t>(pairs * emit_blocks));
     for (int level = 0; level < 3; ++level) {
         if (level == 1) {
             hipLaunchKernelGGL(topk_split_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_split, s.slots,
@@ -1033,8 +1280,12 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
             APMS_RETURN_IF_ERROR();
         }
         if (level > 0) {
-            hipLaunchKernelGGL(topk_cand_hist_kernel<false>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
-                               s.tile_split, s.hist, s.state, tpc, cand_blocks, level);
+            if (level == 1)
+                hipLaunchKernelGGL(topk_cand_hist_kernel<false>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
+                                   s.tile_split, s.hist, s.state, tpc, cand_blocks, level);
+            else
+                hipLaunchKernelGGL(topk_near_kernel, cand_grid, block, 0, stream, s.slots, s.slots_per_tile, s.tile_split,
+                                   s.hist, s.state, s.tile_counts, s.near, tpc, cand_blocks);
             APMS_RETURN_IF_ERROR();
             hipLaunchKernelGGL(topk_key_hist_walk_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d,
                                geo.L, geo.C, pairs, tpc, level);
@@ -1053,9 +1304,11 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
             APMS_RETURN_IF_ERROR();
         }
     }
-    for (int level = 0; level < 3; ++level) {                  // tie selection: returns at once where not needed
-        hipLaunchKernelGGL(topk_cand_hist_kernel<true>, cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
-                           s.tile_split, s.hist, s.state, tpc, cand_blocks, level);
+    hipLaunchKernelGGL(topk_resolve_kernel, per_pair, block, 0, stream, s.state, s.near, s.tile_counts, tpc);
+    APMS_RETURN_IF_ERROR();
+    for (int level = 0; level < 3; ++level) {                  // tie selection from the slots or the buffer: rare
+        hipLaunchKernelGGL(topk_cand_hist_kernel<true>, tie_cand_grid, block, 0, stream, s.slots, s.slots_per_tile,
+                           s.tile_split, s.hist, s.state, tpc, tie_cand_blocks, level);
         APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_tie_hist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L,
                            geo.C, pairs, tpc, level);
@@ -1064,17 +1317,16 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                            static_cast<uint32_t*>(nullptr), false);
         APMS_RETURN_IF_ERROR();
     }
-    const dim3 per_wave_tile(static_cast<uint32_t>((tiles_total + kWaves - 1) / kWaves));
-    hipLaunchKernelGGL(topk_slot_count_kernel, per_wave_tile, block, 0, stream, s.slots, s.slots_per_tile, s.tile_split,
-                       s.state, s.tile_counts, tpc, tiles_total);
+    hipLaunchKernelGGL(topk_slot_count_kernel, emit_grid, block, 0, stream, s.slots, s.slots_per_tile, s.tile_split,
+                       s.state, s.tile_counts, tpc, emit_blocks);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_count_walk_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_counts, geo.d, geo.L,
                        geo.C, pairs, tpc);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_scan_kernel, per_pair, block, 0, stream, s.tile_counts, tpc);
     APMS_RETURN_IF_ERROR();
-    hipLaunchKernelGGL(topk_slot_emit_kernel, per_wave_tile, block, 0, stream, buf, s.slots, s.slots_per_tile,
-                       s.tile_split, s.state, s.tile_counts, idx, val, geo.d, geo.L, geo.C, tpc, tiles_total, K,
+    hipLaunchKernelGGL(topk_slot_emit_kernel, emit_grid, block, 0, stream, buf, s.slots, s.slots_per_tile,
+                       s.tile_split, s.state, s.tile_counts, idx, val, geo.d, geo.L, geo.C, tpc, emit_blocks, K,
                        save_keep == nullptr);
     APMS_RETURN_IF_ERROR();
     hipLaunchKernelGGL(topk_emit_walk_kernel, tie_grid, block, 0, stream, buf, s.state, s.tile_counts, idx, val, geo.d,
@@ -1115,9 +1367,9 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, 
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     hipError_t e = begin_call(pairs, /*resplit=*/false, scratch, stream);
     if (e != hipSuccess) return e;
-    // unused dynamic LDS that caps the pass at 3 workgroups per CU (with its 8 KB histogram): measured 3 %
-    // faster than uncapped, 2 workgroups per CU are slower again
-    constexpr uint32_t kWorkerPassPad = 44 * 1024;
+    // unused dynamic LDS that caps the pass at 3 workgroups per CU: measured 3 % faster than uncapped, 2
+    // workgroups per CU are slower again
+    constexpr uint32_t kWorkerPassPad = 50 * 1024;
     hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), kWorkerPassPad, stream, m, g,
                        werr, scratch.hist, scratch.state, scratch.guess, scratch.tile_split, scratch.slots,
                        scratch.slots_per_tile, werr_pending ? scratch.keep : static_cast<const uint2*>(nullptr), geo.d,
@@ -1137,11 +1389,16 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
     if (e != hipSuccess) return e;
     uint32_t* server_guess = scratch.guess + static_cast<int64_t>(geo.n) * geo.C;   // after the workers' entries
     uint2* server_keep = scratch.keep + static_cast<int64_t>(geo.n) * geo.C;
+    // workers per batch of the decode: as many as fill three quarters of the LDS stage with the share of a
+    // list that falls into one tile, so that an uneven tile still fits
+    const int64_t per_tile = (K * kTopkTile + geo.L - 1) / geo.L;
+    const int64_t fit = (kServerStage * 3 / 4) / (per_tile > 0 ? per_tile : 1);
+    const int32_t workers_per_batch = static_cast<int32_t>(fit < 1 ? 1 : (fit > kServerBatchMax ? kServerBatchMax : fit));
     hipLaunchKernelGGL(topk_server_u_kernel, dim3(static_cast<uint32_t>(static_cast<int64_t>(geo.C) * tpc)),
                        dim3(kThreads), 0, stream, idx, val, serr, scratch.hist, scratch.state, server_guess,
                        scratch.tile_counts, scratch.tile_split, scratch.slots, scratch.slots_per_tile,
                        serr_pending ? server_keep : static_cast<const uint2*>(nullptr), geo.d, geo.L, geo.C, geo.n,
-                       static_cast<int32_t>(K), tpc, inv_n);
+                       static_cast<int32_t>(K), tpc, workers_per_batch, inv_n);
     APMS_RETURN_IF_ERROR();
     return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, defer ? server_keep : nullptr, scratch, stream);
 }

@@ -268,6 +268,37 @@ def test_topk_few_ties_at_the_threshold():
     run.close()
 
 
+@pytest.mark.parametrize("deferred", MODES, ids=MODE_IDS)
+def test_topk_many_ties_at_the_threshold_without_full_tiles(deferred):
+    """The K-th largest magnitude of every (worker, chunk) pair occurs about 1500 times, spread thinly over 48
+    tiles: more elements share the threshold's leading key bits than the selection's short list of such
+    elements holds, while no tile comes near filling its slots, so the tie rule and the per-tile counts are
+    worked out from the slots.  Three steps: the later ones select on the previous step's threshold bin."""
+    n, L, C, K = 2, 4096 * 48, 2, 2000
+    d = L * C
+    rng = np.random.default_rng(23)
+    z = np.zeros
+    werr = rng.normal(0, 3e-3, (n, d)).astype(F)
+    for i in range(n):
+        for k in range(C):
+            chunk = werr[i, k * L:(k + 1) * L]
+            order = np.argsort(-np.abs(chunk), kind="stable")
+            t = np.abs(chunk[order[K - 1]])
+            small = order[K + 50:]
+            picks = rng.choice(small, 1500, replace=False)
+            chunk[picks] = t * np.where(rng.integers(0, 2, 1500) == 0, 1.0, -1.0).astype(F)
+    st = dict(x=rng.normal(0, 0.02, d).astype(F), m=z((n, d), F), v=np.ones(d, F), werr=werr, serr=z(d, F))
+    run, ost = make(d, n, L, st, deferred)
+    for step in range(3):
+        say("many ties mode %d step %d" % (deferred, step))
+        g = z((n, d), F) if step == 0 else rng.normal(0, 1e-4, (n, d)).astype(F)   # step 0: u = werr exactly
+        run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
+        ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
+        compare(run, ost, "many ties step %d" % step, errors=not deferred)
+        settle(run, ost, "many ties step %d" % step, deferred, now=step == 2)
+    run.close()
+
+
 def test_topk_all_zero_and_signed_zero():
     """Everything zero (+0 and -0 mixed): the first K indices of each chunk are kept, values are zeros."""
     n, L, C, K = 2, 4096 + 32, 2, 9
