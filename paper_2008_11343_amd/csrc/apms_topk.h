@@ -7,11 +7,11 @@
 // element index finds the last tie to keep.  Kept elements are then emitted in index order.
 //
 // Passes over the dense buffer: the one that forms u (worker) or ubar (server).  It works on a guess of the
-// threshold's level-0 bin (the previous call's, less one): every element at or above the guessed bin is
-// counted in the level-0 histogram and copied to the tile's slots (under 3 % of a tile when K is 1 % of a
+// threshold (the previous call's, less a margin of 3 to 6 %): every element at or above that floor is
+// counted in the level-0 histogram and copied to the tile's slots (about 1.5 % of a tile when K is 1 % of a
 // chunk); the rest is neither counted nor copied.  Where the guess proves too high (always in a context's
 // first call) one more pass builds the whole histogram and another re-fills the slots from the bin then
-// known.  Key levels 1 and 2, the tie levels, the per-tile counts and the emission work on the slots alone.
+// known.  Key levels 1 and 2, the tie rule, the per-tile counts and the emission work on the slots alone.
 // A chunk with a tile that has more such elements than slots (constant or heavily tied data, or a K far
 // beyond what the slots were sized for) takes full passes over the buffer instead: slower, same result.
 #pragma once
@@ -47,8 +47,8 @@ inline int32_t topk_slots_for(int64_t K, int64_t L) {
 //                                        gather kernels first use it for the tile offsets of their input lists
 //   tile_split  [pairs][tiles] u32       elements of the tile at or above the level-0 bin of the threshold
 //   slots       [pairs][tiles][slots_per_tile] uint2   those elements: (tile-local index, value bits)
-//   guess       [pairs + C] u32          the first pass's guess of that bin (less one) from the previous call: the
-//                                        worker call's n * C entries, then the server call's C;
+//   guess       [pairs + C] u32          the floor of the first pass (the previous call's threshold key less a
+//                                        margin): the worker call's n * C entries, then the server call's C;
 //                                        0xFFFFFFFF in a new context and whenever the slots are re-allocated
 //   near        [pairs][kTopkNearCap] uint2   the slot entries that share the top 22 key bits of the pair's threshold:
 //                                        (chunk-local index, key), in no particular order

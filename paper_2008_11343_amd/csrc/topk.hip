@@ -10,9 +10,9 @@
 // per-tile counts and a scan, so the result does not depend on scheduling.
 //
 // Only the level-0 histogram needs every element, and only if nothing is known: the first pass histograms
-// the elements at or above a guessed bin (the previous call's threshold bin, less one) and leaves the rest
-// uncounted, so that the few populated exponent bins of ordinary data do not serialise on LDS atomics; if the
-// bins it did count hold fewer than K elements the threshold lies below the guess, and one more pass over the
+// the elements whose key is at or above a guessed floor (the previous call's threshold key less a margin) and
+// leaves the rest uncounted, so that the few populated exponent bins of ordinary data do not serialise on LDS
+// atomics; if it counted fewer than K elements the threshold lies below the floor, and one more pass over the
 // buffer builds the whole level-0 histogram for that chunk.  What the later steps need are the elements at or above
 // the level-0 bin of T (kept whatever T turns out to be if above, candidates if inside: under 2 % of a tile
 // when K is 1 % of a chunk).  They are copied to per-tile slots - by the worker's first pass itself, on the
@@ -47,7 +47,10 @@ enum : int {
     kStTieDone = 13,      // 1 if kStIdxT and the per-tile counts were settled from the near list
 };
 
-constexpr uint32_t kNoGuess = 0xFFFFFFFFu;      // guess[pair]: no earlier call to go by
+// The floor of the next call's first pass (guess[pair]) lies this far below the threshold key found: half a
+// level-0 bin, 3 to 6 % in magnitude.  With K at 1 % of a chunk of normal data about 1.5 % of the elements
+// pass it.  With no earlier call to go by the table holds 0xFFFFFFFF, a floor that no key reaches.
+constexpr uint32_t kGuessMargin = 1u << 19;
 
 constexpr uint32_t kTopMask = 0x7FF00000u;      // the level-0 digit of a key
 
@@ -168,14 +171,15 @@ __device__ __forceinline__ void flush_histogram(const uint32_t* lds_hist, uint32
     }
 }
 
-// The first pass counts only the bins at or above its guess, and ordinary data reaches a few dozen bins above
-// the threshold's (8 bins per binade): a workgroup keeps a window of kHistWindow bins starting at the guessed
-// one in LDS and sends the rare element beyond it to the pair's histogram directly.
+// The first pass counts only the elements at or above its floor, and ordinary data reaches a few dozen bins
+// above the threshold's (8 bins per binade): a workgroup keeps a window of kHistWindow bins starting at the
+// floor's bin in LDS and sends the rare element beyond it to the pair's histogram directly.  (The floor's own
+// bin is counted in part: enough, because the selection only ever looks for elements above the floor.)
 constexpr int kHistWindow = 256;
 static_assert(kHistWindow == kThreads, "one window bin per thread");
 __device__ __forceinline__ void count_in_window(uint32_t* lds_window, uint32_t* __restrict__ hist, uint32_t guessed,
                                                 uint32_t bin) {
-    const uint32_t rel = bin - guessed;                        // callers pass bins at or above the guessed one only
+    const uint32_t rel = bin - guessed;                        // callers pass bins at or above the floor's only
     if (rel < static_cast<uint32_t>(kHistWindow)) atomicAdd(&lds_window[rel], 1u); else atomicAdd(&hist[bin], 1u);
 }
 __device__ __forceinline__ void flush_window(const uint32_t* lds_window, uint32_t* __restrict__ hist, uint32_t guessed) {
@@ -217,13 +221,13 @@ __device__ __forceinline__ uint32_t write_tile_slots(const f32x4 (&v)[kTileRows]
 // ------------------------------------------------------------------------
 // Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
 // ------------------------------------------------------------------------
-// The threshold hardly moves from one step to the next, so the pass works on a guess: the level-0 bin of the
-// previous call's threshold, less one (guess[pair]; kNoGuess before the first call).  Elements at or above
-// the guessed bin are histogrammed and copied to the slots, the others are left alone.  The guess is good if
-// it is not above the bin the selection then finds - histogram and slots hold a superset of what is needed,
-// and the extra entries fail every later test; if it is (the counted bins hold fewer than K elements), the
-// pair is marked kStRehist and takes a full histogram pass; where the guess was too high, or a tile
-// overflowed on it, the pair is marked kStResplit and topk_split_kernel fills its slots again.
+// The threshold hardly moves from one step to the next, so the pass works on a guess: a floor kGuessMargin
+// below the previous call's threshold key (guess[pair]; 0xFFFFFFFF before the first call).  Elements at or above
+// the floor are histogrammed and copied to the slots, the others are left alone.  The guess is good if at
+// least K elements passed it: the K-th largest key is then among them, histogram and slots hold a superset
+// of what the selection looks at, and the extra entries fail every later test.  If fewer passed, the pair is
+// marked kStRehist and takes a full histogram pass; there, and where a tile overflowed its slots, the pair
+// is marked kStResplit and topk_split_kernel fills its slots again.
 // One tile per workgroup: taking several tiles in a loop (one histogram flush for all of them, or with the
 // next tile's loads requested ahead) was measured 3 to 10 % slower, like the 1-bit worker kernel this pass
 // streams best as many short-lived workgroups.
@@ -245,8 +249,8 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
     uint32_t* pair_hist = hist + tr.pair * kTopkBins;
     const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
     const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);   // error buffer in deferred form?
-    const uint32_t guessed = guess[tr.pair];
-    const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
+    const uint32_t floor_key = guess[tr.pair];                // 0xFFFFFFFF: no earlier call, nothing passes
+    const uint32_t guessed = floor_key >> 20;                 // first bin of the histogram window
     f32x4 u[kTileRows];
     uint32_t take_mask = 0;
     uint64_t packed = 0;
@@ -266,7 +270,7 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
             const float stored = ve[c];
             u[r][c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const uint32_t key = key_of(u[r][c]);
-            if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
+            if (key >= floor_key) {                            // at or above the floor: counted and slotted
                 count_in_window(lds_window, pair_hist, guessed, key >> 20);
                 take_mask |= 1u << (4 * r + c);
                 ++count;
@@ -311,7 +315,7 @@ __global__ __launch_bounds__(kThreads) void topk_tile_offsets_kernel(const uint3
     offsets[t] = static_cast<uint32_t>(lower_bound_u32(idx + list * K, K, static_cast<uint32_t>(tile * tile_elems)));
 }
 
-// Like the worker's first pass, it counts and slots only the elements at or above a guessed level-0 bin
+// Like the worker's first pass, it counts and slots only the elements at or above a guessed floor
 // (guess[chunk], the server's own table).
 //
 // The decoded messages have to be added position by position in worker order, and walking the workers one
@@ -349,8 +353,8 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // slices = 1: pair = chunk
     uint32_t* pair_hist = hist + tr.pair * kTopkBins;
     const int64_t tile_lo = tr.tile * kTopkTile;
-    const uint32_t guessed = guess[tr.pair];
-    const uint32_t floor_bits = guessed == kNoGuess ? 0xFFFFFFFFu : guessed << 20;   // no key reaches 0xFFFFFFFF
+    const uint32_t floor_key = guess[tr.pair];                // 0xFFFFFFFF: no earlier call, nothing passes
+    const uint32_t guessed = floor_key >> 20;                 // first bin of the histogram window
     const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);
     // the tile of the server error, requested now: it arrives while the messages are being decoded
     f32x4 ve[kTileRows];
@@ -454,7 +458,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
             ubar[r][c] = mean + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const float value = ubar[r][c];
             const uint32_t key = key_of(value);
-            if ((key & kTopMask) >= floor_bits) {              // at or above the guessed bin: counted and slotted
+            if (key >= floor_key) {                            // at or above the floor: counted and slotted
                 count_in_window(lds_window, pair_hist, guessed, key >> 20);
                 take_mask |= 1u << (4 * r + c);
                 ++count;
@@ -480,9 +484,9 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
 // One workgroup per pair.  Scans the level's histogram (from the top bin down for keys, from bin 0 up for
 // indices) to the bin where the running count reaches `remaining`, records it in the state and clears the
 // histogram for the next level.
-// At key level 0 with a guess table: checks the guess the slots were filled on against the bin found (see
-// topk_worker_u_kernel) and leaves the next call's guess.
-// only_rehist: the second level-0 pick of a call, for the pairs whose first histogram fell short (kStRehist).
+// only_rehist: the second level-0 pick of a call, for the pairs whose first histogram fell short (kStRehist:
+// the floor they were counted and slotted on was too high, so their slots are filled again).
+// At key level 2 with a guess table: leaves the floor of the next call's first pass (see topk_worker_u_kernel).
 template <bool kIdx>
 __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
                                                              int level, uint32_t K, uint32_t* __restrict__ guess,
@@ -520,7 +524,7 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
         if (pos < nb) h[kIdx ? pos : nb - 1 - pos] = 0u;
     }
     if (!kIdx && level == 0 && !only_rehist && total < remaining) {
-        // the bins the first pass counted (those at or above its guess) do not reach down to the K-th largest
+        // the elements the first pass counted (those at or above its floor) do not reach down to the K-th largest
         // key: the whole level-0 histogram is needed (topk_key_hist_walk_kernel, then this kernel again)
         if (threadIdx.x == 0) st[kStRehist] = 1u;
         return;
@@ -541,11 +545,9 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
                 } else {
                     st[kStPrefix] = new_prefix;
                     st[kStRemaining] = left;
-                    if (level == 0 && guess) {
-                        if (guess[pair] == kNoGuess || guess[pair] > bin) st[kStResplit] = 1u;
-                        guess[pair] = bin > 0u ? bin - 1u : 0u;
-                    }
+                    if (level == 0 && only_rehist) st[kStResplit] = 1u;
                     if (level == 2) {
+                        if (guess) guess[pair] = new_prefix > kGuessMargin ? new_prefix - kGuessMargin : 0u;
                         st[kStKeyT] = new_prefix;
                         st[kStCountEq] = cnt[q];
                         st[kStTieNeeded] = (left < cnt[q]) ? 1u : 0u;
@@ -1292,15 +1294,15 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
             APMS_RETURN_IF_ERROR();
         }
         hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                           level == 0 ? guess : static_cast<uint32_t*>(nullptr), false);
+                           level == 2 ? guess : static_cast<uint32_t*>(nullptr), false);
         APMS_RETURN_IF_ERROR();
         if (level == 0) {
             // pairs whose first pass did not count down to the threshold bin: full histogram, pick again
             hipLaunchKernelGGL(topk_rehist_kernel, tie_grid, block, 0, stream, buf, s.hist, s.state, geo.d, geo.L, geo.C,
                                pairs, tpc);
             APMS_RETURN_IF_ERROR();
-            hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32, guess,
-                               true);
+            hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
+                               static_cast<uint32_t*>(nullptr), true);
             APMS_RETURN_IF_ERROR();
         }
     }
