@@ -472,11 +472,14 @@ def main():
         "compress": {"bound": "hbm", "frac": d * ab["compress"] / (compress_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
         "server_reduce": {"bound": server_bound,
                           "frac": (server_alu_s if server_bound == "alu" else server_hbm_s) / (mean(t_s) * 1e-3),
-                          "hbm_floor_ms": server_hbm_s * 1e3, "valu_floor_ms": server_alu_s * 1e3,
-                          "valu_model": "%d fp32 VALU ops per decoded worker element x n x d over %d CUs x %d lanes x %.1f GHz" % (
-                              SERVER_VALU_OPS_PER_WORKER_ELEM, CU_COUNT, LANES_PER_CU, CLOCK_GHZ)},
+                          "hbm_floor_ms": server_hbm_s * 1e3},
         "apply": {"bound": "hbm", "frac": d * ab["apply"] / (mean(t_a) * 1e-3) / 1e9 / HBM_PEAK_GBS},
     }
+    if args.algo != "topk":                                   # the 1-bit server kernel's instruction count per element
+        calls["server_reduce"].update(
+            valu_floor_ms=server_alu_s * 1e3,
+            valu_model="%d fp32 VALU ops per decoded worker element x n x d over %d CUs x %d lanes x %.1f GHz" % (
+                SERVER_VALU_OPS_PER_WORKER_ELEM, CU_COUNT, LANES_PER_CU, CLOCK_GHZ))
 
     out = {
         "metric": METRIC, "value": value, "unit": "params/s", "n_gpus": 1, "steps": args.steps,

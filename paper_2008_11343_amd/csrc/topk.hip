@@ -218,6 +218,43 @@ __device__ __forceinline__ uint32_t write_tile_slots(const f32x4 (&v)[kTileRows]
     return row_base;
 }
 
+// The same for a tile whose values also lie in LDS (tile_values[tile-local index]), and with the histogram
+// window: every marked element is counted in the window and copied to the tile's slots.  A thread walks the
+// set bits of its mask (a tile has a few dozen marked elements among 4096, so most threads have none)
+// instead of testing all sixteen of its elements.  Contains workgroup barriers and ends with one: the
+// window is complete.  Returns how many elements were marked in the whole tile.
+__device__ __forceinline__ uint32_t count_and_slot_marked(const float* tile_values /* LDS */, uint32_t take_mask,
+                                                          uint64_t* lds_scan /* kWaves */, uint32_t* lds_window,
+                                                          uint32_t* __restrict__ pair_hist, uint32_t guessed,
+                                                          uint2* __restrict__ my_slots, int32_t slots_per_tile) {
+    static_assert(kTileRows == 4 && kThreads * 4 < 65536, "four 16-bit row counters");
+    uint64_t packed = 0;
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r)
+        packed |= static_cast<uint64_t>(__popc((take_mask >> (4 * r)) & 0xFu)) << (16 * r);
+    uint64_t totals;
+    const uint64_t before = block_exclusive_scan_u64(packed, lds_scan, totals);
+    // field r: the rank of this thread's first marked element of row r = marked elements of the rows before
+    // (the fields stay below 2^16, so the shifted sums do not carry into each other) + those of row r in the
+    // threads before
+    const uint64_t rank0 = (totals << 16) + (totals << 32) + (totals << 48) + before;
+    uint32_t todo = take_mask;
+    while (todo) {
+        const int b = __ffs(static_cast<int>(todo)) - 1;
+        todo &= todo - 1u;
+        const int r = b >> 2;
+        const uint32_t local = static_cast<uint32_t>(threadIdx.x * 4 + r * kRowStride + (b & 3));
+        const float value = tile_values[local];
+        const uint32_t bits = __builtin_bit_cast(uint32_t, value);
+        count_in_window(lds_window, pair_hist, guessed, (bits & 0x7FFFFFFFu) >> 20);
+        const uint32_t rank = static_cast<uint32_t>((rank0 >> (16 * r)) & 0xFFFFu) +
+                              static_cast<uint32_t>(__popc(take_mask & ((1u << b) - 1u) & (0xFu << (4 * r))));
+        if (rank < static_cast<uint32_t>(slots_per_tile)) my_slots[rank] = make_uint2(local, bits);
+    }
+    __syncthreads();
+    return static_cast<uint32_t>((totals & 0xFFFFu) + ((totals >> 16) & 0xFFFFu) + ((totals >> 32) & 0xFFFFu) + (totals >> 48));
+}
+
 // ------------------------------------------------------------------------
 // Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
 // ------------------------------------------------------------------------
@@ -243,45 +280,38 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
                                                                  int32_t tiles_per_chunk, float beta, float omb) {
     __shared__ uint32_t lds_window[kHistWindow];
     __shared__ uint64_t lds_scan[kWaves];
+    __shared__ __align__(16) float tile_u[kTopkTile];          // the tile's u, for the marked elements' second look
     lds_window[threadIdx.x] = 0u;
-    __syncthreads();
     const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);
     uint32_t* pair_hist = hist + tr.pair * kTopkBins;
     const int64_t off0 = tr.tile * kTopkTile + threadIdx.x * 4;
     const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);   // error buffer in deferred form?
     const uint32_t floor_key = guess[tr.pair];                // 0xFFFFFFFF: no earlier call, nothing passes
     const uint32_t guessed = floor_key >> 20;                 // first bin of the histogram window
-    f32x4 u[kTileRows];
     uint32_t take_mask = 0;
-    uint64_t packed = 0;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int64_t off = off0 + r * kRowStride;
-        u[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (off >= L) continue;
         const int64_t p = tr.base + off;
         const f32x4 vm = load_stream(m + p), vg = load_stream(g + p), ve = load_stream(e + p);
-        uint32_t count = 0;
+        f32x4 u;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
             const float bm = beta * vm[c];
             const float bg = omb * vg[c];
             const float mi = bm + bg;
             const float stored = ve[c];
-            u[r][c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
-            const uint32_t key = key_of(u[r][c]);
-            if (key >= floor_key) {                            // at or above the floor: counted and slotted
-                count_in_window(lds_window, pair_hist, guessed, key >> 20);
-                take_mask |= 1u << (4 * r + c);
-                ++count;
-            }
+            u[c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
+            const float value = u[c];
+            take_mask |= key_of(value) >= floor_key ? 1u << (4 * r + c) : 0u;   // at or above the floor: counted and slotted
         }
-        packed |= static_cast<uint64_t>(count) << (16 * r);
-        store_stream(e + p, u[r]);
+        *reinterpret_cast<f32x4*>(&tile_u[threadIdx.x * 4 + r * kRowStride]) = u;
+        store_stream(e + p, u);
     }
     const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
-    const uint32_t marked = write_tile_slots(u, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
-                                             slots_per_tile);        // its barriers also cover lds_window
+    const uint32_t marked = count_and_slot_marked(tile_u, take_mask, lds_scan, lds_window, pair_hist, guessed,
+                                                  slots + tile_id * slots_per_tile, slots_per_tile);   // its barriers also cover lds_window
     if (threadIdx.x == 0) {
         tile_split[tile_id] = marked;
         if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
@@ -293,26 +323,40 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
 // Server: decode + average the n sparse messages of a tile in LDS, add the server error, write ubar into
 // the error buffer + level-0 key histogram (Algorithm 1 line 9).
 // ------------------------------------------------------------------------
-__device__ __forceinline__ int lower_bound_u32(const uint32_t* __restrict__ a, int count, uint32_t x) {
-    int lo = 0, hi = count;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (a[mid] < x) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
 // offsets[list][tile] = how many entries of the sorted index list `list` lie below the tile's first element:
-// where the tile's stretch of the list starts (it ends where the next tile's starts, or at K).
+// where the tile's stretch of the list starts (it ends where the next tile's starts, or at K).  One thread per
+// list entry (four per thread): the entry that is the first of its list at or beyond a tile's start writes that tile's offset
+// (and those of the empty tiles before it), the last entry those of the tiles after it.  Tiles are
+// 1 << tile_shift elements.  Indices at or beyond the chunk's end count as lying in its last tile, so every
+// store stays inside the table whatever the lists hold.
+constexpr int kOffsetsPerThread = 4;
 __global__ __launch_bounds__(kThreads) void topk_tile_offsets_kernel(const uint32_t* __restrict__ idx,
-                                                                     uint32_t* __restrict__ offsets, int64_t lists,
-                                                                     int32_t tiles_per_chunk, int32_t tile_elems,
-                                                                     int32_t K) {
-    const int64_t t = static_cast<int64_t>(blockIdx.x) * kThreads + threadIdx.x;
-    if (t >= lists * tiles_per_chunk) return;
-    const int64_t list = t / tiles_per_chunk;
-    const int64_t tile = t - list * tiles_per_chunk;
-    offsets[t] = static_cast<uint32_t>(lower_bound_u32(idx + list * K, K, static_cast<uint32_t>(tile * tile_elems)));
+                                                                     uint32_t* __restrict__ offsets,
+                                                                     int32_t tiles_per_chunk, int tile_shift,
+                                                                     int32_t K, int32_t blocks_per_list) {
+    const int64_t list = blockIdx.x / blocks_per_list;
+    const int32_t e0 = static_cast<int32_t>(blockIdx.x - list * blocks_per_list) * (kThreads * kOffsetsPerThread) +
+                       static_cast<int32_t>(threadIdx.x);
+    const uint32_t* mine = idx + list * K;
+    uint32_t* row = offsets + list * tiles_per_chunk;
+    const uint32_t last_tile = static_cast<uint32_t>(tiles_per_chunk - 1);
+    uint32_t at[kOffsetsPerThread], before[kOffsetsPerThread];
+#pragma unroll
+    for (int k = 0; k < kOffsetsPerThread; ++k) {              // all loads first
+        const int32_t e = e0 + k * kThreads;
+        at[k] = e < K ? mine[e] : 0u;
+        before[k] = (e > 0 && e < K) ? mine[e - 1] : 0u;
+    }
+#pragma unroll
+    for (int k = 0; k < kOffsetsPerThread; ++k) {
+        const int32_t e = e0 + k * kThreads;
+        if (e >= K) continue;
+        const int32_t to = static_cast<int32_t>(min(at[k] >> tile_shift, last_tile));
+        const int32_t from = e == 0 ? 0 : static_cast<int32_t>(min(before[k] >> tile_shift, last_tile)) + 1;
+        for (int32_t tile = from; tile <= to; ++tile) row[tile] = static_cast<uint32_t>(e);
+        if (e == K - 1)
+            for (int32_t tile = to + 1; tile <= static_cast<int32_t>(last_tile); ++tile) row[tile] = static_cast<uint32_t>(K);
+    }
 }
 
 // Like the worker's first pass, it counts and slots only the elements at or above a guessed floor
@@ -343,7 +387,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
                                                                  int32_t workers_per_batch, float inv_n) {
     __shared__ uint32_t lds_window[kHistWindow];
     __shared__ uint64_t lds_scan[kWaves];
-    __shared__ float acc[kTopkTile];
+    __shared__ __align__(16) float acc[kTopkTile];
     __shared__ uint2 stage[kServerStage];                      // (tile-local position, value bits), worker-major
     __shared__ uint32_t stage_first[kServerBatchMax];          // per worker of the batch: first list entry of the tile
     __shared__ uint32_t stage_start[kServerBatchMax + 1];      // ... and where its entries start in the stage
@@ -384,7 +428,7 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
                 const uint32_t* off = offsets + which * tiles_per_chunk + tr.tile;
                 first = off[0];
                 const uint32_t last = (tr.tile + 1 < tiles_per_chunk) ? off[1] : static_cast<uint32_t>(K);
-                count = last - first;
+                count = (first < last && last <= static_cast<uint32_t>(K)) ? last - first : 0u;   // always, for sorted lists
             }
             uint32_t total;
             const uint32_t start = block_exclusive_scan_u32(count, stage_scan, total);
@@ -440,36 +484,29 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
             __syncthreads();                                   // before the next batch reuses the stage tables
         }
     }
-    f32x4 ubar[kTileRows];
+    // ubar = mean + server error, into the error buffer and back into the LDS tile; marked if at or above the floor
     uint32_t take_mask = 0;
-    uint64_t packed = 0;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int local = threadIdx.x * 4 + r * kRowStride;
         const int64_t off = tile_lo + local;
-        ubar[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
         if (off >= L) continue;
-        const int64_t p = tr.base + off;
-        uint32_t count = 0;
+        const f32x4 sums = *reinterpret_cast<const f32x4*>(&acc[local]);
+        f32x4 ubar;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const float mean = acc[local + c] * inv_n;
+            const float mean = sums[c] * inv_n;
             const float stored = ve[r][c];
-            ubar[r][c] = mean + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
-            const float value = ubar[r][c];
-            const uint32_t key = key_of(value);
-            if (key >= floor_key) {                            // at or above the floor: counted and slotted
-                count_in_window(lds_window, pair_hist, guessed, key >> 20);
-                take_mask |= 1u << (4 * r + c);
-                ++count;
-            }
+            ubar[c] = mean + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
+            const float value = ubar[c];
+            take_mask |= key_of(value) >= floor_key ? 1u << (4 * r + c) : 0u;
         }
-        packed |= static_cast<uint64_t>(count) << (16 * r);
-        store_stream(serr + p, ubar[r]);
+        *reinterpret_cast<f32x4*>(&acc[local]) = ubar;
+        store_stream(serr + tr.base + off, ubar);
     }
     const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
-    const uint32_t marked = write_tile_slots(ubar, take_mask, packed, lds_scan, slots + tile_id * slots_per_tile,
-                                             slots_per_tile);        // its barriers also cover lds_window
+    const uint32_t marked = count_and_slot_marked(acc, take_mask, lds_scan, lds_window, pair_hist, guessed,
+                                                  slots + tile_id * slots_per_tile, slots_per_tile);
     if (threadIdx.x == 0) {
         tile_split[tile_id] = marked;
         if (marked > static_cast<uint32_t>(slots_per_tile)) state[tr.pair * kTopkStateWords + kStResplit] = 1u;
@@ -1177,8 +1214,8 @@ __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __
     for (int j = threadIdx.x; j < kTile; j += kThreads) dense[j] = 0.0f;
     const int64_t list = chunk * K;
     const uint32_t* off = offsets + chunk * tiles_per_chunk + tr.tile;
-    const int first = static_cast<int>(off[0]);
-    const int last = (tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : K;
+    const int last = min((tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : K, K);   // min, first >= 0: no-ops
+    const int first = max(static_cast<int>(off[0]), 0);                                       // for sorted lists
     __syncthreads();
     for (int t = first + threadIdx.x; t < last; t += kThreads) {
         const uint32_t j = sidx[list + t] - static_cast<uint32_t>(tile_lo);
@@ -1342,12 +1379,18 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     return hipSuccess;
 }
 
-// Fills s.tile_counts[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries.
+// Fills s.tile_counts[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries;
+// tile_elems is a power of two.
 hipError_t tile_offsets(int64_t lists, int32_t tpc, int32_t tile_elems, int64_t K, const uint32_t* idx,
                         const TopkScratch& s, hipStream_t stream) {
-    const int64_t blocks = (lists * tpc + kThreads - 1) / kThreads;
+    const int64_t per_block = kThreads * kOffsetsPerThread;
+    const int64_t blocks_per_list = (K + per_block - 1) / per_block;
+    const int64_t blocks = lists * blocks_per_list;
+    if (blocks <= 0) return hipSuccess;
+    int tile_shift = 0;
+    while ((1 << tile_shift) < tile_elems) ++tile_shift;
     hipLaunchKernelGGL(topk_tile_offsets_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, idx,
-                       s.tile_counts, lists, tpc, tile_elems, static_cast<int32_t>(K));
+                       s.tile_counts, tpc, tile_shift, static_cast<int32_t>(K), static_cast<int32_t>(blocks_per_list));
     return hipGetLastError();
 }
 
@@ -1371,7 +1414,7 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, 
     if (e != hipSuccess) return e;
     // unused dynamic LDS that caps the pass at 3 workgroups per CU: measured 3 % faster than uncapped, 2
     // workgroups per CU are slower again
-    constexpr uint32_t kWorkerPassPad = 50 * 1024;
+    constexpr uint32_t kWorkerPassPad = 34 * 1024;           // beside the kernel's own 17 KB
     hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), kWorkerPassPad, stream, m, g,
                        werr, scratch.hist, scratch.state, scratch.guess, scratch.tile_split, scratch.slots,
                        scratch.slots_per_tile, werr_pending ? scratch.keep : static_cast<const uint2*>(nullptr), geo.d,
