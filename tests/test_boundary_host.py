@@ -239,6 +239,38 @@ def test_static_server_reduce_validates_before_touching_the_device():
     assert re.search(r"#define\s+APMS_STATIC_SCRATCH_BYTES\s+\(1 << 20\)", header) and B.APMS_STATIC_SCRATCH_BYTES == 1 << 20
 
 
+def function_body(source, signature_start):
+    """Text of the function whose definition starts with `signature_start`, braces matched."""
+    at = source.index(signature_start)
+    open_brace = source.index("{", source.index(")", at))
+    depth, i = 0, open_brace
+    while True:
+        depth += {"{": 1, "}": -1}.get(source[i], 0)
+        if depth == 0:
+            return source[at:i + 1]
+        i += 1
+
+
+def test_static_server_reduce_holds_no_allocating_call():
+    """The entry point for callers that cannot allocate, the helper that resolves its scratch array and the three
+    launchers it queues contain no call that allocates or frees device or pinned memory (read off the source: on
+    a GPU the device's free memory also moves with the runtime's own pools, so it is no measure of this)."""
+    csrc = os.path.join(ROOT, "paper_2008_11343_amd", "csrc")
+    api = open(os.path.join(csrc, "api.hip")).read()
+    kernels = open(os.path.join(csrc, "kernels.hip")).read()
+    bodies = [function_body(api, "int apms_server_reduce_static("), function_body(api, "hipError_t static_scratch("),
+              function_body(kernels, "hipError_t launch_server_reduce("), function_body(kernels, "hipError_t launch_scales("),
+              function_body(kernels, "hipError_t launch_finalize(")]
+    for body in bodies:
+        assert len(body) > 200
+        body = re.sub(r"//[^\n]*", "", body)                  # comments may say "new"
+        assert not re.search(r"hip\w*(Malloc|Free|Alloc|MemPool)\w*\s*\(|\bnew\b|\bmalloc\s*\(|std::vector", body), body[:80]
+    entry = bodies[0]
+    assert "static_scratch(device, &base)" in entry and "launch_server_reduce(" in entry
+    assert "HIP_SYMBOL(scratch)" in bodies[1] and re.search(
+        r"static __device__ __align__\(256\) unsigned char scratch\[APMS_STATIC_SCRATCH_BYTES\];", api)
+
+
 def test_empty_problem_is_ok_without_a_device():
     c = B.apms_create(0, 4, 64, B.APMS_DEVICE_NONE)
     try:

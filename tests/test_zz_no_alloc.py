@@ -58,12 +58,13 @@ def check_one(d, n, L, seed):
     # the allocation-free one: every tensor exists before the call; the call itself must not allocate
     serr_st = serr0.clone()
     spacked_st, sscales_st = outputs(d, L)
+    # (that the entry point's code holds no allocating call is checked on its source, in test_boundary_host.py: the
+    # device's free memory is no measure of it, the runtime's own pools move it by megabytes when memory is short)
     torch.cuda.synchronize()
-    before = torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]
+    before = torch.cuda.memory_allocated()
     B.apms_server_reduce_static(d, n, L, packed, scales, serr_st, spacked_st, sscales_st)
     torch.cuda.synchronize()
-    after = torch.cuda.memory_allocated(), torch.cuda.mem_get_info()[0]
-    assert after[0] == before[0] and after[1] >= before[1], "the call changed the device's free memory"
+    assert torch.cuda.memory_allocated() == before, "the call went through torch's allocator"
     assert torch.equal(spacked_st, spacked_ctx), "server sign words differ from apms_server_reduce"
     assert torch.equal(sscales_st, sscales_ctx), "server scales differ from apms_server_reduce"
     assert torch.equal(serr_st, serr_ctx), "server error differs from apms_server_reduce"
