@@ -192,6 +192,41 @@ def test_worker_counts(n):
     run.close()
 
 
+def sweep_cases():
+    """Twenty seeded draws of (workers, chunk length, chunks, deferral mode): chunk lengths from one sign word
+    to six tiles, mostly ragged."""
+    rng = np.random.default_rng(20080811)
+    cases = []
+    for i in range(20):
+        n = int(rng.integers(1, 10))
+        L = 32 * int(rng.integers(1, 2 if i % 7 == 0 else 700))
+        C = int(rng.integers(1, 6))
+        cases.append((i, n, L, C, MODES[int(rng.integers(0, len(MODES)))]))
+    return cases
+
+
+@pytest.mark.parametrize("case,n,L,C,deferred", sweep_cases(), ids=lambda v: str(v))
+def test_random_shape_sweep(case, n, L, C, deferred):
+    """Four steps on each drawn shape with gradients of a drawn scale (every fifth case heavy-tailed), sign words
+    compared after every step, every buffer after the closing finalize."""
+    d = L * C
+    rng = np.random.default_rng(1000 + case)
+    st, _ = random_case(500 + case, d, n, L, err_scale=float(10.0 ** rng.uniform(-5, -2)))
+    ost = oracle_state(d, n, L, st)
+    run = DeviceRun(d, n, L, DEV, deferred=deferred, state={k: torch.from_numpy(v) for k, v in st.items()})
+    sigma = float(10.0 ** rng.uniform(-4, -1))
+    for step in range(4):
+        say("sweep case %d n=%d L=%d C=%d mode=%d step %d" % (case, n, L, C, deferred, step))
+        g = (rng.standard_t(3, (n, d)) if case % 5 == 0 else rng.normal(0, 1, (n, d))).astype(F) * F(sigma)
+        run.step(torch.from_numpy(g).to(DEV), 0.9, 1e-3, 1e-8)
+        ost.step(g, 0.9, 1e-3, 1e-8)
+        same_words(host(run.packed), ost.packed, "case %d step %d packed" % (case, step))
+        same_words(host(run.spacked), ost.spacked, "case %d step %d spacked" % (case, step))
+    run.finalize()
+    compare_all(run, ost, "sweep case %d" % case)
+    run.close()
+
+
 def test_degenerate_values():
     """All-zero input (scale 0, all signs +), denormals, huge and tiny magnitudes side by side."""
     n, L, C = 2, 4096 + 64, 2

@@ -102,6 +102,45 @@ def test_topk_trajectory(n, L, C, K, deferred):
     run.close()
 
 
+def sweep_cases():
+    """Sixteen seeded draws of (workers, chunk length, chunks, K, error mode): K from one element to a fifth of
+    the chunk, chunk lengths up to twelve tiles, mostly ragged; values quantised in every fourth case, so that
+    ties at the threshold are common there."""
+    rng = np.random.default_rng(5_1_2008)
+    cases = []
+    for i in range(16):
+        n = int(rng.integers(1, 7))
+        L = 32 * int(rng.integers(1, 1500))
+        C = int(rng.integers(1, 4))
+        K = max(1, int(L * 10.0 ** rng.uniform(-3.5, -0.7)))
+        cases.append((i, n, L, C, K, MODES[i % 2]))
+    return cases
+
+
+@pytest.mark.parametrize("case,n,L,C,K,deferred", sweep_cases(), ids=lambda v: str(v))
+def test_topk_random_shape_sweep(case, n, L, C, K, deferred):
+    d = L * C
+    rng = np.random.default_rng(7000 + case)
+    st = dict(x=rng.normal(0, 0.02, d).astype(F), m=rng.normal(0, 1e-3, (n, d)).astype(F), v=np.ones(d, F),
+              werr=rng.normal(0, 3e-3, (n, d)).astype(F), serr=rng.normal(0, 1e-3, d).astype(F))
+    coarse = case % 4 == 3                                     # few distinct values everywhere: ties
+    if coarse:
+        st["m"] = (rng.integers(-1, 2, (n, d)) * 2.0 ** -6).astype(F)
+        st["werr"] = (rng.integers(-2, 3, (n, d)) * 2.0 ** -8).astype(F)
+        st["serr"] = (rng.integers(-2, 3, d) * 2.0 ** -9).astype(F)
+    run, ost = make(d, n, L, st, deferred)
+    for step in range(4):
+        say("sweep case %d n=%d L=%d C=%d K=%d mode %d step %d" % (case, n, L, C, K, deferred, step))
+        g = rng.normal(0, 1e-2, (n, d)).astype(F)
+        if coarse:
+            g = (rng.integers(-2, 3, (n, d)) * 0.25).astype(F)
+        run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
+        ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
+        compare(run, ost, "case %d step %d" % (case, step), errors=not deferred)
+        settle(run, ost, "case %d step %d" % (case, step), deferred, now=step in (1, 3))
+    run.close()
+
+
 def test_topk_changing_K_between_steps():
     """The worker pass fills its slots on the previous call's threshold bin: a K that grows (threshold falls
     below the guess: the slots are filled again), shrinks (guess low: superset) or outgrows the slots
