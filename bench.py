@@ -394,8 +394,8 @@ def main():
     if args.chunk_elems:
         import dataclasses
         wl = dataclasses.replace(wl, chunk=args.chunk_elems, name="%s-chunk%d" % (wl.name, args.chunk_elems))
-    if args.algo == "topk" and (args.mode not in ("eager", "deferred-errors") or args.grad_dtype != "f32"):
-        sys.exit("bench.py: --algo topk takes fp32 gradients and --mode eager or deferred-errors (its gather is always eager)")
+    if args.algo == "topk" and args.grad_dtype != "f32":
+        sys.exit("bench.py: --algo topk takes fp32 gradients")
     d, n, L = wl.d_pad, wl.n, wl.L
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))
@@ -422,10 +422,15 @@ def main():
         # algorithmic: worker reads m, g, delta and writes delta and its K-entry lists (the selection's extra
         # read of u and its slots are implementation, not counted); server reads the n lists, reads and
         # writes its error, writes its list; gather writes dense m to n slices and takes the model step
+        # with the gather deferred the worker call decodes the server's list instead of reading m and writes m
+        # (not with implicit momentum), and the gather call is the model step alone
         kf = topk_K / L
         ab["compress"] = (16.0 + 8.0 * kf) * n
         ab["server_reduce"] = 8.0 * kf * n + 8.0 + 8.0 * kf
         ab["apply"] = 4.0 * n + 12.0 + 8.0 * kf
+        if gather_deferred:
+            ab["compress"] += 8.0 * kf * n - (4.0 * n if deferral & B.APMS_IMPLICIT_MOMENTUM else 0.0)
+            ab["apply"] -= 4.0 * n
     if args.algo == "gradient":
         # worker: read g, delta; write delta, n/8 signs.  apply: read + write m per worker, n/8 signs, v, x, x
         ab["compress"] = (8.0 + gbytes) * n + n / 8.0

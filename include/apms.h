@@ -345,16 +345,22 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
 
 /*
  * Top-k compressor (Section 5.1, second bullet) under the same error-compensated worker / server /
- * gather structure: C[u] keeps the K elements of largest |u| of every chunk (the paper's "top k%":
- * K = k% of chunk_elems, chosen by the caller) and zeroes the rest.  Between equal magnitudes the lower
+ * gather structure: C[u] keeps the K elements of largest |u| of every chunk (K is the paper's percentage
+ * of chunk_elems, chosen by the caller) and zeroes the rest.  Between equal magnitudes the lower
  * index is kept first (the paper is silent; this makes the result unique).  The wire form of a chunk is
  * K (index, value) pairs, indices local to the chunk and ascending; the selection is exact.
- * The gather is always eager here (apms_topk_apply writes m).  APMS_DEFER_ERRORS applies: eagerly, a call
- * zeroes the kept positions of its error buffer before its work ends (scattered stores); deferred, it leaves the
- * compensated vector in the buffer whole and the context remembers each chunk's threshold, and the next
- * apms_topk_compress / apms_topk_server_reduce on the SAME buffer (or apms_finalize) reads the kept positions as
- * zero - the same values.  A buffer left so by a top-k call and one left by a 1-bit call are different forms:
- * each path returns ESTATE while the other has a buffer pending, and for a pending buffer other than its own.
+ * The deferral flags apply as in the 1-bit path.  APMS_DEFER_ERRORS: eagerly, a call zeroes the kept positions
+ * of its error buffer before its work ends (scattered stores); deferred, it leaves the compensated vector in the
+ * buffer whole and the context remembers each chunk's threshold, and the next apms_topk_compress /
+ * apms_topk_server_reduce on the SAME buffer (or apms_finalize) reads the kept positions as zero - the same
+ * values.  APMS_DEFER_GATHER: apms_topk_apply takes the model step and leaves m untouched; the next
+ * apms_topk_compress on the SAME m (or apms_finalize) decodes the server's list, uses it as the momentum and
+ * writes it to m (with APMS_IMPLICIT_MOMENTUM it does not write m: m is then defined only by apms_finalize
+ * between apms_topk_apply and that call).  Until then the context reads sidx and sval where the caller passed
+ * them: they must stay unchanged, and an apms_topk_server_reduce that would write over them returns ESTATE.
+ * A buffer left pending by a top-k call and one left by a 1-bit call are different forms: each path returns
+ * ESTATE for a buffer the other left pending, and for a pending buffer other than the one it is given
+ * (apms_apply and apms_topk_apply supersede a gather pending on the m they are given).
  * EINVAL unless 1 <= K <= chunk_elems; ESHAPE if chunk_elems > 2^31 or K > 2^31 - 1.
  *
  * apms_topk_reserve(ctx, K_max) is the set-up call that allocates the selection's scratch, sized for calls
@@ -367,16 +373,17 @@ int apms_apply_gradient(apms_ctx *ctx, const uint32_t *spacked, const float *ssc
  *
  * apms_topk_compress:       u = (fl(beta*m_i) + fl(fl(1-beta)*g_i)) + delta_i ;  (idx, val) <- C[u] ;
  *                           delta_i <- u - C[u]  (zero where kept, u elsewhere)
- *     m, g [n][d] in;  worker_err [n][d] in/out;  idx, val [n][C][K] out.
+ *     m [n][d] in (out, or untouched, while a gather is pending on it);  g [n][d] in;  worker_err [n][d]
+ *     in/out;  idx, val [n][C][K] out.
  * apms_topk_server_reduce:  ubar = (sum_{i=0}^{n-1} C[u_i]) * fl(1/n) + deltabar  (decoded lists summed in
  *                           worker order) ;  (sidx, sval) <- C[ubar] ;  deltabar <- ubar - C[ubar]
  *     idx, val [n][C][K] in, as written by apms_topk_compress;  server_err [d] in/out;  sidx, sval [C][K] out.
  * apms_topk_apply:          m_i <- C[ubar] (dense: zero outside the kept positions) for every worker ;
  *                           x <- x - lr * ( m / (sqrt(v) + eps) )
- *     sidx, sval [C][K], v [d] in;  x [d] in/out;  m [n][d] out.
+ *     sidx, sval [C][K], v [d] in;  x [d] in/out;  m [n][d] out (untouched with APMS_DEFER_GATHER).
  */
 int apms_topk_reserve(apms_ctx *ctx, int64_t K_max);
-int apms_topk_compress(apms_ctx *ctx, const float *m, const float *g, float *worker_err, uint32_t *idx,
+int apms_topk_compress(apms_ctx *ctx, float *m, const float *g, float *worker_err, uint32_t *idx,
                        float *val, int64_t K, float beta, void *stream);
 int apms_topk_server_reduce(apms_ctx *ctx, const uint32_t *idx, const float *val, int64_t K, float *server_err,
                             uint32_t *sidx, float *sval, void *stream);

@@ -43,6 +43,10 @@ struct apms_ctx {
     // deferral bookkeeping (host side, follows call order = stream order)
     const void* pending_werr = nullptr;       // error buffers that hold u instead of delta
     const void* pending_serr = nullptr;
+    bool pending_m_topk = false;              // ... by apms_topk_apply: the momentum is the server's list below, decoded
+    const uint32_t* pending_sidx = nullptr;   //     (the caller's arrays, which have to stay as they are meanwhile)
+    const float* pending_sval = nullptr;
+    int64_t pending_gather_K = 0;
     bool pending_werr_topk = false;           // ... left so by a top-k call (kept positions still in, see TopkScratch.keep)
     bool pending_serr_topk = false;           //     rather than by a 1-bit call (context scales w_pending / s_pending)
     const void* pending_m = nullptr;          // momentum buffer whose gather is still to be written ...
@@ -162,9 +166,18 @@ struct DeviceScope {
     }
 };
 
+void clear_pending_gather(apms_ctx* c) {
+    c->pending_m = nullptr;
+    c->pending_m_topk = false;
+    c->pending_spacked = nullptr;
+    c->pending_sidx = nullptr;
+    c->pending_sval = nullptr;
+    c->pending_gather_K = 0;
+}
+
 void free_topk_scratch(apms_ctx* c) {
-    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.near, c->topk.tile_counts,
-                      c->topk.tile_split, c->topk.slots};
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.near, c->topk.gather_offsets,
+                      c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
     for (void* a : arrays)
         if (a) (void)hipFree(a);
     c->topk = {};
@@ -179,7 +192,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
     const int64_t guesses = pairs + c->C;                     // the worker call's pairs, then the server call's chunks
     const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords + 2 * apms::kTopkNearCap) + 3 * guesses) * 4 +
-                          2 * tiles * 4;
+                          2 * tiles * 4 + tiles / c->n * 4;
     const int32_t want = apms::topk_slots_for(K_max, c->L);
     if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
     hipError_t e = hipDeviceSynchronize();                     // kernels of earlier calls may still use the scratch
@@ -190,6 +203,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), guesses * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.keep), guesses * 8);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.near), pairs * apms::kTopkNearCap * 8);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.gather_offsets), tiles / c->n * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_counts), tiles * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.tile_split), tiles * 4);
         if (e != hipSuccess) {
@@ -488,12 +502,15 @@ int apms_finalize(apms_ctx* c, float* worker_err, float* server_err, float* m, v
         c->pending_serr_topk = false;
     }
     if (m && c->pending_m == m) {
-        hipError_t e = apms::launch_apply(geo, c->pending_spacked, c->g_pending, nullptr, nullptr, m, nullptr,
-                                          /*write_m=*/true, /*model_step=*/false, 0.0f, 0.0f,
-                                          c->lds_pad[APMS_KERNEL_APPLY], s);
+        hipError_t e = c->pending_m_topk
+                           ? apms::launch_topk_apply(geo, c->pending_gather_K, c->pending_sidx, c->pending_sval, nullptr,
+                                                     nullptr, m, 0.0f, 0.0f, /*write_m=*/true, /*model_step=*/false,
+                                                     c->topk, s)
+                           : apms::launch_apply(geo, c->pending_spacked, c->g_pending, nullptr, nullptr, m, nullptr,
+                                                /*write_m=*/true, /*model_step=*/false, 0.0f, 0.0f,
+                                                c->lds_pad[APMS_KERNEL_APPLY], s);
         if (e != hipSuccess) return hip_fail(c, e);
-        c->pending_m = nullptr;
-        c->pending_spacked = nullptr;
+        clear_pending_gather(c);
     }
     return APMS_OK;
 }
@@ -545,11 +562,11 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
     const int64_t all = c->d * 4 * c->n;
     const bool gather = with_momentum && c->pending_m != nullptr;
     const Range r[] = {{g, c->d * gbytes * c->n}, {worker_err, all}, {packed, all / 32}, {scales, c->n * c->C * 4},
-                       {m, with_momentum ? all : 0}, {c->pending_spacked, gather ? c->d / 8 : 0}};
+                       {m, with_momentum ? all : 0}, {c->pending_spacked, (gather && !c->pending_m_topk) ? c->d / 8 : 0}};
     if (int rc = check_arrays(r, 6)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
     if (c->pending_werr && (c->pending_werr != worker_err || c->pending_werr_topk)) return APMS_ESTATE;
-    if (gather && c->pending_m != m) return APMS_ESTATE;
+    if (gather && (c->pending_m != m || c->pending_m_topk)) return APMS_ESTATE;   // another buffer, or the top-k path's form
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -598,10 +615,7 @@ int compress_impl(apms_ctx* c, bool with_momentum, float* m, const void* g, int 
     if (e != hipSuccess) return hip_fail(c, e);
     // every launch of the call is queued: m holds the gathered momentum (unless implicit); deferred, the
     // error buffer holds u and the context its scales
-    if (gather) {
-        c->pending_m = nullptr;
-        c->pending_spacked = nullptr;
-    }
+    if (gather) clear_pending_gather(c);
     c->pending_werr = eager ? nullptr : worker_err;
     return APMS_OK;
 }
@@ -664,7 +678,7 @@ int apms_server_reduce(apms_ctx* c, const uint32_t* packed, const float* scales,
     if (int rc = check_arrays(r, 5)) return rc;
     if (c->pending_serr && (c->pending_serr != server_err || c->pending_serr_topk)) return APMS_ESTATE;
     // a pending gather still needs the sign words at that address
-    if (c->pending_m && overlap({c->pending_spacked, vec / 32}, {spacked, vec / 32})) return APMS_ESTATE;
+    if (c->pending_m && !c->pending_m_topk && overlap({c->pending_spacked, vec / 32}, {spacked, vec / 32})) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -740,6 +754,7 @@ int apms_apply(apms_ctx* c, const uint32_t* spacked, const float* sscales, const
     if (e != hipSuccess) return hip_fail(c, e);
     // eager: m is final (a gather pending on it from an earlier call is superseded);
     // deferred: m is to be written from these sign words and the saved scales
+    clear_pending_gather(c);
     c->pending_m = defer ? m : nullptr;
     c->pending_spacked = defer ? spacked : nullptr;
     return APMS_OK;
@@ -783,27 +798,36 @@ int apms_topk_reserve(apms_ctx* c, int64_t K_max) {
     return e == hipSuccess ? APMS_OK : hip_fail(c, e);
 }
 
-int apms_topk_compress(apms_ctx* c, const float* m, const float* g, float* worker_err, uint32_t* idx, float* val,
+int apms_topk_compress(apms_ctx* c, float* m, const float* g, float* worker_err, uint32_t* idx, float* val,
                        int64_t K, float beta, void* stream) {
     if (!c) return APMS_EINVAL;
     if (c->d > 0)
         if (int rc = topk_shape_ok(c, K)) return rc;
     const int64_t all = c->d * 4 * c->n, lists = c->n * c->C * K * 4;
-    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {idx, lists}, {val, lists}};
-    if (int rc = check_arrays(r, 5)) return rc;
+    const bool gather = c->pending_m != nullptr;
+    const int64_t glists = gather ? c->C * c->pending_gather_K * 4 : 0;
+    const Range r[] = {{m, all}, {g, all}, {worker_err, all}, {idx, lists}, {val, lists},
+                       {c->pending_sidx, glists}, {c->pending_sval, glists}};
+    if (int rc = check_arrays(r, 7)) return rc;
     if (!unit_interval(beta)) return APMS_EINVAL;
-    // this path reads m as it is, and the error either final or as a top-k call left it
-    if (c->pending_m || (c->pending_werr && !(c->pending_werr_topk && c->pending_werr == worker_err))) return APMS_ESTATE;
+    // the momentum is read as it is, or is the pending gather of this path on this buffer; the error is final or
+    // as a top-k call left it
+    if (gather && !(c->pending_m_topk && c->pending_m == m)) return APMS_ESTATE;
+    if (c->pending_werr && !(c->pending_werr_topk && c->pending_werr == worker_err)) return APMS_ESTATE;
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
     if (!topk_reserved_for(c, K)) return APMS_ESTATE;
     const bool defer = (c->deferral & APMS_DEFER_ERRORS) != 0;
-    hipError_t e = apms::launch_topk_compress(geometry(c), K, m, g, worker_err, idx, val, beta, 1.0f - beta,
-                                              c->pending_werr != nullptr, defer, c->topk,
+    const apms::TopkGather list = {c->pending_sidx, c->pending_sval, c->pending_gather_K};
+    // implicit momentum: the pending gather is consumed without materialising m
+    float* m_arg = (gather && (c->deferral & APMS_IMPLICIT_MOMENTUM)) ? nullptr : m;
+    hipError_t e = apms::launch_topk_compress(geometry(c), K, m_arg, g, worker_err, idx, val, beta, 1.0f - beta,
+                                              c->pending_werr != nullptr, defer, gather ? &list : nullptr, c->topk,
                                               static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(c, e);
+    if (gather) clear_pending_gather(c);
     c->pending_werr = defer ? worker_err : nullptr;
     c->pending_werr_topk = defer;
     return APMS_OK;
@@ -818,6 +842,13 @@ int apms_topk_server_reduce(apms_ctx* c, const uint32_t* idx, const float* val, 
     const Range r[] = {{idx, lists}, {val, lists}, {server_err, c->d * 4}, {sidx, slists}, {sval, slists}};
     if (int rc = check_arrays(r, 5)) return rc;
     if (c->pending_serr && !(c->pending_serr_topk && c->pending_serr == server_err)) return APMS_ESTATE;
+    // a pending gather still needs the server's list at that address
+    if (c->pending_m && c->pending_m_topk) {
+        const int64_t held = c->C * c->pending_gather_K * 4;
+        if (overlap({c->pending_sidx, held}, {sidx, slists}) || overlap({c->pending_sval, held}, {sval, slists}) ||
+            overlap({c->pending_sidx, held}, {sval, slists}) || overlap({c->pending_sval, held}, {sidx, slists}))
+            return APMS_ESTATE;
+    }
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
@@ -842,15 +873,26 @@ int apms_topk_apply(apms_ctx* c, const uint32_t* sidx, const float* sval, int64_
     const Range r[] = {{sidx, slists}, {sval, slists}, {v, vec}, {x, vec}, {m, vec * c->n}};
     if (int rc = check_arrays(r, 5)) return rc;
     if (!(lr == lr) || !(eps == eps)) return APMS_EINVAL;
-    if (c->pending_m) return APMS_ESTATE;
+    if (c->pending_m && c->pending_m != m) return APMS_ESTATE;   // a gather pending on the same buffer is superseded
     int status;
     if (!ready_to_launch(c, &status)) return status;
     DeviceScope scope(c->device);
     if (scope.err != hipSuccess) return hip_fail(c, scope.err);
     if (!topk_reserved_for(c, K)) return APMS_ESTATE;
-    hipError_t e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps, c->topk,
-                                    static_cast<hipStream_t>(stream));
-    return e == hipSuccess ? APMS_OK : hip_fail(c, e);
+    const bool defer = (c->deferral & APMS_DEFER_GATHER) != 0;
+    hipError_t e = apms::launch_topk_apply(geometry(c), K, sidx, sval, v, x, m, lr, eps, /*write_m=*/!defer,
+                                           /*model_step=*/true, c->topk, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(c, e);
+    // eager: m is final; deferred: m is to be written from this list, which the caller leaves as it is until then
+    clear_pending_gather(c);
+    if (defer) {
+        c->pending_m = m;
+        c->pending_m_topk = true;
+        c->pending_sidx = sidx;
+        c->pending_sval = sval;
+        c->pending_gather_K = K;
+    }
+    return APMS_OK;
 }
 
 }  // extern "C"

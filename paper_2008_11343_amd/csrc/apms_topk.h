@@ -52,6 +52,7 @@ inline int32_t topk_slots_for(int64_t K, int64_t L) {
 //                                        0xFFFFFFFF in a new context and whenever the slots are re-allocated
 //   near        [pairs][kTopkNearCap] uint2   the slot entries that share the top 22 key bits of the pair's threshold:
 //                                        (chunk-local index, key), in no particular order
+//   gather_offsets [C][tiles] u32        tile offsets of the server's list while its gather is pending on m
 //   keep        [pairs + C] uint2        {T, idxT} of the last call per pair, for an error buffer left in deferred
 //                                        form (APMS_DEFER_ERRORS): worker pairs, then the server's chunks
 struct TopkScratch {
@@ -60,10 +61,19 @@ struct TopkScratch {
     uint32_t* guess;
     uint2* keep;
     uint2* near;
+    uint32_t* gather_offsets;
     uint32_t* tile_counts;
     uint32_t* tile_split;
     uint2* slots;
     int32_t slots_per_tile;
+};
+
+// The server's list of the previous step while its gather is pending on m: [C][K] (index, value) pairs, with
+// their tile offsets in TopkScratch.gather_offsets (left by launch_topk_apply with write_m = false).
+struct TopkGather {
+    const uint32_t* idx;
+    const float* val;
+    int64_t K;
 };
 
 // Worker: u = beta*m + (1-beta)*g + delta for all (worker, chunk) pairs, written into werr, then the K
@@ -71,9 +81,11 @@ struct TopkScratch {
 // their positions in werr are zeroed, which leaves werr = u - C[u].
 // werr_pending: werr holds the previous call's compensated vector with the kept positions still in (deferred
 // form; scratch.keep says which they are).  defer: leave it in that form again instead of zeroing them.
-hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, const float* g, float* werr,
-                                uint32_t* idx, float* val, float beta, float one_minus_beta, bool werr_pending,
-                                bool defer, const TopkScratch& scratch, hipStream_t stream);
+// gather: null = m is read; else the momentum is that list decoded (zero elsewhere) and is written to m
+// unless m is null.
+hipError_t launch_topk_compress(const Geometry& geo, int64_t K, float* m, const float* g, float* werr, uint32_t* idx,
+                                float* val, float beta, float one_minus_beta, bool werr_pending, bool defer,
+                                const TopkGather* gather, const TopkScratch& scratch, hipStream_t stream);
 
 // Server: ubar = (sum over workers of the decoded lists, worker order) * inv_n + serr, written into serr,
 // then top-K per chunk to sidx/sval [C][K], kept positions of serr zeroed.
@@ -86,9 +98,11 @@ hipError_t launch_topk_finalize(const Geometry& geo, bool server, float* err, co
                                 hipStream_t stream);
 
 // Gather + model update: every slice of m becomes the decoded server list (zero elsewhere);
-// x <- x - lr * m / (sqrt(v) + eps).
+// x <- x - lr * m / (sqrt(v) + eps).  write_m false: the model step alone, m is not touched and the list's tile
+// offsets are left in scratch.gather_offsets for the worker call that carries the gather out; model_step false
+// (with write_m): the gather alone.
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
-                             const float* v, float* x, float* m, float lr, float eps, const TopkScratch& scratch,
-                             hipStream_t stream);
+                             const float* v, float* x, float* m, float lr, float eps, bool write_m, bool model_step,
+                             const TopkScratch& scratch, hipStream_t stream);
 
 }  // namespace apms

@@ -144,6 +144,7 @@ __device__ __forceinline__ uint64_t block_exclusive_scan_u64(uint64_t v, uint64_
 // Decomposition of blockIdx into (pair, tile) for kernels that take one kTopkTile tile per workgroup.
 struct TileRef {
     int64_t pair;        // slice * C + chunk
+    int64_t chunk;
     int64_t tile;
     int64_t base;        // element offset of the chunk inside the [slices][d] buffer
 };
@@ -153,8 +154,8 @@ __device__ __forceinline__ TileRef tile_ref(int64_t d, int64_t L, int32_t C, int
     r.pair = blk / tiles_per_chunk;
     r.tile = blk - r.pair * tiles_per_chunk;
     const int64_t slice = r.pair / C;
-    const int64_t chunk = r.pair - slice * C;
-    r.base = slice * d + chunk * L;
+    r.chunk = r.pair - slice * C;
+    r.base = slice * d + r.chunk * L;
     return r;
 }
 
@@ -268,15 +269,23 @@ __device__ __forceinline__ uint32_t count_and_slot_marked(const float* tile_valu
 // One tile per workgroup: taking several tiles in a loop (one histogram flush for all of them, or with the
 // next tile's loads requested ahead) was measured 3 to 10 % slower, like the 1-bit worker kernel this pass
 // streams best as many short-lived workgroups.
-__global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __restrict__ m,
-                                                                 const float* __restrict__ g,
+//
+// kGather: a gather is pending on m (Algorithm 1 line 10 not yet carried out): the momentum of every worker
+// is the server's list of the previous step (gather_idx, gather_val: [C][gather_K], with the table of tile
+// offsets apms_topk_apply left), zero elsewhere.  The tile's stretch of the list is decoded into the LDS
+// tile, used directly as the momentum term and written to m (unless m is null: implicit-momentum mode).
+template <bool kGather>
+__global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(float* __restrict__ m, const float* __restrict__ g,
                                                                  float* __restrict__ e, uint32_t* __restrict__ hist,
                                                                  uint32_t* __restrict__ state,
                                                                  const uint32_t* __restrict__ guess,
                                                                  uint32_t* __restrict__ tile_split,
                                                                  uint2* __restrict__ slots, int32_t slots_per_tile,
                                                                  const uint2* __restrict__ prev_keep,
-                                                                 int64_t d, int64_t L, int32_t C,
+                                                                 const uint32_t* __restrict__ gather_idx,
+                                                                 const float* __restrict__ gather_val,
+                                                                 const uint32_t* __restrict__ gather_offsets,
+                                                                 int32_t gather_K, int64_t d, int64_t L, int32_t C,
                                                                  int32_t tiles_per_chunk, float beta, float omb) {
     __shared__ uint32_t lds_window[kHistWindow];
     __shared__ uint64_t lds_scan[kWaves];
@@ -288,26 +297,59 @@ __global__ __launch_bounds__(kThreads) void topk_worker_u_kernel(const float* __
     const uint2 keep = prev_keep ? prev_keep[tr.pair] : make_uint2(0xFFFFFFFFu, 0u);   // error buffer in deferred form?
     const uint32_t floor_key = guess[tr.pair];                // 0xFFFFFFFF: no earlier call, nothing passes
     const uint32_t guessed = floor_key >> 20;                 // first bin of the histogram window
+    f32x4 vg[kTileRows], ve[kTileRows], vm[kTileRows];
+#pragma unroll
+    for (int r = 0; r < kTileRows; ++r) {                      // requested first: they arrive during the decode
+        const int64_t off = off0 + r * kRowStride;
+        vg[r] = ve[r] = vm[r] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        if (off >= L) continue;
+        const int64_t p = tr.base + off;
+        vg[r] = load_stream(g + p);
+        ve[r] = load_stream(e + p);
+        if (!kGather) vm[r] = load_stream(m + p);
+    }
+    if (kGather) {
+        const int64_t chunk = tr.chunk;
+        const uint32_t* off = gather_offsets + chunk * tiles_per_chunk + tr.tile;
+        const int last = min((tr.tile + 1 < tiles_per_chunk) ? static_cast<int>(off[1]) : gather_K, gather_K);   // min, first >= 0:
+        const int first = max(static_cast<int>(off[0]), 0);                                                     // no-ops for sorted lists
+#pragma unroll
+        for (int r = 0; r < kTileRows; ++r)
+            *reinterpret_cast<f32x4*>(&tile_u[threadIdx.x * 4 + r * kRowStride]) = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+        __syncthreads();
+        const int64_t list = chunk * gather_K;
+        const uint32_t tile_lo = static_cast<uint32_t>(tr.tile * kTopkTile);
+        for (int t = first + threadIdx.x; t < last; t += kThreads) {
+            const uint32_t j = gather_idx[list + t] - tile_lo;
+            if (j < static_cast<uint32_t>(kTopkTile)) tile_u[j] = gather_val[list + t];      // always true for sorted lists
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kTileRows; ++r) {
+            const int64_t off = off0 + r * kRowStride;
+            if (off >= L) continue;
+            vm[r] = *reinterpret_cast<const f32x4*>(&tile_u[threadIdx.x * 4 + r * kRowStride]);
+            if (m) store_stream(m + tr.base + off, vm[r]);
+        }
+    }
     uint32_t take_mask = 0;
 #pragma unroll
     for (int r = 0; r < kTileRows; ++r) {
         const int64_t off = off0 + r * kRowStride;
         if (off >= L) continue;
-        const int64_t p = tr.base + off;
-        const f32x4 vm = load_stream(m + p), vg = load_stream(g + p), ve = load_stream(e + p);
         f32x4 u;
 #pragma unroll
         for (int c = 0; c < 4; ++c) {
-            const float bm = beta * vm[c];
-            const float bg = omb * vg[c];
+            const float bm = beta * vm[r][c];
+            const float bg = omb * vg[r][c];
             const float mi = bm + bg;
-            const float stored = ve[c];
+            const float stored = ve[r][c];
             u[c] = mi + deferred_error(stored, static_cast<uint32_t>(off + c), keep);
             const float value = u[c];
             take_mask |= key_of(value) >= floor_key ? 1u << (4 * r + c) : 0u;   // at or above the floor: counted and slotted
         }
-        *reinterpret_cast<f32x4*>(&tile_u[threadIdx.x * 4 + r * kRowStride]) = u;
-        store_stream(e + p, u);
+        *reinterpret_cast<f32x4*>(&tile_u[threadIdx.x * 4 + r * kRowStride]) = u;   // this thread's own four positions
+        store_stream(e + tr.base + off, u);
     }
     const int64_t tile_id = tr.pair * tiles_per_chunk + tr.tile;
     const uint32_t marked = count_and_slot_marked(tile_u, take_mask, lds_scan, lds_window, pair_hist, guessed,
@@ -1197,7 +1239,7 @@ __global__ __launch_bounds__(kThreads) void topk_emit_walk_kernel(float* __restr
 // One workgroup = one tile of ROWS * 1024 elements of ONE worker's momentum slice, slice-major like the
 // 1-bit gather: the n slices are one long contiguous fill.  The tile's stretch of the list is staged
 // through LDS (zero, scatter, read back as quads).
-template <int ROWS>
+template <int ROWS, bool kWriteM, bool kModelStep>
 __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __restrict__ sidx,
                                                               const float* __restrict__ sval,
                                                               const float* __restrict__ v, float* __restrict__ x,
@@ -1207,7 +1249,7 @@ __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __
                                                               int32_t K, float lr, float eps) {
     constexpr int kTile = ROWS * kRowStride;
     __shared__ float dense[kTile];
-    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // pair = slice * C + chunk
+    const TileRef tr = tile_ref(d, L, C, tiles_per_chunk);    // pair = slice * C + chunk; slice 0 only if !kWriteM
     const int64_t slice = tr.pair / C;
     const int64_t chunk = tr.pair - slice * C;
     const int64_t tile_lo = tr.tile * kTile;
@@ -1222,14 +1264,14 @@ __global__ __launch_bounds__(kThreads) void topk_apply_kernel(const uint32_t* __
         if (j < static_cast<uint32_t>(kTile)) dense[j] = sval[list + t];                 // always true for sorted lists
     }
     __syncthreads();
-    const bool model_step = (slice == 0);
+    const bool model_step = kModelStep && (slice == 0);
 #pragma unroll
     for (int r = 0; r < ROWS; ++r) {
         const int local = threadIdx.x * 4 + r * kRowStride;
         const int64_t off = tile_lo + local;
         if (off >= L) continue;
         const f32x4 mom = {dense[local], dense[local + 1], dense[local + 2], dense[local + 3]};
-        store_stream(m + tr.base + off, mom);
+        if (kWriteM) store_stream(m + tr.base + off, mom);
         if (model_step) {
             const int64_t p = chunk * L + off;
             const f32x4 vv = load_stream(v + p), vx = load_stream(x + p);
@@ -1379,10 +1421,10 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
     return hipSuccess;
 }
 
-// Fills s.tile_counts[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries;
+// Fills table[lists][tiles_per_chunk] with the tile offsets of `lists` sorted index lists of K entries;
 // tile_elems is a power of two.
 hipError_t tile_offsets(int64_t lists, int32_t tpc, int32_t tile_elems, int64_t K, const uint32_t* idx,
-                        const TopkScratch& s, hipStream_t stream) {
+                        uint32_t* table, hipStream_t stream) {
     const int64_t per_block = kThreads * kOffsetsPerThread;
     const int64_t blocks_per_list = (K + per_block - 1) / per_block;
     const int64_t blocks = lists * blocks_per_list;
@@ -1390,7 +1432,7 @@ hipError_t tile_offsets(int64_t lists, int32_t tpc, int32_t tile_elems, int64_t 
     int tile_shift = 0;
     while ((1 << tile_shift) < tile_elems) ++tile_shift;
     hipLaunchKernelGGL(topk_tile_offsets_kernel, dim3(static_cast<uint32_t>(blocks)), dim3(kThreads), 0, stream, idx,
-                       s.tile_counts, tpc, tile_shift, static_cast<int32_t>(K), static_cast<int32_t>(blocks_per_list));
+                       table, tpc, tile_shift, static_cast<int32_t>(K), static_cast<int32_t>(blocks_per_list));
     return hipGetLastError();
 }
 
@@ -1404,9 +1446,9 @@ hipError_t begin_call(int64_t pairs, bool resplit, const TopkScratch& s, hipStre
 
 }  // namespace
 
-hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, const float* g, float* werr,
-                                uint32_t* idx, float* val, float beta, float one_minus_beta, bool werr_pending,
-                                bool defer, const TopkScratch& scratch, hipStream_t stream) {
+hipError_t launch_topk_compress(const Geometry& geo, int64_t K, float* m, const float* g, float* werr, uint32_t* idx,
+                                float* val, float beta, float one_minus_beta, bool werr_pending, bool defer,
+                                const TopkGather* gather, const TopkScratch& scratch, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
     if (pairs <= 0) return hipSuccess;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
@@ -1415,10 +1457,18 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, const float* m, 
     // unused dynamic LDS that caps the pass at 3 workgroups per CU: measured 3 % faster than uncapped, 2
     // workgroups per CU are slower again
     constexpr uint32_t kWorkerPassPad = 34 * 1024;           // beside the kernel's own 17 KB
-    hipLaunchKernelGGL(topk_worker_u_kernel, dim3(static_cast<uint32_t>(pairs * tpc)), dim3(kThreads), kWorkerPassPad, stream, m, g,
-                       werr, scratch.hist, scratch.state, scratch.guess, scratch.tile_split, scratch.slots,
-                       scratch.slots_per_tile, werr_pending ? scratch.keep : static_cast<const uint2*>(nullptr), geo.d,
-                       geo.L, geo.C, tpc, beta, one_minus_beta);
+    const dim3 grid(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
+    const uint2* prev_keep = werr_pending ? scratch.keep : static_cast<const uint2*>(nullptr);
+    if (gather)
+        hipLaunchKernelGGL(topk_worker_u_kernel<true>, grid, block, kWorkerPassPad, stream, m, g, werr, scratch.hist,
+                           scratch.state, scratch.guess, scratch.tile_split, scratch.slots, scratch.slots_per_tile,
+                           prev_keep, gather->idx, gather->val, scratch.gather_offsets, static_cast<int32_t>(gather->K),
+                           geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
+    else
+        hipLaunchKernelGGL(topk_worker_u_kernel<false>, grid, block, kWorkerPassPad, stream, m, g, werr, scratch.hist,
+                           scratch.state, scratch.guess, scratch.tile_split, scratch.slots, scratch.slots_per_tile,
+                           prev_keep, static_cast<const uint32_t*>(nullptr), static_cast<const float*>(nullptr),
+                           static_cast<const uint32_t*>(nullptr), 0, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
     APMS_RETURN_IF_ERROR();
     return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, defer ? scratch.keep : nullptr, scratch, stream);
 }
@@ -1430,7 +1480,7 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     hipError_t e = begin_call(geo.C, /*resplit=*/false, scratch, stream);
     if (e != hipSuccess) return e;
-    e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, kTopkTile, K, idx, scratch, stream);
+    e = tile_offsets(static_cast<int64_t>(geo.n) * geo.C, tpc, kTopkTile, K, idx, scratch.tile_counts, stream);
     if (e != hipSuccess) return e;
     uint32_t* server_guess = scratch.guess + static_cast<int64_t>(geo.n) * geo.C;   // after the workers' entries
     uint2* server_keep = scratch.keep + static_cast<int64_t>(geo.n) * geo.C;
@@ -1460,26 +1510,41 @@ hipError_t launch_topk_finalize(const Geometry& geo, bool server, float* err, co
 }
 
 hipError_t launch_topk_apply(const Geometry& geo, int64_t K, const uint32_t* sidx, const float* sval,
-                             const float* v, float* x, float* m, float lr, float eps, const TopkScratch& scratch,
-                             hipStream_t stream) {
+                             const float* v, float* x, float* m, float lr, float eps, bool write_m, bool model_step,
+                             const TopkScratch& scratch, hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(geo.n) * geo.C;
     if (pairs <= 0) return hipSuccess;
+    const dim3 block(kThreads);
+    const int32_t K32 = static_cast<int32_t>(K);
+    if (!write_m) {
+        // the model step alone (the gather stays pending): 4096-element tiles over the one [d] vector, with the
+        // offsets table the worker's first pass will decode the list by (scratch.gather_offsets)
+        const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
+        const hipError_t e = tile_offsets(geo.C, tpc, kTopkTile, K, sidx, scratch.gather_offsets, stream);
+        if (e != hipSuccess) return e;
+        if (model_step)
+            hipLaunchKernelGGL((topk_apply_kernel<kTileRows, false, true>), dim3(static_cast<uint32_t>(geo.C) * tpc), block, 0,
+                               stream, sidx, sval, v, x, m, scratch.gather_offsets, geo.d, geo.L, geo.C, tpc, K32, lr, eps);
+        return hipGetLastError();
+    }
     // 2048-element tiles (measured best: 4.1 ms against 4.4 ms for 4096 and 5.3 ms for 1024 on the
     // BERT-Large-sized buffer), provided the offsets table for them fits the tile_counts array
     // ([n * C][L / 4096]: n >= 2)
     const int rows = geo.n >= 2 ? 2 : kTileRows;
     const int32_t tile = rows * kRowStride;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, tile));
-    const hipError_t e = tile_offsets(geo.C, tpc, tile, K, sidx, scratch, stream);
+    const hipError_t e = tile_offsets(geo.C, tpc, tile, K, sidx, scratch.tile_counts, stream);
     if (e != hipSuccess) return e;
-    const dim3 grid(static_cast<uint32_t>(pairs * tpc)), block(kThreads);
-    const int32_t K32 = static_cast<int32_t>(K);
-    if (rows == 2)
-        hipLaunchKernelGGL(topk_apply_kernel<2>, grid, block, 0, stream, sidx, sval, v, x, m, scratch.tile_counts, geo.d,
-                           geo.L, geo.C, tpc, K32, lr, eps);
-    else
-        hipLaunchKernelGGL(topk_apply_kernel<kTileRows>, grid, block, 0, stream, sidx, sval, v, x, m,
-                           scratch.tile_counts, geo.d, geo.L, geo.C, tpc, K32, lr, eps);
+    const dim3 grid(static_cast<uint32_t>(pairs * tpc));
+#define APMS_LAUNCH_TOPK_APPLY(ROWS, STEP)                                                                          \
+    hipLaunchKernelGGL((topk_apply_kernel<ROWS, true, STEP>), grid, block, 0, stream, sidx, sval, v, x, m,           \
+                       scratch.tile_counts, geo.d, geo.L, geo.C, tpc, K32, lr, eps)
+    if (rows == 2) {
+        if (model_step) APMS_LAUNCH_TOPK_APPLY(2, true); else APMS_LAUNCH_TOPK_APPLY(2, false);
+    } else {
+        if (model_step) APMS_LAUNCH_TOPK_APPLY(kTileRows, true); else APMS_LAUNCH_TOPK_APPLY(kTileRows, false);
+    }
+#undef APMS_LAUNCH_TOPK_APPLY
     return hipGetLastError();
 }
 

@@ -37,15 +37,18 @@ def same(a, b, what):
 
 
 def compare(run, ost, tag, errors=True):
-    """errors=False: the error buffers are in deferred form (APMS_DEFER_ERRORS) and not compared."""
+    """errors: False, or a deferral mask: buffers that are in deferred form (the errors with APMS_DEFER_ERRORS,
+    the momentum with APMS_DEFER_GATHER) are not compared; True or 0: everything is."""
+    mode = 0 if errors is True else B.APMS_DEFER_ERRORS if errors is False else int(errors)
     same(host(run.idx), ost.idx, tag + " worker indices")
     same(host(run.val), ost.val, tag + " worker values")
     same(host(run.sidx), ost.sidx, tag + " server indices")
     same(host(run.sval), ost.sval, tag + " server values")
-    if errors:
+    if not mode & B.APMS_DEFER_ERRORS:
         same(host(run.werr), ost.werr, tag + " worker_err")
         same(host(run.serr), ost.serr, tag + " server_err")
-    same(host(run.m), ost.m, tag + " momentum")
+    if not mode & B.APMS_DEFER_GATHER:
+        same(host(run.m), ost.m, tag + " momentum")
     np.testing.assert_allclose(host(run.x), ost.x, rtol=1e-5, atol=1e-7, err_msg=tag + " x")
 
 
@@ -56,17 +59,20 @@ def make(d, n, L, st, deferred=0):
 
 
 def settle(run, ost, tag, deferred, now):
-    """With the errors deferred they are final only after apms_finalize: materialise and compare them `now`
-    (mid-run: the run then goes on from final buffers) or leave them pending."""
+    """Deferred buffers are final only after apms_finalize: materialise and compare them `now` (mid-run: the run
+    then goes on from final buffers) or leave them pending."""
     if deferred and now:
         run.finalize()
         torch.cuda.synchronize()
         same(host(run.werr), ost.werr, tag + " worker_err after finalize")
         same(host(run.serr), ost.serr, tag + " server_err after finalize")
+        same(host(run.m), ost.m, tag + " momentum after finalize")
 
 
-MODES = [0, B.APMS_DEFER_ERRORS]
-MODE_IDS = ["eager", "defer-errors"]
+IMPLICIT = B.APMS_DEFER_GATHER | B.APMS_IMPLICIT_MOMENTUM
+MODES = [0, B.APMS_DEFER_ERRORS, B.APMS_DEFER_GATHER, B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER,
+         B.APMS_DEFER_ERRORS | IMPLICIT]
+MODE_IDS = ["eager", "defer-errors", "defer-gather", "defer-all", "implicit"]
 
 
 CASES = [
@@ -97,7 +103,7 @@ def test_topk_trajectory(n, L, C, K, deferred):
         g = W.host_grad(wl, step)
         run.step_topk(torch.from_numpy(g).to(DEV), K, wl.beta, wl.lr, wl.eps)
         ost.step_topk(g, K, wl.beta, wl.lr, wl.eps)
-        compare(run, ost, "step %d" % step, errors=not deferred)
+        compare(run, ost, "step %d" % step, errors=deferred)
         settle(run, ost, "step %d" % step, deferred, now=step in (1, wl.steps - 1))
     run.close()
 
@@ -113,7 +119,7 @@ def sweep_cases():
         L = 32 * int(rng.integers(1, 1500))
         C = int(rng.integers(1, 4))
         K = max(1, int(L * 10.0 ** rng.uniform(-3.5, -0.7)))
-        cases.append((i, n, L, C, K, MODES[i % 2]))
+        cases.append((i, n, L, C, K, MODES[i % len(MODES)]))
     return cases
 
 
@@ -136,7 +142,7 @@ def test_topk_random_shape_sweep(case, n, L, C, K, deferred):
             g = (rng.integers(-2, 3, (n, d)) * 0.25).astype(F)
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
-        compare(run, ost, "case %d step %d" % (case, step), errors=not deferred)
+        compare(run, ost, "case %d step %d" % (case, step), errors=deferred)
         settle(run, ost, "case %d step %d" % (case, step), deferred, now=step in (1, 3))
     run.close()
 
@@ -178,7 +184,7 @@ def test_topk_ties(K, deferred):
             g[:] = 0.0                                        # a step where the new information is all zero
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.5, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.5, 1e-3, 1e-8)
-        compare(run, ost, "ties step %d" % step, errors=not deferred)
+        compare(run, ost, "ties step %d" % step, errors=deferred)
         settle(run, ost, "ties step %d" % step, deferred, now=step == 2)
     run.close()
 
@@ -208,7 +214,7 @@ def test_topk_one_constant_tile_among_random_ones(level, deferred):
             g[1, lo:lo + 4096] = 0.0
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
-        compare(run, ost, "constant tile (%s) step %d" % (level, step), errors=not deferred)
+        compare(run, ost, "constant tile (%s) step %d" % (level, step), errors=deferred)
         settle(run, ost, "constant tile (%s) step %d" % (level, step), deferred, now=step == 2)
     run.close()
 
@@ -333,7 +339,7 @@ def test_topk_many_ties_at_the_threshold_without_full_tiles(deferred):
         g = z((n, d), F) if step == 0 else rng.normal(0, 1e-4, (n, d)).astype(F)   # step 0: u = werr exactly
         run.step_topk(torch.from_numpy(g).to(DEV), K, 0.9, 1e-3, 1e-8)
         ost.step_topk(g, K, 0.9, 1e-3, 1e-8)
-        compare(run, ost, "many ties step %d" % step, errors=not deferred)
+        compare(run, ost, "many ties step %d" % step, errors=deferred)
         settle(run, ost, "many ties step %d" % step, deferred, now=step == 2)
     run.close()
 
@@ -400,6 +406,53 @@ def test_topk_deferred_errors_state_machine():
     ost.step_topk(g, K, 0.9, 1e-4, 1e-8)
     compare(run, ost, "eager after deferred")
     run.step(gd, 0.9, 1e-4, 1e-8)                                                   # nothing pending: the 1-bit path runs
+    torch.cuda.synchronize()
+    run.close()
+
+
+@pytest.mark.parametrize("implicit", [False, True], ids=["defer-gather", "implicit"])
+def test_topk_deferred_gather_state_machine(implicit):
+    """APMS_DEFER_GATHER on the top-k path: apms_topk_apply leaves m untouched, the next apms_topk_compress on that
+    m decodes the server's list as the momentum and writes it there (not with APMS_IMPLICIT_MOMENTUM), or
+    apms_finalize does.  Meanwhile the list must stay where it is, and the 1-bit worker call refuses the buffer."""
+    n, L, C, K = 3, 4096 * 3 + 160, 2, 70
+    d = L * C
+    wl = W.Workload("topk-defer-gather", 2, d=d, n=n, chunk=L)
+    st = W.host_state(wl)
+    mode = B.APMS_DEFER_GATHER | (B.APMS_IMPLICIT_MOMENTUM if implicit else 0)
+    run, ost = make(d, n, L, st, mode)
+    m_start = host(run.m).copy()
+    g0, g1 = W.host_grad(wl, 0), W.host_grad(wl, 1)
+    gd0, gd1 = torch.from_numpy(g0).to(DEV), torch.from_numpy(g1).to(DEV)
+    run.step_topk(gd0, K, 0.9, 1e-4, 1e-8)
+    ost.step_topk(g0, K, 0.9, 1e-4, 1e-8)
+    assert np.array_equal(host(run.m), m_start), "apms_topk_apply must leave m untouched"
+    np.testing.assert_allclose(host(run.x), ost.x, rtol=1e-5, atol=1e-7)             # the model step was taken
+    other_m = torch.zeros_like(run.m)
+    sidx2, sval2 = torch.zeros_like(run.sidx), torch.zeros_like(run.sval)
+    for call in (lambda: run.compress(gd1, 0.9),                                      # 1-bit worker call on this m
+                 lambda: B.apms_topk_compress(run.ctx, other_m, gd1, run.werr, run.idx, run.val, K, 0.9),
+                 lambda: B.apms_topk_server_reduce(run.ctx, run.idx, run.val, K, run.serr, run.sidx, sval2),
+                 lambda: B.apms_topk_server_reduce(run.ctx, run.idx, run.val, K, run.serr, sidx2, run.sval),
+                 lambda: B.apms_topk_apply(run.ctx, run.sidx, run.sval, K, run.v, run.x, other_m, 1e-4, 1e-8)):
+        with pytest.raises(B.ApmsError) as ei:
+            call()
+        assert ei.value.status == B.APMS_ESTATE
+    m_gathered = ost.m.copy()                                                        # what the gather makes of m
+    B.apms_topk_compress(run.ctx, run.m, gd1, run.werr, run.idx, run.val, K, 0.9)
+    torch.cuda.synchronize()
+    if implicit:
+        assert np.array_equal(host(run.m), m_start), "implicit momentum: the worker call must not write m"
+    else:
+        same(host(run.m), m_gathered, "m after the worker call that carried the gather out")
+    B.apms_topk_server_reduce(run.ctx, run.idx, run.val, K, run.serr, run.sidx, run.sval)
+    B.apms_topk_apply(run.ctx, run.sidx, run.sval, K, run.v, run.x, run.m, 1e-4, 1e-8)
+    ost.step_topk(g1, K, 0.9, 1e-4, 1e-8)
+    compare(run, ost, "second step", errors=mode)
+    run.finalize()                                                                   # the pending gather, from the list
+    torch.cuda.synchronize()
+    same(host(run.m), ost.m, "m after apms_finalize")
+    run.step(gd0, 0.9, 1e-4, 1e-8)                                                   # nothing pending in this form: the 1-bit path runs
     torch.cuda.synchronize()
     run.close()
 
