@@ -498,29 +498,37 @@ def test_topk_calls_need_reserved_scratch():
         B.apms_destroy(ctx)
 
 
-def test_topk_full_size_sampled_chunk():
+@pytest.mark.parametrize("deferred,steps", [(0, 1), (B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, 2)],
+                         ids=["eager", "defer-all"])
+def test_topk_full_size_sampled_chunk(deferred, steps):
     """BERT-Base-sized buffer (d_pad = 110 002 176, n = 8, chunk = d_pad / 8), K = 0.1 % of the chunk: the GPU
-    runs the whole step, the oracle follows the last chunk (chunks are independent) on the same bits."""
+    runs the whole step, the oracle follows the last chunk (chunks are independent) on the same bits.  With
+    everything deferred, two steps: the second reads the error buffers in deferred form and decodes the
+    server's list as its momentum, and apms_finalize then makes every buffer final."""
     wl = W.BERT_BASE
     d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
     K = L // 1000
     st = W.device_state(wl, DEV)
-    run = DeviceRun(d, n, L, DEV, state=st)
+    run = DeviceRun(d, n, L, DEV, deferred=deferred, state=st)
     del st
     k = C - 1
     sl = slice(k * L, (k + 1) * L)
     ost = oracle.State(L, n, L, run.x[sl].cpu().numpy(), run.m[:, sl].cpu().numpy(), run.v[sl].cpu().numpy())
     g = torch.empty(n, d, dtype=torch.float32, device=DEV)
-    W.device_grad_(wl, 0, g)
-    say("full size: GPU step, d=%d n=%d L=%d K=%d" % (d, n, L, K))
-    run.step_topk(g, K, wl.beta, wl.lr, wl.eps)
-    torch.cuda.synchronize()
-    say("full size: oracle on chunk %d (sorts %d x %d elements)" % (k, n + 1, L))
-    ost.step_topk(np.ascontiguousarray(g[:, sl].cpu().numpy()), K, wl.beta, wl.lr, wl.eps)
-    same(host(run.idx[:, k]), ost.idx[:, 0], "worker indices")
-    same(host(run.val[:, k]), ost.val[:, 0], "worker values")
-    same(host(run.sidx[k]), ost.sidx[0], "server indices")
-    same(host(run.sval[k]), ost.sval[0], "server values")
+    for step in range(steps):
+        W.device_grad_(wl, step, g)
+        say("full size: GPU step %d, d=%d n=%d L=%d K=%d mode %d" % (step, d, n, L, K, deferred))
+        run.step_topk(g, K, wl.beta, wl.lr, wl.eps)
+        torch.cuda.synchronize()
+        say("full size: oracle on chunk %d (sorts %d x %d elements)" % (k, n + 1, L))
+        ost.step_topk(np.ascontiguousarray(g[:, sl].cpu().numpy()), K, wl.beta, wl.lr, wl.eps)
+        same(host(run.idx[:, k]), ost.idx[:, 0], "worker indices, step %d" % step)
+        same(host(run.val[:, k]), ost.val[:, 0], "worker values, step %d" % step)
+        same(host(run.sidx[k]), ost.sidx[0], "server indices, step %d" % step)
+        same(host(run.sval[k]), ost.sval[0], "server values, step %d" % step)
+    if deferred:
+        run.finalize()
+        torch.cuda.synchronize()
     same(host(run.serr[sl]), ost.serr, "server_err")
     for i in (0, n - 1):
         same(host(run.werr[i, sl]), ost.werr[i], "worker_err[%d]" % i)
