@@ -672,20 +672,16 @@ __device__ __forceinline__ void hist_tile(const float* __restrict__ buf, uint32_
 // The kernels for the rare cases (ties to break, pairs that overflowed their slots) run on a small grid in
 // which every workgroup visits the flagged pairs and strides over their tiles.  The flags are read kThreads
 // pairs at a time, one per thread, so a launch with nothing to do costs one state read per thread.  A pair
-// is flagged if both state words named are non-zero (name one word twice to test it alone) and, if
-// `zero_word` names one, that word is zero.
+// is flagged if both state words named are non-zero (name one word twice to test it alone).
 // `body(pair)` may contain workgroup barriers: all threads see the same flags.
 template <class Body>
 __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ state, int64_t pairs, int flag_word,
-                                                  int second_flag_word, int zero_word, Body body) {
+                                                  int second_flag_word, Body body) {
     __shared__ uint32_t flags[kThreads];
     for (int64_t p0 = 0; p0 < pairs; p0 += kThreads) {
         const int64_t p = p0 + threadIdx.x;
-        uint32_t mine = 0u;
-        if (p < pairs) {
-            const uint32_t* st = state + p * kTopkStateWords;
-            mine = (st[flag_word] != 0u && st[second_flag_word] != 0u && (zero_word < 0 || st[zero_word] == 0u)) ? 1u : 0u;
-        }
+        const uint32_t mine = (p < pairs && state[p * kTopkStateWords + flag_word] != 0u &&
+                               state[p * kTopkStateWords + second_flag_word] != 0u) ? 1u : 0u;
         if (!__syncthreads_or(mine != 0u)) continue;           // same answer in every thread
         flags[threadIdx.x] = mine;
         __syncthreads();
@@ -693,11 +689,6 @@ __device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ s
             if (flags[q] != 0u) body(p0 + q);
         __syncthreads();                                       // before the next round overwrites the flags
     }
-}
-template <class Body>
-__device__ __forceinline__ void for_flagged_pairs(const uint32_t* __restrict__ state, int64_t pairs, int flag_word,
-                                                  int second_flag_word, Body body) {
-    for_flagged_pairs(state, pairs, flag_word, second_flag_word, -1, body);
 }
 
 // The whole level-0 histogram of the pairs marked kStRehist (their first pass counted only the bins at or
