@@ -400,7 +400,7 @@ def main():
     log("workload %s: d_pad=%d n=%d chunk=%d (%d chunks), %s gradients, mode=%s" %
         (wl.name, d, n, L, wl.C, wl.grad, args.mode))
 
-    placeable = (args.algo == "momentum" and args.mode == "deferred" and args.grad_dtype == "f32"
+    placeable = (args.algo in ("momentum", "topk") and args.mode == "deferred" and args.grad_dtype == "f32"
                  and 4 * n * d >= (4 << 30))
     packed = None
     if args.placement == "both" and placeable:
