@@ -83,6 +83,7 @@ CASES = [
     (3, 4096 * 5 + 96, 3, 207),       # ragged last tile
     (4, 65536, 2, 655),               # 1 %
     (16, 4096 * 3 + 1024, 2, 13),
+    (70, 4096 * 2 + 96, 1, 30),       # more workers than one batch of the server's decode takes
     (2, 65536, 2, 6554),              # 10 %: many candidates per tile, still inside the slots
     (2, 65536 + 4096 + 64, 2, 34848), # half of everything: the threshold sits where the key bins are fullest
 ]
