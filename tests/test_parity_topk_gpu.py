@@ -499,15 +499,18 @@ def test_topk_calls_need_reserved_scratch():
         B.apms_destroy(ctx)
 
 
-@pytest.mark.parametrize("deferred,steps", [(0, 1), (B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, 2)],
+@pytest.mark.parametrize("deferred,steps,chunks", [(0, 1, 8), (B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER, 2, 64)],
                          ids=["eager", "defer-all"])
-def test_topk_full_size_sampled_chunk(deferred, steps):
-    """BERT-Base-sized buffer (d_pad = 110 002 176, n = 8, chunk = d_pad / 8), K = 0.1 % of the chunk: the GPU
-    runs the whole step, the oracle follows the last chunk (chunks are independent) on the same bits.  With
-    everything deferred, two steps: the second reads the error buffers in deferred form and decodes the
-    server's list as its momentum, and apms_finalize then makes every buffer final."""
-    wl = W.BERT_BASE
+def test_topk_full_size_sampled_chunk(deferred, steps, chunks):
+    """BERT-Base-sized buffer (d_pad = 110 002 176, n = 8), K = 0.1 % of the chunk: the GPU runs the whole step,
+    the oracle follows the last chunk (chunks are independent) on the same bits.  Eager: chunks of d_pad / 8, as
+    the configuration has them.  With everything deferred, two steps on 64 chunks of d_pad / 64 (ragged tiles;
+    the oracle's sorts are what this test's time goes into): the second step reads the error buffers in deferred
+    form and decodes the server's list as its momentum, and apms_finalize then makes every buffer final."""
+    import dataclasses
+    wl = dataclasses.replace(W.BERT_BASE, chunk=W.BERT_BASE.d_pad // chunks)
     d, n, L, C = wl.d_pad, wl.n, wl.L, wl.C
+    assert C == chunks and L % 32 == 0
     K = L // 1000
     st = W.device_state(wl, DEV)
     run = DeviceRun(d, n, L, DEV, deferred=deferred, state=st)
