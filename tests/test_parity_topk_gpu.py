@@ -458,6 +458,48 @@ def test_topk_deferred_gather_state_machine(implicit):
     run.close()
 
 
+def test_topk_hip_graph_replay_matches_eager():
+    """The top-k step allocates nothing once its scratch is reserved, never synchronises and records no memset: a
+    steady-state step (errors and gather pending) captured in a HIP graph replays to the bits of the eager path,
+    with fresh gradients in the same buffer and unrelated eager work between the replays."""
+    n, L, C, K = 3, 4096 * 6 + 320, 2, 120
+    d = L * C
+    wl = W.Workload("topk-graph", 2, d=d, n=n, chunk=L)
+    st = W.host_state(wl)
+    mode = B.APMS_DEFER_ERRORS | B.APMS_DEFER_GATHER
+    runs = [make(d, n, L, st, mode)[0] for _ in range(2)]
+    graphed, eager = runs
+    gd = torch.empty(n, d, dtype=torch.float32, device=DEV)
+    for step in range(2):                       # reach the steady state (and reserve the scratch)
+        gd.copy_(torch.from_numpy(W.host_grad(wl, step)))
+        for r in runs:
+            r.step_topk(gd, K, 0.9, 1e-3, 1e-8)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    with torch.cuda.graph(graph, stream=side):
+        graphed.step_topk(gd, K, 0.9, 1e-3, 1e-8)
+    torch.cuda.synchronize()
+    scratch = torch.empty(1 << 20, device=DEV)
+    for step in range(2, 7):
+        say("top-k graph replay for step %d" % step)
+        gd.copy_(torch.from_numpy(W.host_grad(wl, step)))
+        torch.cuda.synchronize()
+        graph.replay()
+        scratch.normal_()                       # unrelated eager work between replays
+        eager.step_topk(gd, K, 0.9, 1e-3, 1e-8)
+        torch.cuda.synchronize()
+        for name in ("idx", "val", "sidx", "sval", "x"):
+            assert torch.equal(getattr(graphed, name), getattr(eager, name)), "replay of step %d: %s" % (step, name)
+    for r in runs:
+        r.finalize()
+    torch.cuda.synchronize()
+    for name in ("m", "werr", "serr"):
+        assert torch.equal(getattr(graphed, name), getattr(eager, name)), name
+    for r in runs:
+        r.close()
+
+
 def test_topk_calls_need_reserved_scratch():
     """The compute calls allocate nothing: without apms_topk_reserve, or with a K beyond what was reserved,
     they answer ESTATE and queue nothing; after reserving they run."""
