@@ -3,8 +3,9 @@
 // error-compensated worker / server / gather structure as the 1-bit path.
 //
 // Selection is exact and deterministic: a 3-level radix select on the 31 magnitude bits finds the K-th
-// largest key T of a chunk; if more elements equal T than may be kept, a second 3-level radix select on the
-// element index finds the last tie to keep.  Kept elements are then emitted in index order.
+// largest key T of a chunk; if more elements equal T than may be kept, the lower indices are (found from a
+// short list of the elements next to T, or by a second radix select on the element index).  Kept elements
+// are then emitted in index order.
 //
 // Passes over the dense buffer: the one that forms u (worker) or ubar (server).  It works on a guess of the
 // threshold (the previous call's, less a margin of 3 to 6 %): every element at or above that floor is

@@ -5,20 +5,22 @@
 // Exact selection without sorting: the magnitude key of a value is its binary32 pattern without the sign
 // bit, which orders like |u|.  A 3-level radix select (11 + 11 + 9 bits) over per-chunk histograms finds
 // the K-th largest key T and how many elements equal to T may still be kept; only if that is fewer than
-// there are, a second 3-level radix select (11 + 11 + 10 bits) over the chunk-local index finds the last
-// such element to keep.  Histograms use integer atomics (order-independent), the emission order comes from
-// per-tile counts and a scan, so the result does not depend on scheduling.
+// there are, the index rule picks the last such element to keep: from the short list of elements that share
+// T's leading 22 bits (topk_resolve_kernel), or, where that list or a tile's slots overflow, by a second
+// 3-level radix select (11 + 11 + 10 bits) over the chunk-local index.  Histograms use integer atomics
+// (order-independent), the emission order comes from per-tile counts and a scan, so the result does not
+// depend on scheduling.
 //
 // Only the level-0 histogram needs every element, and only if nothing is known: the first pass histograms
 // the elements whose key is at or above a guessed floor (the previous call's threshold key less a margin) and
 // leaves the rest uncounted, so that the few populated exponent bins of ordinary data do not serialise on LDS
 // atomics; if it counted fewer than K elements the threshold lies below the floor, and one more pass over the
-// buffer builds the whole level-0 histogram for that chunk.  What the later steps need are the elements at or above
-// the level-0 bin of T (kept whatever T turns out to be if above, candidates if inside: under 2 % of a tile
-// when K is 1 % of a chunk).  They are copied to per-tile slots - by the worker's first pass itself, on the
-// previous call's bin, else by one more pass once the bin is known - and key levels 1 and 2, the tie
-// levels, the per-tile kept counts and the emission work on the slots alone.  A chunk with a tile that has
-// more such elements than slots is flagged and takes full passes over the buffer instead.
+// buffer builds the whole level-0 histogram for that chunk.  What the later steps need are the elements at or
+// above the level-0 bin of T (kept whatever T turns out to be if above, candidates if inside).  They are
+// copied to per-tile slots - by the first pass itself, on its floor (about 1.5 % of a tile when K is 1 % of a
+// chunk), else by one more pass once the bin is known - and key levels 1 and 2, the tie rule, the per-tile
+// kept counts and the emission work on the slots alone.  A chunk with a tile that has more such elements
+// than slots is flagged and takes full passes over the buffer instead.
 //
 // Built with -ffp-contract=off: the elementwise arithmetic is that of the 1-bit path.
 
