@@ -176,7 +176,7 @@ void clear_pending_gather(apms_ctx* c) {
 }
 
 void free_topk_scratch(apms_ctx* c) {
-    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.keep, c->topk.near, c->topk.gather_offsets,
+    void* arrays[] = {c->topk.hist, c->topk.state, c->topk.guess, c->topk.last_T, c->topk.keep, c->topk.near, c->topk.gather_offsets,
                       c->topk.tile_counts, c->topk.tile_split, c->topk.slots};
     for (void* a : arrays)
         if (a) (void)hipFree(a);
@@ -191,7 +191,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     const int64_t pairs = static_cast<int64_t>(c->n) * c->C;
     const int64_t tiles = pairs * apms::tiles_per_chunk(geometry(c), apms::kTopkTile);
     const int64_t guesses = pairs + c->C;                     // the worker call's pairs, then the server call's chunks
-    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords + 2 * apms::kTopkNearCap) + 3 * guesses) * 4 +
+    const int64_t fixed = (pairs * (apms::kTopkBins + apms::kTopkStateWords + 2 * apms::kTopkNearCap) + 4 * guesses) * 4 +
                           2 * tiles * 4 + tiles / c->n * 4;
     const int32_t want = apms::topk_slots_for(K_max, c->L);
     if (c->topk.slots && c->topk.slots_per_tile >= want) return hipSuccess;
@@ -201,6 +201,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
         e = hipMalloc(reinterpret_cast<void**>(&c->topk.hist), pairs * apms::kTopkBins * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.state), pairs * apms::kTopkStateWords * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.guess), guesses * 4);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.last_T), guesses * 4);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.keep), guesses * 8);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.near), pairs * apms::kTopkNearCap * 8);
         if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void**>(&c->topk.gather_offsets), tiles / c->n * 4);
@@ -227,6 +228,7 @@ hipError_t reserve_topk_scratch(apms_ctx* c, int64_t K_max) {
     }
     // no guess to go by: the slots' size decides how low a guess may be without overflowing them
     e = hipMemset(c->topk.guess, 0xFF, guesses * 4);
+    if (e == hipSuccess) e = hipMemset(c->topk.last_T, 0xFF, guesses * 4);
     if (e == hipSuccess) e = hipDeviceSynchronize();           // the fill is on the null stream: done before any caller stream goes on
     if (e != hipSuccess) return e;
     c->topk.slots_per_tile = want;

@@ -8,9 +8,9 @@
 // are then emitted in index order.
 //
 // Passes over the dense buffer: the one that forms u (worker) or ubar (server).  It works on a guess of the
-// threshold (the previous call's, less a margin of 3 to 6 %): every element at or above that floor is
-// counted in the level-0 histogram and copied to the tile's slots (about 1.5 % of a tile when K is 1 % of a
-// chunk); the rest is neither counted nor copied.  Where the guess proves too high (always in a context's
+// threshold (the previous call's, less a margin of 0.2 to 6 % that follows how far the threshold moves):
+// every element at or above that floor is counted in the level-0 histogram and copied to the tile's slots
+// (1.1 to 1.5 % of a tile when K is 1 % of a chunk); the rest is neither counted nor copied.  Where the guess proves too high (always in a context's
 // first call) one more pass builds the whole histogram and another re-fills the slots from the bin then
 // known.  Key levels 1 and 2, the tie rule, the per-tile counts and the emission work on the slots alone.
 // A chunk with a tile that has more such elements than slots (constant or heavily tied data, or a K far
@@ -51,6 +51,7 @@ inline int32_t topk_slots_for(int64_t K, int64_t L) {
 //   guess       [pairs + C] u32          the floor of the first pass (the previous call's threshold key less a
 //                                        margin): the worker call's n * C entries, then the server call's C;
 //                                        0xFFFFFFFF in a new context and whenever the slots are re-allocated
+//   last_T      [pairs + C] u32          that threshold key itself (the margin follows how far it moves), same layout
 //   near        [pairs][kTopkNearCap] uint2   the slot entries that share the top 22 key bits of the pair's threshold:
 //                                        (chunk-local index, key), in no particular order
 //   gather_offsets [C][tiles] u32        tile offsets of the server's list while its gather is pending on m
@@ -60,6 +61,7 @@ struct TopkScratch {
     uint32_t* hist;
     uint32_t* state;
     uint32_t* guess;
+    uint32_t* last_T;
     uint2* keep;
     uint2* near;
     uint32_t* gather_offsets;

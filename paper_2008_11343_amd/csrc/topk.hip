@@ -49,10 +49,18 @@ enum : int {
     kStTieDone = 13,      // 1 if kStIdxT and the per-tile counts were settled from the near list
 };
 
-// The floor of the next call's first pass (guess[pair]) lies this far below the threshold key found: half a
-// level-0 bin, 3 to 6 % in magnitude.  With K at 1 % of a chunk of normal data about 1.5 % of the elements
-// pass it.  With no earlier call to go by the table holds 0xFFFFFFFF, a floor that no key reaches.
-constexpr uint32_t kGuessMargin = 1u << 19;
+// The floor of the next call's first pass (guess[pair]) lies a margin below the threshold key found.  Only a
+// threshold that FALLS below the floor costs extra passes, so the margin follows how far it fell since the
+// call before (last_T[pair] remembers it): eight times that, at least half the previous margin (it shrinks
+// over a few calls while the threshold rises or stands still), between 2^15 (0.2 to 0.4 % in magnitude) and
+// half a level-0 bin (2^19: 3 to 6 %); half a bin when there is no history or this call's floor proved too
+// high.  The tighter the floor, the fewer elements the first pass copies to the slots and the later passes
+// read: with K at 1 % of a chunk of normal data 1.5 % of the elements pass a floor half a bin down, 1.1 % one
+// at 2^16, and the worker call is 4 % faster.  With no earlier call to go by the tables hold 0xFFFFFFFF, a
+// floor that no key reaches.
+constexpr uint32_t kGuessMarginMax = 1u << 19;
+constexpr uint32_t kGuessMarginMin = 1u << 15;
+constexpr uint32_t kGuessMarginPerFall = 8u;
 
 constexpr uint32_t kTopMask = 0x7FF00000u;      // the level-0 digit of a key
 
@@ -261,7 +269,7 @@ __device__ __forceinline__ uint32_t count_and_slot_marked(const float* tile_valu
 // ------------------------------------------------------------------------
 // Worker: u into the error buffer + level-0 key histogram (Algorithm 1 lines 6-7).
 // ------------------------------------------------------------------------
-// The threshold hardly moves from one step to the next, so the pass works on a guess: a floor kGuessMargin
+// The threshold hardly moves from one step to the next, so the pass works on a guess: a floor a margin
 // below the previous call's threshold key (guess[pair]; 0xFFFFFFFF before the first call).  Elements at or above
 // the floor are histogrammed and copied to the slots, the others are left alone.  The guess is good if at
 // least K elements passed it: the K-th largest key is then among them, histogram and slots hold a superset
@@ -567,11 +575,11 @@ __global__ __launch_bounds__(kThreads) void topk_server_u_kernel(const uint32_t*
 // histogram for the next level.
 // only_rehist: the second level-0 pick of a call, for the pairs whose first histogram fell short (kStRehist:
 // the floor they were counted and slotted on was too high, so their slots are filled again).
-// At key level 2 with a guess table: leaves the floor of the next call's first pass (see topk_worker_u_kernel).
+// At key level 2 with a guess table: leaves the floor of the next call's first pass (see kGuessMarginMax).
 template <bool kIdx>
 __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restrict__ hist, uint32_t* __restrict__ state,
                                                              int level, uint32_t K, uint32_t* __restrict__ guess,
-                                                             bool only_rehist) {
+                                                             uint32_t* __restrict__ last_T, bool only_rehist) {
     __shared__ uint32_t lds[kWaves];
     const int64_t pair = blockIdx.x;
     uint32_t* h = hist + pair * kTopkBins;
@@ -628,7 +636,18 @@ __global__ __launch_bounds__(kThreads) void topk_pick_kernel(uint32_t* __restric
                     st[kStRemaining] = left;
                     if (level == 0 && only_rehist) st[kStResplit] = 1u;
                     if (level == 2) {
-                        if (guess) guess[pair] = new_prefix > kGuessMargin ? new_prefix - kGuessMargin : 0u;
+                        if (guess) {
+                            const uint32_t before = last_T[pair], floor_before = guess[pair];   // 0xFFFFFFFF: no call before
+                            uint32_t margin = kGuessMarginMax;
+                            if (before != 0xFFFFFFFFu && floor_before <= before && st[kStRehist] == 0u) {
+                                const uint32_t fell = before > new_prefix ? before - new_prefix : 0u;
+                                const uint32_t wanted = fell < kGuessMarginMax / kGuessMarginPerFall ? kGuessMarginPerFall * fell
+                                                                                                     : kGuessMarginMax;
+                                margin = min(kGuessMarginMax, max(kGuessMarginMin, max(wanted, (before - floor_before) / 2u)));
+                            }
+                            guess[pair] = new_prefix > margin ? new_prefix - margin : 0u;
+                            last_T[pair] = new_prefix;
+                        }
                         st[kStKeyT] = new_prefix;
                         st[kStCountEq] = cnt[q];
                         st[kStTieNeeded] = (left < cnt[q]) ? 1u : 0u;
@@ -1331,11 +1350,12 @@ __global__ __launch_bounds__(kThreads) void topk_begin_kernel(uint32_t* __restri
     } while (0)
 
 // The selection + emission over `slices` x C pairs of `buf` ([slices][d]) whose level-0 histogram is filled.
-// `guess`: the per-pair table the first pass counted and filled the slots on (see topk_worker_u_kernel).
+// `guess`, `last_T`: the per-pair tables of the first pass's floor and of the threshold found (see kGuessMarginMax).
 // `save_keep`: null = eager (the kept positions of buf are zeroed); else the call leaves buf in deferred form
 // and {T, idxT} of every pair go there.
 hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float* buf, uint32_t* idx, float* val,
-                           uint32_t* guess, uint2* save_keep, const TopkScratch& s, hipStream_t stream) {
+                           uint32_t* guess, uint32_t* last_T, uint2* save_keep, const TopkScratch& s,
+                           hipStream_t stream) {
     const int64_t pairs = static_cast<int64_t>(slices) * geo.C;
     const int32_t tpc = static_cast<int32_t>(tiles_per_chunk(geo, kTopkTile));
     const dim3 per_pair(static_cast<uint32_t>(pairs)), block(kThreads);
@@ -1366,7 +1386,7 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
             APMS_RETURN_IF_ERROR();
         }
         hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                           level == 2 ? guess : static_cast<uint32_t*>(nullptr), false);
+                           level == 2 ? guess : static_cast<uint32_t*>(nullptr), last_T, false);
         APMS_RETURN_IF_ERROR();
         if (level == 0) {
             // pairs whose first pass did not count down to the threshold bin: full histogram, pick again
@@ -1374,7 +1394,7 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                                pairs, tpc);
             APMS_RETURN_IF_ERROR();
             hipLaunchKernelGGL(topk_pick_kernel<false>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                               static_cast<uint32_t*>(nullptr), true);
+                               static_cast<uint32_t*>(nullptr), last_T, true);
             APMS_RETURN_IF_ERROR();
         }
     }
@@ -1388,7 +1408,7 @@ hipError_t select_and_emit(const Geometry& geo, int32_t slices, int64_t K, float
                            geo.C, pairs, tpc, level);
         APMS_RETURN_IF_ERROR();
         hipLaunchKernelGGL(topk_pick_kernel<true>, per_pair, block, 0, stream, s.hist, s.state, level, K32,
-                           static_cast<uint32_t*>(nullptr), false);
+                           static_cast<uint32_t*>(nullptr), static_cast<uint32_t*>(nullptr), false);
         APMS_RETURN_IF_ERROR();
     }
     hipLaunchKernelGGL(topk_slot_count_kernel, emit_grid, block, 0, stream, s.slots, s.slots_per_tile, s.tile_split,
@@ -1463,7 +1483,8 @@ hipError_t launch_topk_compress(const Geometry& geo, int64_t K, float* m, const 
                            prev_keep, static_cast<const uint32_t*>(nullptr), static_cast<const float*>(nullptr),
                            static_cast<const uint32_t*>(nullptr), 0, geo.d, geo.L, geo.C, tpc, beta, one_minus_beta);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, defer ? scratch.keep : nullptr, scratch, stream);
+    return select_and_emit(geo, geo.n, K, werr, idx, val, scratch.guess, scratch.last_T, defer ? scratch.keep : nullptr, scratch,
+                           stream);
 }
 
 hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint32_t* idx, const float* val,
@@ -1488,7 +1509,8 @@ hipError_t launch_topk_server_reduce(const Geometry& geo, int64_t K, const uint3
                        serr_pending ? server_keep : static_cast<const uint2*>(nullptr), geo.d, geo.L, geo.C, geo.n,
                        static_cast<int32_t>(K), tpc, workers_per_batch, inv_n);
     APMS_RETURN_IF_ERROR();
-    return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, defer ? server_keep : nullptr, scratch, stream);
+    return select_and_emit(geo, 1, K, serr, sidx, sval, server_guess, scratch.last_T + static_cast<int64_t>(geo.n) * geo.C,
+                           defer ? server_keep : nullptr, scratch, stream);
 }
 
 hipError_t launch_topk_finalize(const Geometry& geo, bool server, float* err, const TopkScratch& scratch,
